@@ -1,0 +1,227 @@
+"""Pins for the oracle's whole training step: finite differences, an independently written torch
+autograd model, accumulation equality, padding invariance, loss-scale invariance, parameter count."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import nmt_inputs as I
+from oracle import nmt_oracle as O
+
+SMALL = dict(enc_layers=2, dec_layers=2, d_model=16, n_heads=2, d_ff=32, vocab=40)
+
+
+def _setup(dropout=0.0, act_dropout=0.0, seed=0, B=4, S=7, T=6, model=SMALL):
+    cfg = O.Config(**{k: model[k] for k in ("enc_layers", "dec_layers", "d_model", "n_heads", "d_ff", "vocab")},
+                   dropout=dropout, act_dropout=act_dropout, seed=11)
+    W = I.init_weights(seed=seed, perturb=0.3, **model)
+    P = {k: v.astype(np.float64) for k, v in W.items()}
+    batch = I.tiny_batch(seed=5, B=B, S=S, T=T, vocab=model["vocab"], short_rows=2, short_by=3)
+    return cfg, P, batch
+
+
+def test_parameter_counts_match_the_paper():
+    # the paper states 210M parameters for the 32K-vocabulary big model
+    assert I.param_count(**I.MODELS["big"]) == 209_911_808
+    assert round(I.param_count(**I.MODELS["big"]) / 1e6) == 210
+    assert I.param_count(**I.MODELS["big40k"]) == 217_317_376
+    assert I.param_count(**I.MODELS["tiny"]) == 297_472
+    assert I.param_count(**I.MODELS["base"]) == 60_915_712
+
+
+@pytest.mark.parametrize("dropout,act_dropout", [(0.0, 0.0), (0.25, 0.2)])
+def test_gradient_matches_central_finite_differences(dropout, act_dropout):
+    cfg, P, batch = _setup(dropout, act_dropout)
+    loss, ntok, cache = O.forward_loss(P, cfg, **batch, step=3, micro=1)
+    G = O.backward(P, cfg, cache, loss_scale=1.0)
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    worst = 0.0
+    for name in P:
+        flat = P[name].reshape(-1)
+        g = G[name].reshape(-1)
+        idx = rng.choice(flat.size, size=min(6, flat.size), replace=False)
+        if name == "embed":   # make sure rows used by source, target and output are probed
+            d = cfg.d_model
+            idx = np.concatenate([idx, [batch["src"][0, 0] * d + 1, batch["tgt_in"][0, 1] * d + 2,
+                                        batch["tgt_out"][1, 0] * d + 3, I.PAD * d, I.BOS * d + 5]])
+        for i in idx:
+            old = flat[i]
+            flat[i] = old + h
+            lp, _, _ = O.forward_loss(P, cfg, **batch, step=3, micro=1)
+            flat[i] = old - h
+            lm, _, _ = O.forward_loss(P, cfg, **batch, step=3, micro=1)
+            flat[i] = old
+            fd = (lp - lm) / (2 * h)
+            err = abs(fd - g[i]) / max(1e-3, abs(fd), abs(g[i]))
+            worst = max(worst, err)
+            assert err < 1e-6, (name, i, fd, g[i])
+    assert worst < 1e-6
+
+
+# ---- an independent model written with torch library ops and differentiated by autograd --------
+def _torch_model(Pt, cfg, batch, keeps, p_res, p_act):
+    src, tgt_in, tgt_out = (torch.tensor(batch[k], dtype=torch.long) for k in ("src", "tgt_in", "tgt_out"))
+    B, S = src.shape
+    T = tgt_in.shape[1]
+    d, h = cfg.d_model, cfg.n_heads
+
+    def pe(n):
+        pos = torch.arange(n, dtype=torch.float64)[:, None]
+        div = torch.exp(torch.arange(0, d, 2, dtype=torch.float64) * (-math.log(10000.0) / d))
+        out = torch.zeros(n, d, dtype=torch.float64)
+        out[:, 0::2] = torch.sin(pos * div)
+        out[:, 1::2] = torch.cos(pos * div)
+        return out
+
+    def drop(x, key, p):
+        if p <= 0:
+            return x
+        return x * torch.tensor(keeps[key].reshape(x.shape), dtype=torch.float64) / (1.0 - float(np.float32(p)))
+
+    def mha(xq, xkv, wq, bq, wk, bk, wv, bv, wo, bo, allow):
+        q = F.linear(xq, wq, bq).view(B, -1, h, d // h).transpose(1, 2)
+        k = F.linear(xkv, wk, bk).view(B, -1, h, d // h).transpose(1, 2)
+        v = F.linear(xkv, wv, bv).view(B, -1, h, d // h).transpose(1, 2)
+        o = F.scaled_dot_product_attention(q, k, v, attn_mask=allow[:, None])
+        return F.linear(o.transpose(1, 2).reshape(B, -1, d), wo, bo)
+
+    def ln(x, pre):
+        return F.layer_norm(x, (d,), Pt[pre + "g"], Pt[pre + "b"], cfg.ln_eps)
+
+    def ffn(x, pre, key):
+        hid = drop(F.relu(F.linear(x, Pt[pre + "w1"], Pt[pre + "b1"])), key, p_act)
+        return F.linear(hid, Pt[pre + "w2"], Pt[pre + "b2"])
+
+    E = Pt["embed"]
+    src_ok = (src != cfg.pad_id)
+    x = drop(math.sqrt(d) * F.embedding(src, E) + pe(S)[None], "emb_src", p_res)
+    for l in range(cfg.enc_layers):
+        pre = f"enc{l}."
+        w, b = Pt[pre + "attn.wqkv"], Pt[pre + "attn.bqkv"]
+        a = mha(x, x, w[:d], b[:d], w[d:2 * d], b[d:2 * d], w[2 * d:], b[2 * d:], Pt[pre + "attn.wo"],
+                Pt[pre + "attn.bo"], src_ok[:, None, :].expand(B, S, S))
+        x = ln(x + drop(a, f"enc{l}.1", p_res), pre + "ln1.")
+        x = ln(x + drop(ffn(x, pre + "ffn.", f"enc{l}.act"), f"enc{l}.2", p_res), pre + "ln2.")
+    enc = x
+    tgt_ok = (tgt_in != cfg.pad_id)
+    causal = torch.tril(torch.ones(T, T, dtype=torch.bool))
+    y = drop(math.sqrt(d) * F.embedding(tgt_in, E) + pe(T)[None], "emb_tgt", p_res)
+    for l in range(cfg.dec_layers):
+        pre = f"dec{l}."
+        w, b = Pt[pre + "self.wqkv"], Pt[pre + "self.bqkv"]
+        a = mha(y, y, w[:d], b[:d], w[d:2 * d], b[d:2 * d], w[2 * d:], b[2 * d:], Pt[pre + "self.wo"],
+                Pt[pre + "self.bo"], causal[None] & tgt_ok[:, None, :])
+        y = ln(y + drop(a, f"dec{l}.1", p_res), pre + "ln1.")
+        w, b = Pt[pre + "cross.wkv"], Pt[pre + "cross.bkv"]
+        a = mha(y, enc, Pt[pre + "cross.wq"], Pt[pre + "cross.bq"], w[:d], b[:d], w[d:], b[d:],
+                Pt[pre + "cross.wo"], Pt[pre + "cross.bo"], src_ok[:, None, :].expand(B, T, S))
+        y = ln(y + drop(a, f"dec{l}.2", p_res), pre + "ln2.")
+        y = ln(y + drop(ffn(y, pre + "ffn.", f"dec{l}.act"), f"dec{l}.3", p_res), pre + "ln3.")
+    logits = F.linear(y, E)
+    return F.cross_entropy(logits.view(B * T, -1), tgt_out.view(-1), ignore_index=cfg.pad_id, reduction="sum",
+                           label_smoothing=cfg.label_smoothing)
+
+
+@pytest.mark.parametrize("dropout,act_dropout", [(0.0, 0.0), (0.3, 0.1)])
+def test_loss_and_gradient_match_independent_torch_autograd(dropout, act_dropout):
+    model = dict(enc_layers=2, dec_layers=2, d_model=32, n_heads=4, d_ff=64, vocab=120)
+    cfg, P, batch = _setup(dropout, act_dropout, B=5, S=9, T=8, model=model)
+    loss, ntok, cache = O.forward_loss(P, cfg, **batch, step=2, micro=0)
+    G = O.backward(P, cfg, cache, loss_scale=1.0)
+    keeps = {"emb_src": cache["keep_emb_src"], "emb_tgt": cache["keep_emb_tgt"]}
+    for l, c in enumerate(cache["enc"]):
+        keeps.update({f"enc{l}.1": c["keep1"], f"enc{l}.2": c["keep2"], f"enc{l}.act": c["keep_act"]})
+    for l, c in enumerate(cache["dec"]):
+        keeps.update({f"dec{l}.1": c["keep1"], f"dec{l}.2": c["keep2"], f"dec{l}.3": c["keep3"],
+                      f"dec{l}.act": c["keep_act"]})
+    Pt = {k: torch.tensor(v, requires_grad=True) for k, v in P.items()}
+    ref = _torch_model(Pt, cfg, batch, keeps, cache["p_res"], cache["p_act"])
+    ref.backward()
+    assert abs(loss - ref.item()) / abs(ref.item()) < 1e-12
+    assert ntok == int((batch["tgt_out"] != cfg.pad_id).sum())
+    for k in P:
+        g_ref = Pt[k].grad.numpy()
+        denom = max(np.linalg.norm(g_ref), 1e-9)
+        assert np.linalg.norm(G[k] - g_ref) / denom < 1e-10, k
+
+
+def test_accumulated_micro_batches_equal_one_big_batch():
+    """Accumulating k sub-batches before the update equals one k-times larger batch."""
+    cfg, P, batch = _setup(dropout=0.2, act_dropout=0.1, B=8, S=9, T=8)
+    uid = np.arange(100, 108)
+    loss, ntok, cache = O.forward_loss(P, cfg, **batch, step=5, micro=0, sent_uid=uid)
+    G = O.backward(P, cfg, cache, 64.0)
+    for cut in (4, 2):
+        parts = []
+        for sl in (slice(0, cut), slice(cut, 8)):
+            sub = {k: v[sl] for k, v in batch.items()}
+            # drop all-padding trailing columns so the two parts are padded differently
+            keep_s = int((sub["src"] != cfg.pad_id).sum(1).max())
+            keep_t = int((sub["tgt_out"] != cfg.pad_id).sum(1).max())
+            sub = {"src": sub["src"][:, :keep_s], "tgt_in": sub["tgt_in"][:, :keep_t], "tgt_out": sub["tgt_out"][:, :keep_t]}
+            parts.append((sub, uid[sl]))
+        acc, ltot, ntot = None, 0.0, 0
+        for j, (sub, u) in enumerate(parts):
+            l, n, c = O.forward_loss(P, cfg, **sub, step=5, micro=0, sent_uid=u)
+            acc = O.accumulate(acc, O.backward(P, cfg, c, 64.0), j == 0)
+            ltot, ntot = ltot + l, ntot + n
+        assert ntot == ntok
+        assert abs(ltot - loss) / loss < 1e-12
+        for k in G:
+            assert np.linalg.norm(acc[k] - G[k]) <= 1e-12 * max(np.linalg.norm(G[k]), 1e-30), k
+
+
+def test_extra_padding_columns_change_nothing():
+    cfg, P, batch = _setup(dropout=0.2, B=4, S=7, T=6)
+    loss, ntok, cache = O.forward_loss(P, cfg, **batch, step=1)
+    G = O.backward(P, cfg, cache, 1.0)
+    padded = {k: np.concatenate([v, np.full((v.shape[0], 3), cfg.pad_id, dtype=v.dtype)], axis=1) for k, v in batch.items()}
+    loss2, ntok2, cache2 = O.forward_loss(P, cfg, **padded, step=1)
+    G2 = O.backward(P, cfg, cache2, 1.0)
+    assert ntok2 == ntok and abs(loss2 - loss) / loss < 1e-13
+    for k in G:
+        assert np.linalg.norm(G2[k] - G[k]) <= 1e-12 * max(np.linalg.norm(G[k]), 1e-30), k
+
+
+def test_unscaled_gradient_does_not_depend_on_the_loss_scale():
+    cfg, P, batch = _setup(dropout=0.1)
+    _, _, cache = O.forward_loss(P, cfg, **batch, step=1)
+    base = O.backward(P, cfg, cache, 1.0)
+    for S_loss in (128.0, 2.0 ** 15):
+        G = O.backward(P, cfg, cache, S_loss)
+        for k in G:
+            assert (G[k] / S_loss == base[k]).all(), k         # power-of-two scaling is exact
+
+
+def test_key_bias_gradient_vanishes():
+    # adding a constant to every key score of a query leaves the softmax unchanged
+    cfg, P, batch = _setup(dropout=0.0)
+    _, _, cache = O.forward_loss(P, cfg, **batch)
+    G = O.backward(P, cfg, cache, 1.0)
+    d = cfg.d_model
+    scale = np.abs(G["enc0.attn.bqkv"][:d]).max()
+    assert np.abs(G["enc0.attn.bqkv"][d:2 * d]).max() < 1e-12 * max(scale, 1.0)
+
+
+def test_update_skips_on_forced_overflow_and_applies_otherwise():
+    cfg, P, batch = _setup(dropout=0.1)
+    master = {k: v.copy() for k, v in P.items()}
+    m = {k: np.zeros_like(v) for k, v in P.items()}
+    v = {k: np.zeros_like(val) for k, val in P.items()}
+    scaler = O.LossScaler(128.0)
+    snap = {k: a.copy() for k, a in master.items()}
+    out = O.train_update(P, master, m, v, cfg, [batch], scaler, t=1, lr=5e-4, scale_override=128.0 * 2 ** 20)
+    assert out["flag"] == 1 and scaler.scale == 64.0 and scaler.clean == 0
+    assert all((master[k] == snap[k]).all() for k in master)
+    assert all((m[k] == 0).all() and (v[k] == 0).all() for k in m)
+    out = O.train_update(P, master, m, v, cfg, [batch], scaler, t=1, lr=5e-4)
+    assert out["flag"] == 0 and scaler.clean == 1 and scaler.scale == 64.0
+    moved = sum(float(np.abs(master[k] - snap[k]).sum()) for k in master)
+    assert moved > 0
+    # first Adam step from zero state moves every coordinate with a non-zero gradient by ~lr
+    k = "enc0.ffn.w1"
+    nz = np.abs(out["grad"][k]) > 1e-6
+    assert np.abs(np.abs(master[k] - snap[k])[nz] - 5e-4).max() < 1e-6
