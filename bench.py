@@ -1,0 +1,304 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X NMT training step.
+
+One "step" is one weight update of Transformer-big in fp16 with dynamic loss scaling and
+gradient accumulation: 16 sub-batches of at most 3584 tokens (forward + loss, backward,
+accumulate), then overflow check + Adam.  Inputs are synthetic (seeded length / token
+distributions standing in for the paper's WMT sub-batches) and resident in HBM before the timed
+region starts.  Prints ONE JSON line; see the design doc for the field definitions.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big_accum|big|big40k|base|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA peak (published)
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
+
+WORKLOAD_DESC = {
+    "big_accum": ("big", 16, "Transformer-big (6+6, d=1024, F=4096, 16 heads, V=32768), 16 sub-batches of <=3584 tokens per update"),
+    "big": ("big", 1, "Transformer-big, one sub-batch of <=3584 tokens per update"),
+    "big40k": ("big40k", 4, "Transformer-big with V=40000, 4 sub-batches of <=5120 tokens per update"),
+    "base": ("base", 1, "Transformer-base (6+6, d=512), one sub-batch of <=3584 tokens per update"),
+}
+
+
+def model_flops(model, B, S, T):
+    """Algorithmic FLOPs of one sub-batch's forward + backward (3x forward; padded positions count,
+    causal self-attention counts half a square; recomputation is not counted)."""
+    d, F, V, Le, Ld = model["d_model"], model["d_ff"], model["vocab"], model["enc_layers"], model["dec_layers"]
+    Ns, Nt = B * S, B * T
+    enc = Le * (Ns * (8 * d * d + 4 * d * F) + 4 * B * S * S * d)
+    dec = Ld * (Nt * (12 * d * d + 4 * d * F) + Ns * 4 * d * d + 2 * B * T * T * d + 4 * B * T * S * d)
+    return 3 * (enc + dec + 2 * Nt * d * V)
+
+
+def gemm_shapes(model, B, S, T):
+    """(M, N, K, a_t, b_t, count) of every GEMM launch of one sub-batch's forward + backward."""
+    d, F, V, Le, Ld = model["d_model"], model["d_ff"], model["vocab"], model["enc_layers"], model["dec_layers"]
+    Ns, Nt = B * S, B * T
+    out = []
+
+    def linear(N, n_in, n_out, count, wgrad=True, dgrad=True):
+        out.append((N, n_out, n_in, 0, 0, count))                 # y = x W^T
+        if dgrad:
+            out.append((N, n_in, n_out, 0, 1, count))             # dx = dy W
+        if wgrad:
+            out.append((n_out, n_in, N, 1, 1, count))             # dW = dy^T x
+
+    for N, L in ((Ns, Le), (Nt, Ld)):
+        linear(N, d, 3 * d, L)
+        linear(N, d, d, L)
+        linear(N, d, F, L)
+        linear(N, F, d, L)
+    linear(Nt, d, d, 2 * Ld)          # cross-attention query and output projections
+    linear(Ns, d, 2 * d, Ld)          # cross-attention key/value projection
+    linear(Nt, d, V, 1)               # vocabulary projection
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="big_accum", choices=sorted(WORKLOAD_DESC))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives or sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import nmt_inputs as I
+    import paper_1806_00187_amd as A
+    from paper_1806_00187_amd.session import Session, Trainer
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    A.load()
+    model_name, k_micro, desc = WORKLOAD_DESC[args.workload]
+    model = I.MODELS[model_name]
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+
+    t0 = time.time()
+    weights = I.init_weights(seed=0, **model)
+    batches = I.workload_batches(args.workload, which="random", count=k_micro, n_sentences=50_000)
+    shapes = [(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1]) for b in batches]
+    ntoks = [int((b["tgt_out"] != I.PAD).sum()) for b in batches]
+    log(f"[bench] inputs ready in {time.time() - t0:.1f}s; sub-batch shapes (B,S,T): {shapes}")
+    sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256)
+    dbatches = [sess.to_device(b) for b in batches]
+    for b, s, t in shapes:
+        sess.reserve(b, s, t)
+    tr = Trainer(sess, peak_lr=1e-3, warmup=4000, init_scale=128.0)
+
+    # warm-up: also lets the dynamic loss scale settle (an overflowing update is skipped and halves it)
+    skipped = 0
+    for _ in range(max(args.warmup, 0)):
+        _, _, flag = tr.step(dbatches)
+        skipped += flag
+    while True:     # make sure the timed region runs full (non-skipped) updates
+        _, _, flag = tr.step(dbatches)
+        if not flag:
+            break
+        skipped += 1
+    log(f"[bench] warm-up done, loss scale {tr.scale}, skipped {skipped} overflowing updates")
+
+    stream = torch.cuda.current_stream()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    ev0.record(stream)
+    flags = []
+    for _ in range(args.steps):
+        loss, ntok, flag = tr.step(dbatches)
+        flags.append(flag)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    tokens_per_step = sum(ntoks)
+    value = tokens_per_step / (ms_per_step * 1e-3)
+    flops_step = sum(model_flops(model, *s) for s in shapes)
+    achieved_tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    log(f"[bench] {ms_per_step:.2f} ms/update, {value:,.0f} target tok/s, {achieved_tflops:.1f} TFLOP/s, loss/token {loss / ntok:.3f}")
+
+    result = {
+        "metric": "target tokens/sec/GPU (train step, Transformer-big fp16)" if model_name != "base" else "target tokens/sec/GPU (train step)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "micro_batches_per_update": k_micro,
+                   "target_tokens_per_update": tokens_per_step, "padded_shapes_BST": shapes, "loss_scale": tr.scale,
+                   "overflow_updates_in_timed_region": int(sum(flags)), "wall_ms_per_step": wall * 1e3 / args.steps},
+        "roofline": {"bound": "mfma", "kernel": "whole update (every launch of the timed region)", "achieved": achieved_tflops,
+                     "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_FP16_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_update": flops_step},
+        "paper_context": {"tokens_per_s_per_gpu": 24400, "hardware": "V100, inside an 8-GPU job incl. all-reduce (Table 1, cumul)"},
+    }
+
+    if not args.no_legs:
+        result["phases_ms_per_update"] = phase_leg(sess, tr, dbatches, ntoks, torch)
+        result["roofline"]["gemm"] = gemm_leg(model, shapes, k_micro, A, torch, log)
+        result["hbm_kernels"] = hbm_leg(sess, torch)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(model, weights, batches[len(batches) // 2], k_micro, tokens_per_step, log)
+    sess.close()
+    print(json.dumps(result))
+
+
+def _timed(torch, fn, reps):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    st = torch.cuda.current_stream()
+    fn()
+    torch.cuda.synchronize()
+    e0.record(st)
+    for _ in range(reps):
+        fn()
+    e1.record(st)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def phase_leg(sess, tr, dbatches, ntoks, torch):
+    """Time of each C-ABI call summed over one update (HIP events on the launch stream)."""
+    st = torch.cuda.current_stream()
+    names = ["forward_loss", "backward", "accumulate", "check_overflow", "adam_step"]
+    acc = dict.fromkeys(names, 0.0)
+    events = []
+
+    def mark():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(st)
+        events.append(e)
+
+    torch.cuda.synchronize()
+    for j, db in enumerate(dbatches):
+        mark(); sess.forward_loss(db, tr.scale, tr.t, j)
+        mark(); sess.backward()
+        mark(); sess.accumulate(j == 0)
+    mark(); sess.check_overflow(1.0 / (tr.scale * sum(ntoks)))
+    mark(); sess.adam_step(tr.lr(), tr.t)
+    mark()
+    torch.cuda.synchronize()
+    seq = ["forward_loss", "backward", "accumulate"] * len(dbatches) + ["check_overflow", "adam_step"]
+    for i, name in enumerate(seq):
+        acc[name] += events[i].elapsed_time(events[i + 1])
+    return acc
+
+
+def gemm_leg(model, shapes, k_micro, A, torch, log):
+    """Every distinct GEMM of the update timed alone through nmt_op_gemm (HIP events, 10 launches
+    each): algorithmic FLOPs / summed average durations = achieved rate of the GEMM kernel."""
+    agg = {}
+    for s in shapes:
+        for (M, N, K, a_t, b_t, count) in gemm_shapes(model, *s):
+            key = (M, N, K, a_t, b_t)
+            agg[key] = agg.get(key, 0) + count
+    tot_flops = tot_ms = 0.0
+    n_launch = 0
+    worst, best = None, None
+    per_kind = {}
+    cache = {}
+    for (M, N, K, a_t, b_t), count in agg.items():
+        rows_a, cols_a = (K, M) if a_t else (M, K)
+        rows_b, cols_b = (K, N) if b_t else (N, K)
+        bufs = cache.get((rows_a, cols_a, rows_b, cols_b, M, N))
+        if bufs is None:
+            bufs = (torch.randn(rows_a, cols_a, device="cuda", dtype=torch.float16),
+                    torch.randn(rows_b, cols_b, device="cuda", dtype=torch.float16) * 0.03,
+                    torch.empty(M, N, device="cuda", dtype=torch.float16))
+            cache = {(rows_a, cols_a, rows_b, cols_b, M, N): bufs}
+        a, b, c = bufs
+        ms = _timed(torch, lambda: A.nmt_op_gemm(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K), 10)
+        fl = 2.0 * M * N * K
+        tot_flops += fl * count
+        tot_ms += ms * count
+        n_launch += count
+        kind = {(0, 0): "forward", (0, 1): "dgrad", (1, 1): "wgrad"}[(a_t, b_t)]
+        pk = per_kind.setdefault(kind, [0.0, 0.0])
+        pk[0] += fl * count
+        pk[1] += ms * count
+        rate = fl / ms / 1e9
+        if worst is None or rate < worst[0]:
+            worst = (rate, [M, N, K, kind])
+        if best is None or rate > best[0]:
+            best = (rate, [M, N, K, kind])
+    achieved = tot_flops / tot_ms / 1e9
+    log(f"[bench] GEMM leg: {achieved:.1f} TFLOP/s over {n_launch} launches, {tot_ms:.2f} ms per update; worst {worst}, best {best}")
+    return {"bound": "mfma", "kernel": "gemm_kernel (all GEMM launches of one update, each shape timed alone)",
+            "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS,
+            "launches_per_update": n_launch, "avg_launch_us": tot_ms * 1e3 / n_launch, "ms_per_update": tot_ms,
+            "by_kind_tflops": {k: v[0] / v[1] / 1e9 for k, v in per_kind.items()}, "worst_tflops": worst, "best_tflops": best}
+
+
+def hbm_leg(sess, torch):
+    """Achieved GB/s of the HBM-bound update kernels: algorithmic bytes per parameter
+    (accumulate 2+4+4, overflow check 4+4, Adam 16 read + 14 written) x P / duration."""
+    P = sess.P
+    out = {}
+    for name, fn, bpp in (("accumulate", lambda: sess.accumulate(False), 10), ("check_overflow", lambda: sess.check_overflow(1.0), 8),
+                          ("adam_step", None, 30)):
+        if fn is None:
+            sess.flag.zero_()
+            fn = lambda: sess.adam_step(0.0, 1)          # lr 0: full traffic, weights unchanged
+        ms = _timed(torch, fn, 5)
+        gbs = bpp * P / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "bytes_per_param": bpp, "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+    return out
+
+
+def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, log):
+    """The fp64 numpy oracle timed on the host cores: forward + backward + fp16 rounding + accumulate
+    on the first 24 sentences of one sub-batch, and overflow check + Adam over all parameters once;
+    scaled to a whole update."""
+    import numpy as np
+    import nmt_inputs as I
+    from oracle import nmt_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    nb = min(24, batch["src"].shape[0])
+    sub = {k: v[:nb] for k, v in batch.items()}
+    ntok = int((sub["tgt_out"] != I.PAD).sum())
+    cfg = O.Config(model["enc_layers"], model["dec_layers"], model["d_model"], model["n_heads"], model["d_ff"], model["vocab"],
+                   dropout=model["dropout"])
+    P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    t0 = time.perf_counter()
+    loss, n, cache = O.forward_loss(P16, cfg, sub["src"], sub["tgt_in"], sub["tgt_out"], step=1, micro=0)
+    g = O.to_fp16_storage(O.backward(P16, cfg, cache, 128.0))
+    acc = O.accumulate(None, g, True)
+    t_micro = time.perf_counter() - t0
+    del cache, g
+    t0 = time.perf_counter()
+    flag, un = O.check_overflow(acc, 1.0 / (128.0 * n))
+    m = {k: np.zeros_like(v) for k, v in P16.items()}
+    v = {k: np.zeros_like(val) for k, val in P16.items()}
+    O.adam_step(P16, m, v, un, 1e-3, 0.9, 0.98, 1e-8, 1, flag)
+    t_update = time.perf_counter() - t0
+    per_token = t_micro / ntok
+    total = per_token * tokens_per_update + t_update
+    val = tokens_per_update / total
+    log(f"[bench] oracle: {t_micro:.1f}s for {ntok} tokens, {t_update:.1f}s for overflow check + Adam; {val:.1f} tok/s on {cores} threads")
+    return {"value": val, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"fp64 numpy oracle: forward+backward+fp16 rounding+accumulate on the first {nb} sentences ({ntok} target tokens) of one "
+                      f"sub-batch ({t_micro:.1f} s), overflow check + Adam over all parameters once ({t_update:.1f} s), scaled to one update of "
+                      f"{tokens_per_update} tokens"}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,222 @@
+/*
+ * nmt.h — C ABI of the MI355X (gfx950) reduced-precision NMT training-step library.
+ *
+ * The library runs the data-parallel hot path of "Scaling Neural Machine Translation" on one
+ * GPU: Transformer encoder-decoder forward and backward in fp16 with fp32 accumulation,
+ * label-smoothed cross-entropy, loss scaling with overflow detection, fp32 master weights and
+ * Adam, and gradient accumulation over several sub-batches.
+ *
+ * Conventions
+ *  - Every function returns int: NMT_OK (0) or a negative NMT_E* code; nmt_last_error() gives
+ *    the message of the last failure on the calling thread.  No C++ exception crosses the ABI.
+ *  - Pointers named d_* (and all buffers handed to nmt_bind) are DEVICE pointers owned by the
+ *    caller; they must stay valid until the work enqueued on them has finished.  The library
+ *    never allocates or frees device memory.  Host pointers are marked "host".
+ *  - `stream` is a hipStream_t passed as void*; all kernels are enqueued on it and no function
+ *    synchronises unless it says so.
+ *  - fp16 buffers are IEEE binary16 (passed as void*).  Matrices are row-major.
+ *  - Linear weights are stored [out, in]; y = x W^T + b.
+ */
+#ifndef NMT_H_
+#define NMT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NMT_OK 0
+#define NMT_EINVAL (-1) /* bad argument or unsupported shape */
+#define NMT_ESTATE (-2) /* call out of order (e.g. backward before forward) */
+#define NMT_ENOMEM (-3) /* caller's workspace too small */
+#define NMT_EHIP (-4)   /* HIP runtime error */
+
+typedef struct nmt_ctx nmt_ctx;
+
+/* Model and regularisation hyper-parameters (section "Models and Hyperparameters"). */
+typedef struct {
+  int32_t enc_layers, dec_layers; /* blocks in the encoder / decoder                     */
+  int32_t d_model, n_heads, d_ff; /* d_model % n_heads == 0, head size in {16,32,64,128}  */
+  int32_t vocab;                  /* shared vocabulary, multiple of 8, <= 65536           */
+  int32_t pad_id;                 /* id of the padding symbol                              */
+  float dropout;                  /* on each sub-layer output before the residual add, and
+                                     on the embedding + position sum                       */
+  float act_dropout;              /* after the ReLU of the feed-forward layer              */
+  float label_smoothing;          /* weight of the uniform prior over the vocabulary       */
+  float ln_eps;                   /* variance floor of layer normalisation                 */
+  uint64_t seed;                  /* Philox key of the dropout streams                     */
+  int32_t max_sentences, max_len; /* limits for B and for S, T (max_len <= 1024)           */
+} nmt_config;
+
+const char* nmt_last_error(void);
+
+/* Host only.  Validates the configuration and builds the parameter layout. */
+int nmt_create(const nmt_config* cfg, nmt_ctx** out);
+void nmt_destroy(nmt_ctx* ctx);
+
+/* Flat parameter layout: P scalars; tensor idx occupies [offset, offset + rows*cols).
+ * Biases and LayerNorm vectors have rows == 1.  idx past the end returns NMT_EINVAL.
+ * *name points into storage owned by ctx.  Every tensor offset is a multiple of 8. */
+int64_t nmt_param_count(const nmt_ctx* ctx);
+int32_t nmt_param_tensors(const nmt_ctx* ctx);
+int nmt_param_info(const nmt_ctx* ctx, int32_t idx, const char** name, int64_t* offset,
+                   int32_t* rows, int32_t* cols);
+
+/* Bytes of workspace nmt_forward_loss / nmt_backward need for a batch of B sentences padded to
+ * S source and T target positions (negative on invalid shapes). */
+int64_t nmt_workspace_bytes(const nmt_ctx* ctx, int32_t B, int32_t S, int32_t T);
+
+/* Attach the caller's device buffers.  w16, g16: fp16[P] weights and per-sub-batch gradients;
+ * master32, acc32, adam_m, adam_v: fp32[P]; workspace: ws_bytes bytes, 256-byte aligned.
+ * Any of master32/acc32/adam_m/adam_v may be NULL if the calls using them are not made. */
+int nmt_bind(nmt_ctx* ctx, void* d_w16, void* d_g16, float* d_master32, float* d_acc32,
+             float* d_adam_m, float* d_adam_v, void* d_workspace, int64_t ws_bytes);
+
+/* Forward pass in fp16 and the label-smoothed loss in fp32 (sections "Models and
+ * Hyperparameters", "Half-Precision Training").  d_src [B,S], d_tgt_in [B,T], d_tgt_out [B,T]:
+ * int32 ids right-padded with pad_id; every sentence has at least one token.
+ * The gradient of loss_scale * (sum of token losses) with respect to the logits is left in
+ * the workspace for nmt_backward ("scale the loss right after the forward pass").
+ * step (< 2^24) and micro_idx (< 256) select the dropout streams; d_sent_uid [B] (uint32, may
+ * be NULL = row index) names each sentence so its dropout mask does not depend on batching.
+ * training == 0 disables dropout.
+ * Outputs: *d_loss_sum = sum over non-pad target tokens of the UNSCALED loss in nats,
+ * *d_ntok = number of non-pad target tokens. */
+int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_t* d_tgt_in,
+                     const int32_t* d_tgt_out, int32_t B, int32_t S, int32_t T, float loss_scale,
+                     uint32_t step, uint32_t micro_idx, const uint32_t* d_sent_uid, int32_t training,
+                     float* d_loss_sum, int32_t* d_ntok, void* stream);
+
+/* Backward pass in fp16 of the last nmt_forward_loss; writes every element of g16 with the
+ * gradient of loss_scale * loss_sum ("perform the backward pass as usual"). */
+int nmt_backward(nmt_ctx* ctx, void* stream);
+
+/* Gradient accumulation over sub-batches ("Training with Larger Batches"):
+ * first != 0: acc32 = float(g16); else acc32 += float(g16). */
+int nmt_accumulate(nmt_ctx* ctx, int32_t first, void* stream);
+
+/* Conversion of the accumulated gradients to their original scale plus overflow detection in
+ * one pass ("Half-Precision Training"): *d_flag = 1 iff any element of acc32 is inf or NaN,
+ * else 0; acc32 is multiplied by inv_scale = 1 / (loss_scale * total n_tok) in place (its
+ * content is meaningless when the flag is set). */
+int nmt_check_overflow(nmt_ctx* ctx, float inv_scale, int32_t* d_flag, void* stream);
+
+/* Adam on the fp32 master weights with gradient acc32, then w16 = round-to-nearest-even of the
+ * new master weights.  t is the 1-based update count.  If *d_flag != 0 the call changes
+ * nothing (the update is skipped on overflow). */
+int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, float eps, int32_t t,
+                  const int32_t* d_flag, void* stream);
+
+/* Host helpers holding the scalar decision logic.
+ * Dynamic loss scaling: overflow -> scale /= 2, clean = 0; otherwise clean += 1 and when clean
+ * reaches `window` (2000 in the paper) scale *= 2, clean = 0.  Returns NMT_EINVAL if the scale
+ * would fall below 2^-14. */
+int nmt_scaler_update(float* scale /*host*/, int32_t* clean /*host*/, int32_t overflow, int32_t window);
+/* Learning rate of update t (1-based): linear warm-up to `peak` over `warmup` updates, then
+ * proportional to the inverse square root of t. */
+double nmt_lr_schedule(int64_t t, double peak, int64_t warmup);
+
+/* ------------------------------------------------------------------------------------------
+ * Kernel-level entry points (used by the per-kernel parity tests and by profiling).
+ * ------------------------------------------------------------------------------------------ */
+
+/* Dropout description for the kernels that draw masks.  Element (row r, column c) of a
+ * [rows, n_cols] activation whose row r is position r % n_pos of sentence r / n_pos is kept iff
+ * the 16-bit word  (Philox4x32-10(counter = (c >> 3, uid, site << 16 | pos, step << 8 | micro),
+ * key = seed)[(c >> 1) & 3] >> 16 * (c & 1)) & 0xffff  is >= ceil(p * 2^16); kept values are
+ * multiplied by 1 / (1 - p).  uid = d_sent_uid[sentence] or the sentence index if NULL. */
+typedef struct {
+  float p;
+  uint32_t site, step, micro;
+  uint64_t seed;
+  int32_t n_pos;
+  const uint32_t* d_sent_uid;
+} nmt_dropout;
+
+/* C[M,N] = epilogue(sum_k A(m,k) B(n,k)), fp16 operands, fp32 accumulation, fp16 result.
+ * a_t == 0: A stored [M,K] (lda >= K); a_t != 0: stored [K,M] (lda >= M).
+ * b_t == 0: B stored [N,K]; b_t != 0: stored [K,N].  The contiguous dimension of each operand,
+ * N, and all leading dimensions must be multiples of 8; pointers 16-byte aligned.
+ * Epilogue, in this order: + bias[n] (fp16, or NULL); ReLU if relu != 0; dropout if drop != NULL
+ * and drop->p > 0; + add[m,n] (fp16 with leading dimension ldc, may alias C; or NULL);
+ * if relu_src != NULL (fp16 [M,N], ld = ldc): result = relu_src > 0 ? result * mask_scale : 0. */
+int nmt_op_gemm(const void* d_A, int32_t a_t, int32_t lda, const void* d_B, int32_t b_t, int32_t ldb,
+                void* d_C, int32_t ldc, int32_t M, int32_t N, int32_t K, const void* d_bias,
+                int32_t relu, const nmt_dropout* drop, const void* d_add, const void* d_relu_src,
+                float mask_scale, void* stream);
+
+/* Masked multi-head attention forward.  Q [B*Tq, *] with row stride ldq (head h at columns
+ * h*dh..), K, V [B*Tk, *]; O [B*Tq, *]; d_lse fp32 [B, H, Tq] = log-sum-exp of the scaled
+ * scores.  Key j of sentence b is hidden iff d_key_ids[b*Tk + j] == pad_id, or causal != 0 and
+ * j > query index.  Scores are scaled by 1/sqrt(dh). */
+int nmt_op_attention_fwd(const void* d_Q, int32_t ldq, const void* d_K, int32_t ldk, const void* d_V,
+                         int32_t ldv, void* d_O, int32_t ldo, float* d_lse, const int32_t* d_key_ids,
+                         int32_t pad_id, int32_t causal, int32_t B, int32_t H, int32_t dh, int32_t Tq,
+                         int32_t Tk, void* stream);
+/* Backward of the above: dQ, dK, dV from dO (and the forward's Q, K, V, O, lse). */
+int nmt_op_attention_bwd(const void* d_Q, int32_t ldq, const void* d_K, int32_t ldk, const void* d_V,
+                         int32_t ldv, const void* d_O, int32_t ldo, const void* d_dO, int32_t lddo,
+                         const float* d_lse, void* d_dQ, int32_t lddq, void* d_dK, int32_t lddk,
+                         void* d_dV, int32_t lddv, const int32_t* d_key_ids, int32_t pad_id,
+                         int32_t causal, int32_t B, int32_t H, int32_t dh, int32_t Tq, int32_t Tk,
+                         void* stream);
+
+/* out = LayerNorm(resid + dropout(sub)) * gamma + beta per row of [rows, d] (fp16 in/out, fp32
+ * math); d_stats fp32 [rows, 2] receives (mean, 1/sqrt(var + eps)). */
+int nmt_op_residual_layernorm_fwd(const void* d_sub, const void* d_resid, const void* d_gamma,
+                                  const void* d_beta, void* d_out, float* d_stats, int32_t rows,
+                                  int32_t d, float eps, const nmt_dropout* drop, void* stream);
+/* Backward: from d_dout (gradient at the LayerNorm output) computes d_dy (gradient at the
+ * pre-normalisation sum), d_dym = dropout-masked d_dy (gradient at the sub-layer output),
+ * and the fp16 vectors dgamma, dbeta and dbias = column sums of d_dym.  d_partial: fp32 scratch
+ * of nmt_op_layernorm_bwd_scratch(d) floats. */
+int64_t nmt_op_layernorm_bwd_scratch(int32_t d);
+int nmt_op_residual_layernorm_bwd(const void* d_dout, const void* d_sub, const void* d_resid,
+                                  const void* d_gamma, const float* d_stats, void* d_dy, void* d_dym,
+                                  void* d_dgamma, void* d_dbeta, void* d_dbias, float* d_partial,
+                                  int32_t rows, int32_t d, const nmt_dropout* drop, void* stream);
+
+/* x[r, :] = dropout(sqrt(d) * E[ids[r], :] + PE(r % n_pos, :)), sinusoidal positions. */
+int nmt_op_embed_fwd(const int32_t* d_ids, const void* d_E, void* d_x, int32_t rows, int32_t d,
+                     int32_t vocab, const nmt_dropout* drop, void* stream);
+
+/* Per row of fp16 logits [rows, V]: label-smoothed loss against d_targets (pad_id rows count
+ * nothing), written to d_row_loss (fp32 [rows]); logits are overwritten in place by
+ * loss_scale * (softmax - smoothed target) (zeros on pad rows).  Then *d_loss_sum, *d_ntok are
+ * reduced deterministically. */
+int nmt_op_softmax_xent(void* d_logits, const int32_t* d_targets, float* d_row_loss, int32_t rows,
+                        int32_t V, int32_t pad_id, float label_smoothing, float loss_scale,
+                        float* d_loss_sum, int32_t* d_ntok, void* stream);
+
+/* dst[c] = fp16(sum_r src[r, c]) for fp16 src [rows, cols] (ld); d_partial: fp32 scratch of
+ * nmt_op_colsum_scratch(cols) floats. */
+int64_t nmt_op_colsum_scratch(int32_t cols);
+int nmt_op_colsum(const void* d_src, int32_t ld, void* d_dst, float* d_partial, int32_t rows,
+                  int32_t cols, void* stream);
+
+/* Embedding backward: d_gE[v, :] = fp16(float(d_gE[v, :]) + sqrt(d) * sum over positions r with
+ * ids[r] == v of dropout-masked d_dx[r, :]), for two id streams (source then target) at once.
+ * Deterministic: positions are summed in increasing order.  d_scratch: int32 scratch of
+ * nmt_op_embed_bwd_scratch(vocab, rows_a + rows_b) int32 elements. */
+int64_t nmt_op_embed_bwd_scratch(int32_t vocab, int32_t rows_total);
+int nmt_op_embed_bwd(const int32_t* d_ids_a, const void* d_dx_a, int32_t rows_a, const nmt_dropout* drop_a,
+                     const int32_t* d_ids_b, const void* d_dx_b, int32_t rows_b, const nmt_dropout* drop_b,
+                     void* d_gE, int32_t d, int32_t vocab, int32_t* d_scratch, void* stream);
+
+/* Element-wise update kernels on n scalars (the bodies of nmt_accumulate, nmt_check_overflow
+ * and nmt_adam_step). */
+int nmt_op_accumulate(const void* d_g16, float* d_acc32, int64_t n, int32_t first, void* stream);
+int nmt_op_check_overflow(float* d_acc32, int64_t n, float inv_scale, int32_t* d_flag, void* stream);
+int nmt_op_adam(float* d_master32, float* d_m, float* d_v, const float* d_g32, void* d_w16, int64_t n,
+                float lr, float beta1, float beta2, float eps, int32_t t, const int32_t* d_flag,
+                void* stream);
+
+/* Writes the dropout keep decisions (1 / 0 bytes) of a [rows, n_cols] activation. */
+int nmt_op_dropout_mask(uint8_t* d_keep, int32_t rows, int32_t n_cols, const nmt_dropout* drop,
+                        void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NMT_H_ */

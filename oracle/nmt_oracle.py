@@ -318,8 +318,12 @@ def forward_loss(P, cfg: Config, src, tgt_in, tgt_out, *, training=True, step=0,
     return loss_sum, n_tok, cache
 
 
-def backward(P, cfg: Config, cache, loss_scale: float):
-    """Gradient of loss_scale * loss_sum with respect to every parameter (dict of float64)."""
+def backward(P, cfg: Config, cache, loss_scale: float, gate_flip=None):
+    """Gradient of loss_scale * loss_sum with respect to every parameter (dict of float64).
+
+    gate_flip (tests only): dict "enc0.ffn." / "dec1.ffn." ... -> bool array [N, d_ff]; the ReLU
+    gates marked True are taken the other way in this backward pass.  Used to measure how much of a
+    gradient hangs on gates whose pre-activation is too close to zero for fp16 arithmetic to decide."""
     B, S, T = cache["B"], cache["S"], cache["T"]
     d, h, Le, Ld = cfg.d_model, cfg.n_heads, cfg.enc_layers, cfg.dec_layers
     p_res, p_act = cache["p_res"], cache["p_act"]
@@ -334,7 +338,12 @@ def backward(P, cfg: Config, cache, loss_scale: float):
     def ffn_bwd(pre, c, x_in, dsub):
         """dsub: gradient at the FFN output (after residual dropout was undone). Returns d x_in."""
         dh, G[pre + "ffn.w2"], G[pre + "ffn.b2"] = linear_bwd(c["hact"], P[pre + "ffn.w2"], dsub)
-        dh = _drop(dh, c["keep_act"], p_act) * (c["hpre"] > 0.0)
+        dh = _drop(dh, c["keep_act"], p_act)
+        c["d_gate"] = dh                       # gradient arriving at the ReLU gate (kept for tests)
+        gate = c["hpre"] > 0.0
+        if gate_flip is not None and pre + "ffn." in gate_flip:
+            gate = gate ^ gate_flip[pre + "ffn."]
+        dh = dh * gate
         dxi, G[pre + "ffn.w1"], G[pre + "ffn.b1"] = linear_bwd(x_in, P[pre + "ffn.w1"], dh)
         return dxi
 

@@ -1,0 +1,152 @@
+// Internal helpers shared by the gfx950 kernels of the NMT training-step library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "nmt.h"
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// ---- error handling --------------------------------------------------------------------------
+void nmt_set_error(const char* fmt, ...);
+
+#define NMT_HIP_CHECK(expr)                                                                  \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) {                                                                  \
+      nmt_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return NMT_EHIP;                                                                       \
+    }                                                                                        \
+  } while (0)
+
+#define NMT_REQUIRE(cond, ...)   \
+  do {                           \
+    if (!(cond)) {               \
+      nmt_set_error(__VA_ARGS__); \
+      return NMT_EINVAL;         \
+    }                            \
+  } while (0)
+
+#define NMT_LAUNCH_CHECK() NMT_HIP_CHECK(hipGetLastError())
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---- wavefront reductions (64 lanes) --------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// ---- Philox4x32-10 counter-based generator (Salmon et al., SC'11) ----------------------------
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+    c = make_uint4(hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0);
+  }
+  return c;
+}
+
+// Device-side dropout description (built on the host from nmt_dropout).
+struct DropDev {
+  uint32_t k0, k1;      // Philox key = seed
+  uint32_t c3;          // step << 8 | micro
+  uint32_t site_hi;     // site << 16
+  uint32_t thr;         // keep iff 16-bit uniform >= thr; 0 = dropout off
+  float scale;          // 1 / (1 - p)
+  int32_t n_pos;        // rows per sentence
+  const uint32_t* uid;  // per-sentence ids or nullptr
+};
+
+DropDev make_drop(const nmt_dropout* d);  // host; d == nullptr or p <= 0 gives thr = 0
+
+// Keep decisions of the 8 columns [8*grp, 8*grp+8) of row `row`: bit i set = column 8*grp+i kept.
+__device__ __forceinline__ uint32_t drop_keep8(const DropDev& dd, uint32_t row, uint32_t grp) {
+  const uint32_t sent = row / (uint32_t)dd.n_pos;
+  const uint32_t pos = row - sent * (uint32_t)dd.n_pos;
+  const uint32_t uid = dd.uid ? dd.uid[sent] : sent;
+  const uint4 w = philox4x32_10(make_uint4(grp, uid, dd.site_hi | pos, dd.c3), dd.k0, dd.k1);
+  const uint32_t words[4] = {w.x, w.y, w.z, w.w};
+  uint32_t bits = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    bits |= ((words[i] & 0xFFFFu) >= dd.thr ? 1u : 0u) << (2 * i);
+    bits |= ((words[i] >> 16) >= dd.thr ? 1u : 0u) << (2 * i + 1);
+  }
+  return bits;
+}
+
+// ---- small vector helpers ---------------------------------------------------------------------
+__device__ __forceinline__ half8_t ld_half8(const half_t* p) { return *reinterpret_cast<const half8_t*>(p); }
+__device__ __forceinline__ void st_half8(half_t* p, half8_t v) { *reinterpret_cast<half8_t*>(p) = v; }
+__device__ __forceinline__ half8_t zero_half8() {
+  half8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+  return z;
+}
+
+// ---- internal launchers (all enqueue on `stream`, return NMT_* codes) -------------------------
+struct GemmEpilogue {
+  const half_t* bias = nullptr;
+  int relu = 0;
+  DropDev drop = {};
+  const half_t* add = nullptr;
+  const half_t* relu_src = nullptr;
+  float mask_scale = 1.f;
+};
+int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc,
+                int M, int N, int K, const GemmEpilogue& ep, hipStream_t stream);
+
+int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O,
+                         int ldo, float* lse, const int32_t* key_ids, int pad_id, int causal, int B, int H,
+                         int dh, int Tq, int Tk, hipStream_t stream);
+int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv,
+                         const half_t* O, int ldo, const half_t* dO, int lddo, const float* lse, half_t* dQ,
+                         int lddq, half_t* dK, int lddk, half_t* dV, int lddv, const int32_t* key_ids, int pad_id,
+                         int causal, int B, int H, int dh, int Tq, int Tk, hipStream_t stream);
+
+int launch_residual_layernorm_fwd(const half_t* sub, const half_t* resid, const half_t* gamma, const half_t* beta,
+                                  half_t* out, float* stats, int rows, int d, float eps, const DropDev& drop,
+                                  hipStream_t stream);
+int64_t layernorm_bwd_scratch_floats(int d);
+int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const half_t* resid, const half_t* gamma,
+                                  const float* stats, half_t* dy, half_t* dym, half_t* dgamma, half_t* dbeta,
+                                  half_t* dbias, float* partial, int rows, int d, const DropDev& drop,
+                                  hipStream_t stream);
+int launch_embed_fwd(const int32_t* ids, const half_t* E, half_t* x, int rows, int d, int vocab, const DropDev& drop,
+                     hipStream_t stream);
+int launch_softmax_xent(half_t* logits, const int32_t* targets, float* row_loss, int rows, int V, int pad_id,
+                        float eps_ls, float loss_scale, float* loss_sum, int32_t* ntok, hipStream_t stream);
+int64_t colsum_scratch_floats(int cols);
+int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream);
+int64_t embed_bwd_scratch_ints(int vocab, int rows_total);
+int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const DropDev& drop_a,
+                     const int32_t* ids_b, const half_t* dx_b, int rows_b, const DropDev& drop_b, half_t* gE, int d,
+                     int vocab, int32_t* scratch, hipStream_t stream);
+int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipStream_t stream);
+int launch_check_overflow(float* acc, int64_t n, float inv_scale, int32_t* flag, hipStream_t stream);
+int launch_adam(float* master, float* m, float* v, const float* g, half_t* w16, int64_t n, float lr, float b1,
+                float b2, float eps, int t, const int32_t* flag, hipStream_t stream);
+int launch_dropout_mask(uint8_t* keep, int rows, int n_cols, const DropDev& drop, hipStream_t stream);

@@ -1,0 +1,637 @@
+// HBM-bound row kernels of the training step: embedding (+positions, dropout), fused
+// residual + dropout + LayerNorm forward / backward (one wavefront per token row), column sums
+// for bias gradients, fused vocabulary softmax + label-smoothed cross-entropy + gradient, and the
+// deterministic embedding-gradient reduction.
+#include <math.h>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / kWave;
+
+__device__ __forceinline__ void unpack8(const half8_t h, float (&f)[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = (float)h[e];
+}
+__device__ __forceinline__ half8_t pack8(const float (&f)[8]) {
+  half8_t h;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) h[e] = (half_t)f[e];
+  return h;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Embedding forward: x = dropout(sqrt(d) * E[id] + PE(pos)); PE[t,2i] = sin(t / 10000^(2i/d)),
+// PE[t,2i+1] = cos(same).  One thread per 8 columns.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) embed_fwd_kernel(const int32_t* __restrict__ ids, const half_t* __restrict__ E,
+                                                             half_t* __restrict__ x, int rows, int d, int vocab,
+                                                             DropDev drop) {
+  const int chunks = d >> 3;
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (gid >= (int64_t)rows * chunks) return;
+  const int row = (int)(gid / chunks), c = (int)(gid % chunks);
+  int id = ids[row];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  float v[8];
+  unpack8(ld_half8(E + (size_t)id * d + c * 8), v);
+  const float pos = (float)(row % drop.n_pos);
+  const float sq = sqrtf((float)d);
+  const float k = -logf(10000.f) / (float)d;
+#pragma unroll
+  for (int e = 0; e < 8; e += 2) {
+    const float ang = pos * expf(k * (float)(c * 8 + e));
+    v[e] = v[e] * sq + sinf(ang);
+    v[e + 1] = v[e + 1] * sq + cosf(ang);
+  }
+  if (drop.thr) {
+    const uint32_t bits = drop_keep8(drop, (uint32_t)row, (uint32_t)c);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = ((bits >> e) & 1u) ? v[e] * drop.scale : 0.f;
+  }
+  st_half8(x + (size_t)row * d + c * 8, pack8(v));
+}
+
+// ------------------------------------------------------------------------------------------------
+// out = LayerNorm(resid + dropout(sub)); one wavefront per row, NCH chunks of 8 columns per lane.
+// ------------------------------------------------------------------------------------------------
+template <int NCH>
+__device__ __forceinline__ void load_presum(float (&y)[NCH][8], const half_t* __restrict__ sub,
+                                            const half_t* __restrict__ resid, int row, int d, int lane,
+                                            const DropDev& drop, uint32_t (&bits)[NCH]) {
+  const int chunks = d >> 3;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + kWave * i;
+    bits[i] = 0xFFu;
+    if (c < chunks) {
+      float s[8], r[8];
+      unpack8(ld_half8(sub + (size_t)row * d + c * 8), s);
+      unpack8(ld_half8(resid + (size_t)row * d + c * 8), r);
+      if (drop.thr) bits[i] = drop_keep8(drop, (uint32_t)row, (uint32_t)c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) y[i][e] = r[e] + (((bits[i] >> e) & 1u) ? s[e] * drop.scale : 0.f);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) y[i][e] = 0.f;
+    }
+  }
+}
+
+template <int NCH>
+__global__ void __launch_bounds__(kThreads) res_ln_fwd_kernel(const half_t* __restrict__ sub, const half_t* __restrict__ resid,
+                                                              const half_t* __restrict__ gamma, const half_t* __restrict__ beta,
+                                                              half_t* __restrict__ out, float* __restrict__ stats, int rows,
+                                                              int d, float eps, DropDev drop) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int chunks = d >> 3;
+  float y[NCH][8];
+  uint32_t bits[NCH];
+  load_presum<NCH>(y, sub, resid, row, d, lane, drop, bits);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += y[i][e];
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+    if (lane + kWave * i < chunks) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q += (y[i][e] - mean) * (y[i][e] - mean);
+    }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + kWave * i;
+    if (c < chunks) {
+      float g[8], b[8], o[8];
+      unpack8(ld_half8(gamma + c * 8), g);
+      unpack8(ld_half8(beta + c * 8), b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (y[i][e] - mean) * rstd * g[e] + b[e];
+      st_half8(out + (size_t)row * d + c * 8, pack8(o));
+    }
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
+// Backward.  Each wavefront walks rows (stride = all wavefronts of the grid), keeps per-lane column
+// sums for dgamma, dbeta and the bias gradient, and the block writes one partial row per quantity.
+constexpr int kLnBwdBlocks = 256;
+
+template <int NCH>
+__global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __restrict__ dout, const half_t* __restrict__ sub,
+                                                              const half_t* __restrict__ resid, const half_t* __restrict__ gamma,
+                                                              const float* __restrict__ stats, half_t* __restrict__ dy_out,
+                                                              half_t* __restrict__ dym_out, float* __restrict__ partial, int rows,
+                                                              int d, DropDev drop) {
+  extern __shared__ float red[];  // [3][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunks = d >> 3;
+  float sg[NCH][8], sb[NCH][8], sbias[NCH][8], gam[NCH][8];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + kWave * i;
+    if (c < chunks) unpack8(ld_half8(gamma + c * 8), gam[i]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sg[i][e] = sb[i][e] = sbias[i][e] = 0.f;
+      if (c >= chunks) gam[i][e] = 0.f;
+    }
+  }
+  for (int row = blockIdx.x * kWavesPerBlock + wave; row < rows; row += gridDim.x * kWavesPerBlock) {
+    float y[NCH][8], go[NCH][8];
+    uint32_t bits[NCH];
+    load_presum<NCH>(y, sub, resid, row, d, lane, drop, bits);
+    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + kWave * i;
+      if (c < chunks) {
+        unpack8(ld_half8(dout + (size_t)row * d + c * 8), go[i]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (y[i][e] - mean) * rstd;
+          y[i][e] = xh;  // keep the normalised value
+          const float g = go[i][e] * gam[i][e];
+          s1 += g;
+          s2 += g * xh;
+          sg[i][e] += go[i][e] * xh;
+          sb[i][e] += go[i][e];
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) go[i][e] = 0.f;
+      }
+    }
+    s1 = wave_sum(s1) / (float)d;
+    s2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + kWave * i;
+      if (c < chunks) {
+        float dy[8], dm[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          dy[e] = rstd * (go[i][e] * gam[i][e] - s1 - y[i][e] * s2);
+          dm[e] = ((bits[i] >> e) & 1u) ? dy[e] * drop.scale : 0.f;
+          sbias[i][e] += drop.thr ? dm[e] : dy[e];
+        }
+        st_half8(dy_out + (size_t)row * d + c * 8, pack8(dy));
+        if (dym_out) st_half8(dym_out + (size_t)row * d + c * 8, pack8(dm));
+      }
+    }
+  }
+  // block reduction, wave after wave (fixed order)
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + kWave * i;
+        if (c < chunks) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int col = c * 8 + e;
+            if (w == 0) {
+              red[col] = sg[i][e];
+              red[d + col] = sb[i][e];
+              red[2 * d + col] = sbias[i][e];
+            } else {
+              red[col] += sg[i][e];
+              red[d + col] += sb[i][e];
+              red[2 * d + col] += sbias[i][e];
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int i = threadIdx.x; i < 3 * d; i += kThreads) partial[(size_t)blockIdx.x * 3 * d + i] = red[i];
+}
+
+// dst_k[col] = fp16(sum_b partial[b][k][col]), k = 0..nq-1
+__global__ void __launch_bounds__(kThreads) finalize_partials_kernel(const float* __restrict__ partial, int nblk, int nq,
+                                                                     int cols, half_t* d0, half_t* d1, half_t* d2) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nq * cols) return;
+  float s = 0.f;
+  for (int b = 0; b < nblk; ++b) s += partial[(size_t)b * nq * cols + i];
+  const int k = i / cols, col = i % cols;
+  half_t* dst = k == 0 ? d0 : (k == 1 ? d1 : d2);
+  if (dst) dst[col] = (half_t)s;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Column sums of an fp16 matrix (bias gradients): grid (column blocks of 512, row splits).
+// ------------------------------------------------------------------------------------------------
+constexpr int kColsumMaxSplits = 64;
+
+__global__ void __launch_bounds__(kThreads) colsum_kernel(const half_t* __restrict__ src, int ld, float* __restrict__ partial,
+                                                          int rows, int cols) {
+  __shared__ float red[kWavesPerBlock][512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = blockIdx.x * 512 + lane * 8;
+  const int nsplit = gridDim.y;
+  const int per = (rows + nsplit - 1) / nsplit;
+  const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (col < cols) {
+    for (int r = r0 + wave; r < r1; r += kWavesPerBlock) {
+      float v[8];
+      unpack8(ld_half8(src + (size_t)r * ld + col), v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] += v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = s[e];
+  __syncthreads();
+  if (wave == 0 && col < cols) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      partial[(size_t)blockIdx.y * cols + col + e] = red[0][lane * 8 + e] + red[1][lane * 8 + e] + red[2][lane * 8 + e] + red[3][lane * 8 + e];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused softmax + label-smoothed cross-entropy + gradient; one block per row, the row held in
+// registers (NCH chunks of 8 logits per thread).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* sh) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  float r = sh[0];
+#pragma unroll
+  for (int w = 1; w < kWavesPerBlock; ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];
+  return r;
+}
+
+template <int NCH>
+__global__ void __launch_bounds__(kThreads) softmax_xent_kernel(half_t* __restrict__ logits, const int32_t* __restrict__ targets,
+                                                                float* __restrict__ row_loss, int V, int pad_id, float eps_ls,
+                                                                float loss_scale) {
+  __shared__ float sh[kWavesPerBlock];
+  const int row = blockIdx.x;
+  const int chunks = V >> 3;
+  half_t* z = logits + (size_t)row * V;
+  const int y = targets[row];
+  if (y == pad_id) {  // padding positions contribute neither loss nor gradient
+    for (int c = threadIdx.x; c < chunks; c += kThreads) st_half8(z + c * 8, zero_half8());
+    if (threadIdx.x == 0) row_loss[row] = 0.f;
+    return;
+  }
+  half8_t reg[NCH];
+  float mx = -INFINITY, sz = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = threadIdx.x + kThreads * i;
+    if (c < chunks) {
+      reg[i] = ld_half8(z + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float f = (float)reg[i][e];
+        mx = fmaxf(mx, f);
+        sz += f;
+      }
+    }
+  }
+  const int yc = min(max(y, 0), V - 1);
+  const float zy = (float)z[yc];
+  mx = block_reduce(mx, true, sh);
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    if (threadIdx.x + kThreads * i < chunks) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) se += __expf((float)reg[i][e] - mx);
+    }
+  }
+  se = block_reduce(se, false, sh);
+  sz = block_reduce(sz, false, sh);
+  const float lse = mx + logf(se);
+  if (threadIdx.x == 0) row_loss[row] = lse - (1.f - eps_ls) * zy - (eps_ls / (float)V) * sz;
+  const float q_uniform = eps_ls / (float)V;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = threadIdx.x + kThreads * i;
+    if (c < chunks) {
+      half8_t o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float g = __expf((float)reg[i][e] - lse) - q_uniform;
+        if (c * 8 + e == yc) g -= 1.f - eps_ls;
+        o[e] = (half_t)(loss_scale * g);
+      }
+      st_half8(z + c * 8, o);
+    }
+  }
+}
+
+// loss_sum = sum of row losses (fixed order), ntok = number of non-pad targets; single block.
+__global__ void __launch_bounds__(1024) loss_reduce_kernel(const float* __restrict__ row_loss, const int32_t* __restrict__ targets,
+                                                           int rows, int pad_id, float* loss_sum, int32_t* ntok) {
+  __shared__ float sl[1024];
+  __shared__ int sn[1024];
+  float s = 0.f;
+  int n = 0;
+  for (int r = threadIdx.x; r < rows; r += 1024) {
+    s += row_loss[r];
+    n += targets[r] != pad_id;
+  }
+  sl[threadIdx.x] = s;
+  sn[threadIdx.x] = n;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      sl[threadIdx.x] += sl[threadIdx.x + o];
+      sn[threadIdx.x] += sn[threadIdx.x + o];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    *loss_sum = sl[0];
+    *ntok = sn[0];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Embedding backward.  A counting sort of the token positions by id (histogram, scan, stable rank)
+// yields, per vocabulary row, the list of positions that used it; one block per distinct id then
+// sums those gradient rows in a fixed order and adds them to the row already holding the output
+// projection's weight gradient.
+// ------------------------------------------------------------------------------------------------
+__global__ void fill_int_kernel(int32_t* p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__device__ __forceinline__ int clamp_id(int id, int vocab) { return id < 0 ? 0 : (id >= vocab ? vocab - 1 : id); }
+__device__ __forceinline__ int id_at(const int32_t* a, int na, const int32_t* b, int i, int vocab) {
+  return clamp_id(i < na ? a[i] : b[i - na], vocab);
+}
+__global__ void __launch_bounds__(kThreads) emb_hist_kernel(const int32_t* a, int na, const int32_t* b, int nb, int vocab, int32_t* cnt) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < na + nb) atomicAdd(&cnt[id_at(a, na, b, i, vocab)], 1);
+}
+// exclusive scan of cnt[0..V) into start[0..V]; single block of 1024 threads
+__global__ void __launch_bounds__(1024) emb_scan_kernel(const int32_t* __restrict__ cnt, int32_t* __restrict__ start, int V) {
+  __shared__ int sh[1024];
+  const int per = (V + 1023) / 1024;
+  const int lo = threadIdx.x * per, hi = min(V, lo + per);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += cnt[i];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int v = (int)threadIdx.x >= o ? sh[threadIdx.x - o] : 0;
+    __syncthreads();
+    sh[threadIdx.x] += v;
+    __syncthreads();
+  }
+  int run = sh[threadIdx.x] - s;
+  for (int i = lo; i < hi; ++i) {
+    start[i] = run;
+    run += cnt[i];
+  }
+  if (threadIdx.x == 1023) start[V] = sh[1023];
+}
+// rank[i] = number of earlier positions with the same id; perm[start[id] + rank] = i
+__global__ void __launch_bounds__(kThreads) emb_rank_kernel(const int32_t* a, int na, const int32_t* b, int nb, int vocab,
+                                                            const int32_t* __restrict__ start, int32_t* __restrict__ rank,
+                                                            int32_t* __restrict__ perm) {
+  __shared__ int tile[kThreads];
+  const int n = na + nb;
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  const int my = i < n ? id_at(a, na, b, i, vocab) : -1;
+  int r = 0;
+  const int last_tile = blockIdx.x;  // positions >= (blockIdx.x+1)*kThreads are never earlier than i
+  for (int t = 0; t <= last_tile; ++t) {
+    const int j = t * kThreads + threadIdx.x;
+    __syncthreads();
+    tile[threadIdx.x] = j < n ? id_at(a, na, b, j, vocab) : -2;
+    __syncthreads();
+    const int lim = t == last_tile ? (int)threadIdx.x : kThreads;
+    for (int k = 0; k < lim; ++k) r += tile[k] == my;
+  }
+  if (i < n) {
+    rank[i] = r;
+    perm[start[my] + r] = i;
+  }
+}
+
+constexpr int kEmbThreads = 512;
+__global__ void __launch_bounds__(kEmbThreads) emb_reduce_kernel(const int32_t* a, const half_t* __restrict__ dxa, int na, DropDev da,
+                                                                 const int32_t* b, const half_t* __restrict__ dxb, int nb, DropDev db,
+                                                                 half_t* __restrict__ gE, int d, int vocab,
+                                                                 const int32_t* __restrict__ start, const int32_t* __restrict__ rank,
+                                                                 const int32_t* __restrict__ perm) {
+  extern __shared__ float part[];  // [groups][d]
+  const int i = blockIdx.x;
+  if (rank[i] != 0) return;  // only the first occurrence of an id reduces its row (block-uniform)
+  const int v = id_at(a, na, b, i, vocab);
+  const int s0 = start[v], n = start[v + 1] - s0;
+  const int chunks = d >> 3;
+  const int groups = kEmbThreads / chunks;
+  const int g = threadIdx.x / chunks, c = threadIdx.x % chunks;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (g < groups) {
+    for (int k = g; k < n; k += groups) {
+      const int pos = perm[s0 + k];
+      const bool in_a = pos < na;
+      const int row = in_a ? pos : pos - na;
+      const half_t* src = (in_a ? dxa : dxb) + (size_t)row * d + c * 8;
+      const DropDev& dd = in_a ? da : db;
+      float x[8];
+      unpack8(ld_half8(src), x);
+      uint32_t bits = 0xFFu;
+      float sc = 1.f;
+      if (dd.thr) {
+        bits = drop_keep8(dd, (uint32_t)row, (uint32_t)c);
+        sc = dd.scale;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += ((bits >> e) & 1u) ? x[e] * sc : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[g * d + c * 8 + e] = acc[e];
+  }
+  __syncthreads();
+  if (g == 0) {
+    float tot[8], cur[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tot[e] = acc[e];
+    for (int gg = 1; gg < groups; ++gg) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tot[e] += part[gg * d + c * 8 + e];
+    }
+    half_t* dst = gE + (size_t)v * d + c * 8;
+    unpack8(ld_half8(dst), cur);
+    const float sq = sqrtf((float)d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cur[e] += sq * tot[e];
+    st_half8(dst, pack8(cur));
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) dropout_mask_kernel(uint8_t* keep, int rows, int n_cols, DropDev drop) {
+  const int groups = (n_cols + 7) >> 3;
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (gid >= (int64_t)rows * groups) return;
+  const int row = (int)(gid / groups), grp = (int)(gid % groups);
+  const uint32_t bits = drop.thr ? drop_keep8(drop, (uint32_t)row, (uint32_t)grp) : 0xFFu;
+  for (int e = 0; e < 8; ++e) {
+    const int col = grp * 8 + e;
+    if (col < n_cols) keep[(size_t)row * n_cols + col] = (bits >> e) & 1u;
+  }
+}
+
+int ln_nch(int d) { return d <= 512 ? 1 : (d <= 1024 ? 2 : 4); }
+
+}  // namespace
+
+// ================================================================================================
+// launchers
+// ================================================================================================
+int launch_embed_fwd(const int32_t* ids, const half_t* E, half_t* x, int rows, int d, int vocab, const DropDev& drop,
+                     hipStream_t stream) {
+  NMT_REQUIRE(rows > 0 && d > 0 && d % 8 == 0 && vocab > 0, "embed_fwd: bad shape rows=%d d=%d", rows, d);
+  NMT_REQUIRE(ids && E && x && aligned16(E) && aligned16(x), "embed_fwd: null or misaligned pointer");
+  NMT_REQUIRE(drop.n_pos > 0, "embed_fwd: positions per sentence must be positive");
+  const int64_t n = (int64_t)rows * (d / 8);
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, ids, E, x, rows, d, vocab, drop);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int launch_residual_layernorm_fwd(const half_t* sub, const half_t* resid, const half_t* gamma, const half_t* beta,
+                                  half_t* out, float* stats, int rows, int d, float eps, const DropDev& drop,
+                                  hipStream_t stream) {
+  NMT_REQUIRE(rows > 0 && d >= 8 && d % 8 == 0 && d <= 2048, "layernorm: d=%d must be a multiple of 8 in [8, 2048]", d);
+  NMT_REQUIRE(sub && resid && gamma && beta && out && stats, "layernorm: null pointer");
+  NMT_REQUIRE(aligned16(sub) && aligned16(resid) && aligned16(gamma) && aligned16(beta) && aligned16(out), "layernorm: misaligned pointer");
+  NMT_REQUIRE(!drop.thr || drop.n_pos > 0, "layernorm: positions per sentence must be positive");
+  const dim3 grid(ceil_div(rows, kWavesPerBlock)), block(kThreads);
+  switch (ln_nch(d)) {
+    case 1: hipLaunchKernelGGL(res_ln_fwd_kernel<1>, grid, block, 0, stream, sub, resid, gamma, beta, out, stats, rows, d, eps, drop); break;
+    case 2: hipLaunchKernelGGL(res_ln_fwd_kernel<2>, grid, block, 0, stream, sub, resid, gamma, beta, out, stats, rows, d, eps, drop); break;
+    default: hipLaunchKernelGGL(res_ln_fwd_kernel<4>, grid, block, 0, stream, sub, resid, gamma, beta, out, stats, rows, d, eps, drop); break;
+  }
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int64_t layernorm_bwd_scratch_floats(int d) { return (int64_t)kLnBwdBlocks * 3 * d; }
+
+int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const half_t* resid, const half_t* gamma,
+                                  const float* stats, half_t* dy, half_t* dym, half_t* dgamma, half_t* dbeta,
+                                  half_t* dbias, float* partial, int rows, int d, const DropDev& drop,
+                                  hipStream_t stream) {
+  NMT_REQUIRE(rows > 0 && d >= 8 && d % 8 == 0 && d <= 2048, "layernorm_bwd: d=%d must be a multiple of 8 in [8, 2048]", d);
+  NMT_REQUIRE(dout && sub && resid && gamma && stats && dy && partial, "layernorm_bwd: null pointer");
+  NMT_REQUIRE(aligned16(dout) && aligned16(sub) && aligned16(resid) && aligned16(gamma) && aligned16(dy) && aligned16(dym),
+              "layernorm_bwd: misaligned pointer");
+  NMT_REQUIRE(!drop.thr || (drop.n_pos > 0 && dym), "layernorm_bwd: dropout needs the masked output and positions per sentence");
+  const int nblk = min(kLnBwdBlocks, ceil_div(rows, kWavesPerBlock));
+  const dim3 grid(nblk), block(kThreads);
+  const size_t smem = (size_t)3 * d * sizeof(float);
+  switch (ln_nch(d)) {
+    case 1: hipLaunchKernelGGL(res_ln_bwd_kernel<1>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
+    case 2: hipLaunchKernelGGL(res_ln_bwd_kernel<2>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
+    default: hipLaunchKernelGGL(res_ln_bwd_kernel<4>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
+  }
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(3 * d, kThreads)), dim3(kThreads), 0, stream, partial, nblk, 3, d,
+                     dgamma, dbeta, dbias);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int64_t colsum_scratch_floats(int cols) { return (int64_t)kColsumMaxSplits * cols; }
+
+int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream) {
+  NMT_REQUIRE(rows > 0 && cols > 0 && cols % 8 == 0 && ld % 8 == 0 && ld >= cols, "colsum: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
+  NMT_REQUIRE(src && dst && partial && aligned16(src), "colsum: null or misaligned pointer");
+  const int cb = ceil_div(cols, 512);
+  int splits = 512 / cb;
+  splits = splits < 1 ? 1 : (splits > kColsumMaxSplits ? kColsumMaxSplits : splits);
+  if (splits > rows) splits = rows;
+  hipLaunchKernelGGL(colsum_kernel, dim3(cb, splits), dim3(kThreads), 0, stream, src, ld, partial, rows, cols);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, kThreads)), dim3(kThreads), 0, stream, partial, splits, 1, cols,
+                     dst, (half_t*)nullptr, (half_t*)nullptr);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int launch_softmax_xent(half_t* logits, const int32_t* targets, float* row_loss, int rows, int V, int pad_id, float eps_ls,
+                        float loss_scale, float* loss_sum, int32_t* ntok, hipStream_t stream) {
+  NMT_REQUIRE(rows > 0 && V >= 8 && V % 8 == 0 && V <= 65536, "softmax_xent: V=%d must be a multiple of 8 in [8, 65536]", V);
+  NMT_REQUIRE(logits && targets && row_loss && loss_sum && ntok && aligned16(logits), "softmax_xent: null or misaligned pointer");
+  const dim3 grid(rows), block(kThreads);
+  const int nch = ceil_div(V / 8, kThreads);
+#define NMT_XENT(N) hipLaunchKernelGGL(softmax_xent_kernel<N>, grid, block, 0, stream, logits, targets, row_loss, V, pad_id, eps_ls, loss_scale)
+  if (nch <= 1) NMT_XENT(1);
+  else if (nch <= 4) NMT_XENT(4);
+  else if (nch <= 16) NMT_XENT(16);
+  else if (nch <= 20) NMT_XENT(20);
+  else NMT_XENT(32);
+#undef NMT_XENT
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, stream, row_loss, targets, rows, pad_id, loss_sum, ntok);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int64_t embed_bwd_scratch_ints(int vocab, int rows_total) { return (int64_t)2 * vocab + 8 + 2 * (int64_t)rows_total; }
+
+int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const DropDev& drop_a, const int32_t* ids_b,
+                     const half_t* dx_b, int rows_b, const DropDev& drop_b, half_t* gE, int d, int vocab, int32_t* scratch,
+                     hipStream_t stream) {
+  NMT_REQUIRE(rows_a >= 0 && rows_b >= 0 && rows_a + rows_b > 0, "embed_bwd: no rows");
+  NMT_REQUIRE(d >= 8 && d % 8 == 0 && d / 8 <= kEmbThreads && vocab > 0, "embed_bwd: bad d=%d", d);
+  NMT_REQUIRE((rows_a == 0 || (ids_a && dx_a && aligned16(dx_a))) && (rows_b == 0 || (ids_b && dx_b && aligned16(dx_b))) && gE &&
+                  aligned16(gE) && scratch,
+              "embed_bwd: null or misaligned pointer");
+  NMT_REQUIRE((!drop_a.thr || drop_a.n_pos > 0) && (!drop_b.thr || drop_b.n_pos > 0), "embed_bwd: positions per sentence must be positive");
+  const int n = rows_a + rows_b;
+  int32_t* cnt = scratch;
+  int32_t* start = cnt + vocab;
+  int32_t* rank = start + vocab + 8;
+  int32_t* perm = rank + n;
+  hipLaunchKernelGGL(fill_int_kernel, dim3(ceil_div(vocab, kThreads)), dim3(kThreads), 0, stream, cnt, vocab, 0);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(emb_hist_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, vocab, cnt);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, stream, cnt, start, vocab);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(emb_rank_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, vocab, start,
+                     rank, perm);
+  NMT_LAUNCH_CHECK();
+  const int groups = kEmbThreads / (d / 8);
+  hipLaunchKernelGGL(emb_reduce_kernel, dim3(n), dim3(kEmbThreads), (size_t)groups * d * sizeof(float), stream, ids_a, dx_a, rows_a,
+                     drop_a, ids_b, dx_b, rows_b, drop_b, gE, d, vocab, start, rank, perm);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int launch_dropout_mask(uint8_t* keep, int rows, int n_cols, const DropDev& drop, hipStream_t stream) {
+  NMT_REQUIRE(keep && rows > 0 && n_cols > 0, "dropout_mask: bad arguments");
+  NMT_REQUIRE(!drop.thr || drop.n_pos > 0, "dropout_mask: positions per sentence must be positive");
+  const int64_t n = (int64_t)rows * ((n_cols + 7) / 8);
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, keep, rows, n_cols, drop);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
