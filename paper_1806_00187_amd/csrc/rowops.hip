@@ -126,7 +126,7 @@ __global__ void __launch_bounds__(kThreads) res_ln_fwd_kernel(const half_t* __re
 
 // Backward.  Each wavefront walks rows (stride = all wavefronts of the grid), keeps per-lane column
 // sums for dgamma, dbeta and the bias gradient, and the block writes one partial row per quantity.
-constexpr int kLnBwdBlocks = 256;
+constexpr int kLnBwdBlocks = 1024;
 
 template <int NCH>
 __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __restrict__ dout, const half_t* __restrict__ sub,
@@ -220,16 +220,26 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
   for (int i = threadIdx.x; i < 3 * d; i += kThreads) partial[(size_t)blockIdx.x * 3 * d + i] = red[i];
 }
 
-// dst_k[col] = fp16(sum_b partial[b][k][col]), k = 0..nq-1
+// dst_k[col] = fp16(sum_b partial[b][k][col]), k = 0..nq-1.  A block owns 32 columns of one quantity;
+// its 8 row-lanes stride over the partial rows and are combined in a fixed order.
 __global__ void __launch_bounds__(kThreads) finalize_partials_kernel(const float* __restrict__ partial, int nblk, int nq,
                                                                      int cols, half_t* d0, half_t* d1, half_t* d2) {
-  const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i >= nq * cols) return;
+  __shared__ float red[8][33];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int cblocks = (cols + 31) / 32;
+  const int k = blockIdx.x / cblocks, col = (blockIdx.x % cblocks) * 32 + cx;
   float s = 0.f;
-  for (int b = 0; b < nblk; ++b) s += partial[(size_t)b * nq * cols + i];
-  const int k = i / cols, col = i % cols;
-  half_t* dst = k == 0 ? d0 : (k == 1 ? d1 : d2);
-  if (dst) dst[col] = (half_t)s;
+  if (col < cols)
+    for (int b = ry; b < nblk; b += 8) s += partial[((size_t)b * nq + k) * cols + col];
+  red[ry][cx] = s;
+  __syncthreads();
+  if (ry == 0 && col < cols) {
+    float t = red[0][cx];
+#pragma unroll
+    for (int r = 1; r < 8; ++r) t += red[r][cx];
+    half_t* dst = k == 0 ? d0 : (k == 1 ? d1 : d2);
+    if (dst) dst[col] = (half_t)t;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -553,7 +563,7 @@ int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const h
     default: hipLaunchKernelGGL(res_ln_bwd_kernel<4>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
   }
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(3 * d, kThreads)), dim3(kThreads), 0, stream, partial, nblk, 3, d,
+  hipLaunchKernelGGL(finalize_partials_kernel, dim3(3 * ceil_div(d, 32)), dim3(kThreads), 0, stream, partial, nblk, 3, d,
                      dgamma, dbeta, dbias);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
@@ -570,7 +580,7 @@ int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int ro
   if (splits > rows) splits = rows;
   hipLaunchKernelGGL(colsum_kernel, dim3(cb, splits), dim3(kThreads), 0, stream, src, ld, partial, rows, cols);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, kThreads)), dim3(kThreads), 0, stream, partial, splits, 1, cols,
+  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, 32)), dim3(kThreads), 0, stream, partial, splits, 1, cols,
                      dst, (half_t*)nullptr, (half_t*)nullptr);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
