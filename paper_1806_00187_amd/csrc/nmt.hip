@@ -71,7 +71,7 @@ struct Plan {
   int64_t x0, y0, logits, rowloss;
   std::vector<EncW> enc;
   std::vector<DecW> dec;
-  int64_t dx_dec, dx_enc, dy, dym, dO, dqkv, dh, dq, dkv, lnpart, cspart, embscratch;
+  int64_t dx_dec, dx_enc, dy[2], dym[2], dO, dqkv[2], dh[2], dq[2], dkv[2], lnpart, cspart, embscratch;
   int64_t total;
 };
 
@@ -97,6 +97,9 @@ struct nmt_ctx {
   const uint32_t* uid = nullptr;
   const int32_t *src = nullptr, *tgt_in = nullptr, *tgt_out = nullptr;
   Plan plan;
+  // second stream for the weight-gradient kernels of the backward pass (created on first use)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_done[2] = {nullptr, nullptr};
 };
 
 namespace {
@@ -184,13 +187,15 @@ int64_t plan_workspace(const nmt_ctx* c, int B, int S, int T, Plan& p) {
   p.rowloss = take(Nt * f4);
   p.dx_dec = take(Nt * d * h2);
   p.dx_enc = take(Ns * d * h2);
-  p.dy = take(Nm * d * h2);
-  p.dym = take(Nm * d * h2);
   p.dO = take(Nm * d * h2);
-  p.dqkv = take(Nm * 3 * d * h2);
-  p.dh = take(Nm * F * h2);
-  p.dq = take(Nt * d * h2);
-  p.dkv = take(Ns * 2 * d * h2);
+  for (int b = 0; b < 2; ++b) {  // two sets: weight-gradient kernels of one sub-layer overlap the next sub-layer
+    p.dy[b] = take(Nm * d * h2);
+    p.dym[b] = take(Nm * d * h2);
+    p.dqkv[b] = take(Nm * 3 * d * h2);
+    p.dh[b] = take(Nm * F * h2);
+    p.dq[b] = take(Nt * d * h2);
+    p.dkv[b] = take(Ns * 2 * d * h2);
+  }
   p.lnpart = take(layernorm_bwd_scratch_floats((int)d) * f4);
   const int64_t widest = F > 3 * d ? F : 3 * d;
   p.cspart = take(colsum_scratch_floats((int)widest) * f4);
@@ -259,7 +264,18 @@ extern "C" int nmt_create(const nmt_config* cfg, nmt_ctx** out) {
   return NMT_OK;
 }
 
-extern "C" void nmt_destroy(nmt_ctx* ctx) { delete ctx; }
+extern "C" void nmt_destroy(nmt_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->side) {
+    (void)hipStreamSynchronize(ctx->side);
+    (void)hipStreamDestroy(ctx->side);
+    (void)hipEventDestroy(ctx->ev_fork);
+    (void)hipEventDestroy(ctx->ev_join);
+    (void)hipEventDestroy(ctx->ev_done[0]);
+    (void)hipEventDestroy(ctx->ev_done[1]);
+  }
+  delete ctx;
+}
 extern "C" int64_t nmt_param_count(const nmt_ctx* ctx) { return ctx ? ctx->P : -1; }
 extern "C" int32_t nmt_param_tensors(const nmt_ctx* ctx) { return ctx ? (int32_t)ctx->tensors.size() : -1; }
 
@@ -427,6 +443,11 @@ extern "C" int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_
 // ================================================================================================
 // backward
 // ================================================================================================
+// Weight gradients (and the bias column sums) are leaves of the backward graph: nothing downstream
+// waits for them.  They are enqueued on a second stream so that they run beside the chain of
+// input-gradient kernels and fill the compute units those leave idle.  Temporaries read by the
+// second stream exist twice; set s is reused two sub-layers later, after the event recorded
+// behind its last reader.
 extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   NMT_REQUIRE(ctx, "nmt_backward: null context");
   nmt_ctx* c = ctx;
@@ -435,65 +456,103 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     return NMT_ESTATE;
   }
   c->have_fwd = false;
+  if (!c->side) {
+    NMT_HIP_CHECK(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+    NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+    NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+    NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_done[0], hipEventDisableTiming));
+    NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_done[1], hipEventDisableTiming));
+  }
   const nmt_config& k = c->cfg;
   const int B = c->B, S = c->S, T = c->T;
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
   const int Ns = B * S, Nt = B * T;
   const Plan& p = c->plan;
-  const Run r{c, static_cast<hipStream_t>(stream)};
-  hipStream_t st = r.st;
+  hipStream_t st = static_cast<hipStream_t>(stream), sd = c->side;
+  const Run r{c, st};   // input-gradient chain
+  const Run w{c, sd};   // weight gradients
   const bool dropping = c->training && k.dropout > 0.f;
   const float act_scale = (c->training && k.act_dropout > 0.f) ? 1.f / (1.f - k.act_dropout) : 1.f;
-
-  half_t* dy = r.ws<half_t>(p.dy);
-  half_t* dym = dropping ? r.ws<half_t>(p.dym) : nullptr;
-  const half_t* dsub = dropping ? dym : dy;  // gradient at a sub-layer's output
   half_t* dO = r.ws<half_t>(p.dO);
-  half_t* dqkv = r.ws<half_t>(p.dqkv);
-  half_t* dhid = r.ws<half_t>(p.dh);
   float* lnpart = r.ws<float>(p.lnpart);
-  float* cspart = r.ws<float>(p.cspart);
+  float* cspart = r.ws<float>(p.cspart);  // used on the second stream only
+
+  int set = 0;            // temporaries of the current sub-layer
+  bool used[2] = {false, false};
+  half_t *dy = nullptr, *dym = nullptr, *dqkv = nullptr, *dhid = nullptr, *dq = nullptr, *dkv = nullptr;
+  const half_t* dsub = nullptr;  // gradient at a sub-layer's output
+  auto begin_sublayer = [&]() -> int {
+    set ^= 1;
+    if (used[set]) NMT_HIP_CHECK(hipStreamWaitEvent(st, c->ev_done[set], 0));
+    used[set] = true;
+    dy = r.ws<half_t>(p.dy[set]);
+    dym = dropping ? r.ws<half_t>(p.dym[set]) : nullptr;
+    dsub = dropping ? dym : dy;
+    dqkv = r.ws<half_t>(p.dqkv[set]);
+    dhid = r.ws<half_t>(p.dh[set]);
+    dq = r.ws<half_t>(p.dq[set]);
+    dkv = r.ws<half_t>(p.dkv[set]);
+    return NMT_OK;
+  };
+  auto fork = [&]() -> int {  // the second stream may start on everything enqueued so far
+    NMT_HIP_CHECK(hipEventRecord(c->ev_fork, st));
+    NMT_HIP_CHECK(hipStreamWaitEvent(sd, c->ev_fork, 0));
+    return NMT_OK;
+  };
+  auto end_sublayer = [&]() -> int {
+    NMT_HIP_CHECK(hipEventRecord(c->ev_done[set], sd));
+    return NMT_OK;
+  };
 
   // feed-forward sub-layer: out = LN(x_in + drop(relu(x_in W1^T + b1) W2^T + b2)); dx holds d out on entry, d x_in on exit
   auto ffn_bwd = [&](half_t* dx, int N, int n_pos, const half_t* x_in, const half_t* hact, const half_t* sub, const float* stats,
                      const FfnP& f, const LnP& ln, uint32_t site_res) -> int {
+    NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, sub, x_in, r.w(ln.g), stats, dy, dym, r.g(ln.g), r.g(ln.b), r.g(f.b2), lnpart, N, d,
                                           r.drop(site_res, n_pos, k.dropout), st));
-    NMT_TRY(r.wgrad(dsub, N, d, hact, F, f.w2));
+    NMT_TRY(fork());
+    NMT_TRY(w.wgrad(dsub, N, d, hact, F, f.w2));
     GemmEpilogue relu_bwd;
     relu_bwd.relu_src = hact;
     relu_bwd.mask_scale = act_scale;
     NMT_TRY(r.dgrad(dsub, N, d, f.w2, F, dhid, relu_bwd));
-    NMT_TRY(launch_colsum(dhid, F, r.g(f.b1), cspart, N, F, st));
-    NMT_TRY(r.wgrad(dhid, N, F, x_in, d, f.w1));
+    NMT_TRY(fork());
+    NMT_TRY(launch_colsum(dhid, F, w.g(f.b1), cspart, N, F, sd));
+    NMT_TRY(w.wgrad(dhid, N, F, x_in, d, f.w1));
     GemmEpilogue res;
     res.add = dy;
     NMT_TRY(r.dgrad(dhid, N, F, f.w1, d, dx, res));
-    return NMT_OK;
+    return end_sublayer();
   };
   // self-attention sub-layer (fused q, k, v projection)
   auto self_bwd = [&](half_t* dx, int N, int n_pos, const half_t* x_in, const half_t* qkv, const half_t* o, const float* lse,
                       const half_t* sub, const float* stats, const AttnP& a, const LnP& ln, uint32_t site_res, const int32_t* key_ids,
                       int causal) -> int {
+    NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, sub, x_in, r.w(ln.g), stats, dy, dym, r.g(ln.g), r.g(ln.b), r.g(a.bo), lnpart, N, d,
                                           r.drop(site_res, n_pos, k.dropout), st));
-    NMT_TRY(r.wgrad(dsub, N, d, o, d, a.wo));
+    NMT_TRY(fork());
+    NMT_TRY(w.wgrad(dsub, N, d, o, d, a.wo));
     NMT_TRY(r.dgrad(dsub, N, d, a.wo, d, dO));
     NMT_TRY(launch_attention_bwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, o, d, dO, d, lse, dqkv, 3 * d, dqkv + d, 3 * d,
                                  dqkv + 2 * d, 3 * d, key_ids, k.pad_id, causal, B, H, dh, n_pos, n_pos, st));
-    NMT_TRY(launch_colsum(dqkv, 3 * d, r.g(a.bqkv), cspart, N, 3 * d, st));
-    NMT_TRY(r.wgrad(dqkv, N, 3 * d, x_in, d, a.wqkv));
+    NMT_TRY(fork());
+    NMT_TRY(launch_colsum(dqkv, 3 * d, w.g(a.bqkv), cspart, N, 3 * d, sd));
+    NMT_TRY(w.wgrad(dqkv, N, 3 * d, x_in, d, a.wqkv));
     GemmEpilogue res;
     res.add = dy;
     NMT_TRY(r.dgrad(dqkv, N, 3 * d, a.wqkv, d, dx, res));
-    return NMT_OK;
+    return end_sublayer();
   };
 
   // ---- output projection: logits = x E^T; the workspace holds d logits ----
+  // (the tied matrix's gradient is finished by the embedding kernels at the very end, so its
+  //  weight-gradient product stays on the main stream)
   const half_t* dlogits = r.ws<half_t>(p.logits);
   const half_t* x_dec = r.ws<half_t>(p.dec[k.dec_layers - 1].x3);
-  NMT_TRY(launch_gemm(dlogits, true, V, x_dec, true, d, r.g(c->embed), d, V, d, Nt, GemmEpilogue{}, st));
   half_t* dx = r.ws<half_t>(p.dx_dec);
+  NMT_TRY(fork());
+  NMT_TRY(launch_gemm(dlogits, true, V, x_dec, true, d, w.g(c->embed), d, V, d, Nt, GemmEpilogue{}, sd));
   NMT_TRY(launch_gemm(dlogits, false, V, r.w(c->embed), true, d, dx, d, Nt, d, V, GemmEpilogue{}, st));
 
   // ---- decoder, top to bottom ----
@@ -507,26 +566,28 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_TRY(ffn_bwd(dx, Nt, T, r.ws<half_t>(W.x2), r.ws<half_t>(W.h), r.ws<half_t>(W.s3), r.ws<float>(W.st3), P.ffn, P.ln3,
                     layer_site(li, kKindFfnRes)));
     // encoder-decoder attention
+    NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, r.ws<half_t>(W.s2), r.ws<half_t>(W.x1), r.w(P.ln2.g), r.ws<float>(W.st2), dy, dym,
                                           r.g(P.ln2.g), r.g(P.ln2.b), r.g(P.cross.bo), lnpart, Nt, d,
                                           r.drop(layer_site(li, kKindCrossRes), T, k.dropout), st));
-    NMT_TRY(r.wgrad(dsub, Nt, d, r.ws<half_t>(W.o2), d, P.cross.wo));
+    NMT_TRY(fork());
+    NMT_TRY(w.wgrad(dsub, Nt, d, r.ws<half_t>(W.o2), d, P.cross.wo));
     NMT_TRY(r.dgrad(dsub, Nt, d, P.cross.wo, d, dO));
-    half_t* dq = r.ws<half_t>(p.dq);
-    half_t* dkv = r.ws<half_t>(p.dkv);
     const half_t* kv = r.ws<half_t>(W.kv);
     NMT_TRY(launch_attention_bwd(r.ws<half_t>(W.q), d, kv, 2 * d, kv + d, 2 * d, r.ws<half_t>(W.o2), d, dO, d, r.ws<float>(W.lse2), dq, d,
                                  dkv, 2 * d, dkv + d, 2 * d, c->src, k.pad_id, 0, B, H, dh, T, S, st));
-    NMT_TRY(launch_colsum(dq, d, r.g(P.cross.bq), cspart, Nt, d, st));
-    NMT_TRY(launch_colsum(dkv, 2 * d, r.g(P.cross.bkv), cspart, Ns, 2 * d, st));
-    NMT_TRY(r.wgrad(dq, Nt, d, r.ws<half_t>(W.x1), d, P.cross.wq));
-    NMT_TRY(r.wgrad(dkv, Ns, 2 * d, enc_out, d, P.cross.wkv));
+    NMT_TRY(fork());
+    NMT_TRY(launch_colsum(dq, d, w.g(P.cross.bq), cspart, Nt, d, sd));
+    NMT_TRY(launch_colsum(dkv, 2 * d, w.g(P.cross.bkv), cspart, Ns, 2 * d, sd));
+    NMT_TRY(w.wgrad(dq, Nt, d, r.ws<half_t>(W.x1), d, P.cross.wq));
+    NMT_TRY(w.wgrad(dkv, Ns, 2 * d, enc_out, d, P.cross.wkv));
     GemmEpilogue res;
     res.add = dy;
     NMT_TRY(r.dgrad(dq, Nt, d, P.cross.wq, d, dx, res));
     GemmEpilogue accum;
     accum.add = (l == k.dec_layers - 1) ? nullptr : denc;  // the encoder output feeds every decoder layer
     NMT_TRY(r.dgrad(dkv, Ns, 2 * d, P.cross.wkv, d, denc, accum));
+    NMT_TRY(end_sublayer());
     // masked self-attention
     NMT_TRY(self_bwd(dx, Nt, T, x_in, r.ws<half_t>(W.qkv), r.ws<half_t>(W.o1), r.ws<float>(W.lse1), r.ws<half_t>(W.s1),
                      r.ws<float>(W.st1), P.self, P.ln1, layer_site(li, kKindSelfRes), c->tgt_in, 1));
@@ -544,7 +605,9 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
                      r.ws<float>(W.st1), P.attn, P.ln1, layer_site(l, kKindSelfRes), c->src, 0));
   }
 
-  // ---- embeddings: both id streams add into the row gradients of the shared matrix ----
+  // ---- join, then the embeddings: both id streams add into the row gradients of the shared matrix ----
+  NMT_HIP_CHECK(hipEventRecord(c->ev_join, sd));
+  NMT_HIP_CHECK(hipStreamWaitEvent(st, c->ev_join, 0));
   NMT_TRY(launch_embed_bwd(c->src, denc, Ns, r.drop(kSiteEmbSrc, S, k.dropout), c->tgt_in, dx_dec0, Nt, r.drop(kSiteEmbTgt, T, k.dropout),
                            r.g(c->embed), d, V, r.ws<int32_t>(p.embscratch), st));
   return NMT_OK;

@@ -124,9 +124,11 @@ __global__ void __launch_bounds__(kThreads) res_ln_fwd_kernel(const half_t* __re
   }
 }
 
-// Backward.  Each wavefront walks rows (stride = all wavefronts of the grid), keeps per-lane column
-// sums for dgamma, dbeta and the bias gradient, and the block writes one partial row per quantity.
-constexpr int kLnBwdBlocks = 1024;
+// Backward.  Each wavefront walks pairs of rows (two rows in flight hide the load latency), keeps
+// per-lane column sums for dgamma, dbeta and the bias gradient in registers, and the block writes
+// one partial row per quantity (pitch NCH*512 floats, column-indexed).
+constexpr int kLnBwdMaxBlocks = 512;
+constexpr int kLnRows = 2;
 
 template <int NCH>
 __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __restrict__ dout, const half_t* __restrict__ sub,
@@ -134,7 +136,7 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
                                                               const float* __restrict__ stats, half_t* __restrict__ dy_out,
                                                               half_t* __restrict__ dym_out, float* __restrict__ partial, int rows,
                                                               int d, DropDev drop) {
-  extern __shared__ float red[];  // [3][d]
+  extern __shared__ __align__(16) float red[];  // [3][NCH][64 lanes][8] = [3][NCH*512]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunks = d >> 3;
   float sg[NCH][8], sb[NCH][8], sbias[NCH][8], gam[NCH][8];
@@ -148,95 +150,128 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
       if (c >= chunks) gam[i][e] = 0.f;
     }
   }
-  for (int row = blockIdx.x * kWavesPerBlock + wave; row < rows; row += gridDim.x * kWavesPerBlock) {
-    float y[NCH][8], go[NCH][8];
-    uint32_t bits[NCH];
-    load_presum<NCH>(y, sub, resid, row, d, lane, drop, bits);
-    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
-    float s1 = 0.f, s2 = 0.f;
+  for (int row0 = (blockIdx.x * kWavesPerBlock + wave) * kLnRows; row0 < rows; row0 += gridDim.x * kWavesPerBlock * kLnRows) {
+    float y[kLnRows][NCH][8], go[kLnRows][NCH][8], mean[kLnRows], rstd[kLnRows], s1[kLnRows], s2[kLnRows];
+    uint32_t bits[kLnRows][NCH];
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = lane + kWave * i;
-      if (c < chunks) {
-        unpack8(ld_half8(dout + (size_t)row * d + c * 8), go[i]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float xh = (y[i][e] - mean) * rstd;
-          y[i][e] = xh;  // keep the normalised value
-          const float g = go[i][e] * gam[i][e];
-          s1 += g;
-          s2 += g * xh;
-          sg[i][e] += go[i][e] * xh;
-          sb[i][e] += go[i][e];
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) go[i][e] = 0.f;
-      }
-    }
-    s1 = wave_sum(s1) / (float)d;
-    s2 = wave_sum(s2) / (float)d;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = lane + kWave * i;
-      if (c < chunks) {
-        float dy[8], dm[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          dy[e] = rstd * (go[i][e] * gam[i][e] - s1 - y[i][e] * s2);
-          dm[e] = ((bits[i] >> e) & 1u) ? dy[e] * drop.scale : 0.f;
-          sbias[i][e] += drop.thr ? dm[e] : dy[e];
-        }
-        st_half8(dy_out + (size_t)row * d + c * 8, pack8(dy));
-        if (dym_out) st_half8(dym_out + (size_t)row * d + c * 8, pack8(dm));
-      }
-    }
-  }
-  // block reduction, wave after wave (fixed order)
-  for (int w = 0; w < kWavesPerBlock; ++w) {
-    if (wave == w) {
+    for (int u = 0; u < kLnRows; ++u) {
+      const int row = min(row0 + u, rows - 1);  // a row past the end repeats the last one and is not written
+      load_presum<NCH>(y[u], sub, resid, row, d, lane, drop, bits[u]);
+      mean[u] = stats[2 * row];
+      rstd[u] = stats[2 * row + 1];
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        const int c = lane + kWave * i;
-        if (c < chunks) {
+        if (lane + kWave * i < chunks) {
+          unpack8(ld_half8(dout + (size_t)row * d + (lane + kWave * i) * 8), go[u][i]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) go[u][i][e] = 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kLnRows; ++u) {
+      const bool live = row0 + u < rows;
+      s1[u] = s2[u] = 0.f;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        if (lane + kWave * i < chunks) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const int col = c * 8 + e;
-            if (w == 0) {
-              red[col] = sg[i][e];
-              red[d + col] = sb[i][e];
-              red[2 * d + col] = sbias[i][e];
-            } else {
-              red[col] += sg[i][e];
-              red[d + col] += sb[i][e];
-              red[2 * d + col] += sbias[i][e];
+            const float xh = (y[u][i][e] - mean[u]) * rstd[u];
+            y[u][i][e] = xh;  // keep the normalised value
+            const float g = go[u][i][e] * gam[i][e];
+            s1[u] += g;
+            s2[u] += g * xh;
+            if (live) {
+              sg[i][e] += go[u][i][e] * xh;
+              sb[i][e] += go[u][i][e];
             }
           }
         }
       }
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+      for (int u = 0; u < kLnRows; ++u) {
+        s1[u] += __shfl_xor(s1[u], o, kWave);
+        s2[u] += __shfl_xor(s2[u], o, kWave);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kLnRows; ++u) {
+      const int row = row0 + u;
+      if (row >= rows) break;
+      const float m1 = s1[u] / (float)d, m2 = s2[u] / (float)d;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + kWave * i;
+        if (c < chunks) {
+          float dy[8], dm[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            dy[e] = rstd[u] * (go[u][i][e] * gam[i][e] - m1 - y[u][i][e] * m2);
+            dm[e] = ((bits[u][i] >> e) & 1u) ? dy[e] * drop.scale : 0.f;
+            sbias[i][e] += dm[e];
+          }
+          st_half8(dy_out + (size_t)row * d + c * 8, pack8(dy));
+          if (dym_out) st_half8(dym_out + (size_t)row * d + c * 8, pack8(dm));
+        }
+      }
+    }
+  }
+  // block reduction, wave after wave (fixed order), 16-byte LDS accesses
+  floatx4* red4 = reinterpret_cast<floatx4*>(red);
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          const float(&src)[8] = q == 0 ? sg[i] : (q == 1 ? sb[i] : sbias[i]);
+          const int idx = ((q * NCH + i) * kWave + lane) * 2;
+          floatx4 lo = {src[0], src[1], src[2], src[3]}, hi = {src[4], src[5], src[6], src[7]};
+          if (w) {
+            lo += red4[idx];
+            hi += red4[idx + 1];
+          }
+          red4[idx] = lo;
+          red4[idx + 1] = hi;
+        }
+      }
+    }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < 3 * d; i += kThreads) partial[(size_t)blockIdx.x * 3 * d + i] = red[i];
+  floatx4* dst = reinterpret_cast<floatx4*>(partial + (size_t)blockIdx.x * 3 * NCH * 512);
+  for (int i = threadIdx.x; i < 3 * NCH * 128; i += kThreads) dst[i] = red4[i];
 }
 
-// dst_k[col] = fp16(sum_b partial[b][k][col]), k = 0..nq-1.  A block owns 32 columns of one quantity;
-// its 8 row-lanes stride over the partial rows and are combined in a fixed order.
-__global__ void __launch_bounds__(kThreads) finalize_partials_kernel(const float* __restrict__ partial, int nblk, int nq,
-                                                                     int cols, half_t* d0, half_t* d1, half_t* d2) {
-  __shared__ float red[8][33];
+// dst_k[col] = fp16(sum_b partial[b][k][col]), k = 0..nq-1.  A block of 1024 threads owns 32 columns of
+// one quantity; its 32 row-lanes stride over the partial rows (independent loads, several in
+// flight) and are combined in a fixed order.
+constexpr int kFinThreads = 1024;
+__global__ void __launch_bounds__(kFinThreads) finalize_partials_kernel(const float* __restrict__ partial, int nblk, int nq,
+                                                                        int cols, int pitch, half_t* d0, half_t* d1, half_t* d2) {
+  __shared__ float red[32][33];
   const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
   const int cblocks = (cols + 31) / 32;
   const int k = blockIdx.x / cblocks, col = (blockIdx.x % cblocks) * 32 + cx;
   float s = 0.f;
-  if (col < cols)
-    for (int b = ry; b < nblk; b += 8) s += partial[((size_t)b * nq + k) * cols + col];
+  if (col < cols) {
+    const float* p = partial + (size_t)k * pitch + col;
+    const size_t step = (size_t)nq * pitch;
+    int b = ry;
+    for (; b + 96 < nblk; b += 128)
+      s += (p[b * step] + p[(b + 32) * step]) + (p[(b + 64) * step] + p[(b + 96) * step]);
+    for (; b < nblk; b += 32) s += p[b * step];
+  }
   red[ry][cx] = s;
   __syncthreads();
   if (ry == 0 && col < cols) {
     float t = red[0][cx];
 #pragma unroll
-    for (int r = 1; r < 8; ++r) t += red[r][cx];
+    for (int r = 1; r < 32; ++r) t += red[r][cx];
     half_t* dst = k == 0 ? d0 : (k == 1 ? d1 : d2);
     if (dst) dst[col] = (half_t)t;
   }
@@ -543,7 +578,7 @@ int launch_residual_layernorm_fwd(const half_t* sub, const half_t* resid, const 
   return NMT_OK;
 }
 
-int64_t layernorm_bwd_scratch_floats(int d) { return (int64_t)kLnBwdBlocks * 3 * d; }
+int64_t layernorm_bwd_scratch_floats(int d) { return (int64_t)kLnBwdMaxBlocks * 3 * ln_nch(d) * 512; }
 
 int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const half_t* resid, const half_t* gamma,
                                   const float* stats, half_t* dy, half_t* dym, half_t* dgamma, half_t* dbeta,
@@ -554,17 +589,18 @@ int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const h
   NMT_REQUIRE(aligned16(dout) && aligned16(sub) && aligned16(resid) && aligned16(gamma) && aligned16(dy) && aligned16(dym),
               "layernorm_bwd: misaligned pointer");
   NMT_REQUIRE(!drop.thr || (drop.n_pos > 0 && dym), "layernorm_bwd: dropout needs the masked output and positions per sentence");
-  const int nblk = min(kLnBwdBlocks, ceil_div(rows, kWavesPerBlock));
+  const int nblk = min(kLnBwdMaxBlocks, ceil_div(rows, kWavesPerBlock * kLnRows));
+  const int nch = ln_nch(d);
   const dim3 grid(nblk), block(kThreads);
-  const size_t smem = (size_t)3 * d * sizeof(float);
-  switch (ln_nch(d)) {
+  const size_t smem = (size_t)3 * nch * 512 * sizeof(float);
+  switch (nch) {
     case 1: hipLaunchKernelGGL(res_ln_bwd_kernel<1>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
     case 2: hipLaunchKernelGGL(res_ln_bwd_kernel<2>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
     default: hipLaunchKernelGGL(res_ln_bwd_kernel<4>, grid, block, smem, stream, dout, sub, resid, gamma, stats, dy, dym, partial, rows, d, drop); break;
   }
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(finalize_partials_kernel, dim3(3 * ceil_div(d, 32)), dim3(kThreads), 0, stream, partial, nblk, 3, d,
-                     dgamma, dbeta, dbias);
+  hipLaunchKernelGGL(finalize_partials_kernel, dim3(3 * ceil_div(d, 32)), dim3(kFinThreads), 0, stream, partial, nblk, 3, d,
+                     nch * 512, dgamma, dbeta, dbias);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -580,8 +616,8 @@ int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int ro
   if (splits > rows) splits = rows;
   hipLaunchKernelGGL(colsum_kernel, dim3(cb, splits), dim3(kThreads), 0, stream, src, ld, partial, rows, cols);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, 32)), dim3(kThreads), 0, stream, partial, splits, 1, cols,
-                     dst, (half_t*)nullptr, (half_t*)nullptr);
+  hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, 32)), dim3(kFinThreads), 0, stream, partial, splits, 1, cols,
+                     cols, dst, (half_t*)nullptr, (half_t*)nullptr);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
