@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="big_accum", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipes", type=int, default=2, help="sub-batches kept in flight on separate streams")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,7 +99,7 @@ def main():
     shapes = [(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1]) for b in batches]
     ntoks = [int((b["tgt_out"] != I.PAD).sum()) for b in batches]
     log(f"[bench] inputs ready in {time.time() - t0:.1f}s; sub-batch shapes (B,S,T): {shapes}")
-    sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256)
+    sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256, n_pipes=max(1, min(args.pipes, k_micro)))
     dbatches = [sess.to_device(b) for b in batches]
     for b, s, t in shapes:
         sess.reserve(b, s, t)
@@ -107,10 +108,10 @@ def main():
     # warm-up: also lets the dynamic loss scale settle (an overflowing update is skipped and halves it)
     skipped = 0
     for _ in range(max(args.warmup, 0)):
-        _, _, flag = tr.step(dbatches)
+        _, _, flag = tr.step(dbatches, n_tok=sum(ntoks))
         skipped += flag
     while True:     # make sure the timed region runs full (non-skipped) updates
-        _, _, flag = tr.step(dbatches)
+        _, _, flag = tr.step(dbatches, n_tok=sum(ntoks))
         if not flag:
             break
         skipped += 1
@@ -123,7 +124,7 @@ def main():
     ev0.record(stream)
     flags = []
     for _ in range(args.steps):
-        loss, ntok, flag = tr.step(dbatches)
+        loss, ntok, flag = tr.step(dbatches, n_tok=sum(ntoks))
         flags.append(flag)
     ev1.record(stream)
     torch.cuda.synchronize()
@@ -142,7 +143,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "micro_batches_per_update": k_micro,
                    "target_tokens_per_update": tokens_per_step, "padded_shapes_BST": shapes, "loss_scale": tr.scale,
-                   "overflow_updates_in_timed_region": int(sum(flags)), "wall_ms_per_step": wall * 1e3 / args.steps},
+                   "overflow_updates_in_timed_region": int(sum(flags)), "sub_batches_in_flight": sess.n_pipes, "wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": {"bound": "mfma", "kernel": "whole update (every launch of the timed region)", "achieved": achieved_tflops,
                      "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_FP16_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_update": flops_step},

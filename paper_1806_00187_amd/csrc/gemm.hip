@@ -6,20 +6,21 @@
 // [K][rows]).  This covers the three products of a linear layer: forward x W^T (both direct),
 // input gradient dy W (B transposed) and weight gradient dy^T x (both transposed).
 //
-// Data path, chosen so that the main loop carries (almost) no vector-ALU work besides the MFMAs:
-//  * global -> registers with raw buffer loads: the per-thread byte offset is fixed at kernel
-//    start, the k advance is one add, and out-of-range rows / k read as zero in hardware
-//    (invalid elements get an offset beyond the buffer's extent), so there are no branches, no
-//    64-bit address arithmetic and no selects;
-//  * registers -> LDS with 16-byte stores, both layouts kept exactly as they are in memory;
-//  * LDS -> MFMA fragments: a direct tile [row][k] gives a lane its 8 consecutive k with one
-//    ds_read_b128; a transposed tile [k][row] gives them with two ds_read_b64_tr_b16 (the
-//    gfx950 transposing LDS read: within 16 lanes, lane L receives element L%4 of the 8-byte
-//    words addressed by lanes 4j + L/4, j = 0..3), so no register shuffling is needed;
-//  * all LDS addresses are one per-lane base plus compile-time offsets; row pitches are padded
-//    (not XOR-swizzled) to keep them additive and bank-conflict free;
-//  * two register sets keep two k-tiles of global loads in flight behind the tile being
-//    multiplied.
+// The kernel is bound by LDS instruction throughput, not by the matrix cores: measured on this
+// chip a wave's ds_read_b128 streams ~64 B/clk per CU and ds_write_b128 half of that, against
+// 4096 MFMA flop/clk.  The data path therefore avoids every LDS instruction it can:
+//  * global -> LDS directly (buffer_load ... lds, 16 bytes per lane, 1 KB contiguous per wave
+//    instruction): no ds_write, no staging registers.  Out-of-range rows / k (offset beyond the
+//    buffer's extent) arrive as zeros, so ragged edges need no branches;
+//  * both tile layouts are kept as they are in memory (direct [row][64 k], transposed
+//    [64 k][row]) and made bank-conflict free by permuting, on the global-address side, which
+//    16-byte chunk lands in which slot (XOR swizzles chosen so that every LDS address is one
+//    per-lane base plus compile-time offsets);
+//  * LDS -> MFMA fragments: one ds_read_b128 per fragment for a direct tile; two
+//    ds_read_b64_tr_b16 (the gfx950 transposing read: within 16 lanes, lane L receives element
+//    L%4 of the 8-byte words addressed by lanes 4j + L/4, j = 0..3) for a transposed tile, so
+//    no register shuffling is needed;
+//  * two LDS stages: the k-tile after the one being multiplied streams in meanwhile.
 #include <stdlib.h>
 
 #include <type_traits>
@@ -32,9 +33,10 @@ constexpr int BK = 64;         // k extent of one LDS stage
 constexpr int kThreads = 256;  // 4 wavefronts, arranged 2 x 2 over the block tile
 constexpr uint32_t kOob = 0x80000000u;  // byte offset no operand reaches: such loads return 0
 
-typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short short8_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) short4_t* lds_short4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 struct GemmArgs {
   const half_t* A;
@@ -48,84 +50,92 @@ struct GemmArgs {
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const half_t* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p), 0, (int)bytes, 0x00020000);
 }
-// The whole byte offset travels in the per-lane offset, which is what the hardware range-checks.
-__device__ __forceinline__ half8_t buf_load(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff) {
-  return __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, 0));
+// One wave instruction: lane L's 16 bytes at byte offset `voff` of the buffer land at lds + 16 L.
+// The whole offset travels in the per-lane operand, which is what the hardware range-checks.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned char* lds_wave_base, uint32_t voff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)lds_wave_base, 16, (int)voff, 0, 0, 0);
 }
 
-// ---- direct operand: memory [rows][K] (k contiguous), LDS tile [R][BK] with padded row pitch ----
+// ---- direct operand: memory [rows][K] (k contiguous), LDS tile [R][64 k], 128 bytes per row ------
+// Slot p (16 bytes) of tile row r holds chunk p ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1).
 template <int R>
 struct DirectOp {
-  static constexpr int NV = R / 32;              // 16-byte chunks moved per thread and k-tile
-  static constexpr int PITCH = (BK + 8) * 2;     // bytes per tile row (144: conflict-free ds_read_b128)
-  static constexpr int BYTES = R * PITCH;
+  static constexpr int NV = R / 32;   // wave instructions (8 rows each) per wave and k-tile
+  static constexpr int BYTES = R * 128;
   uint32_t voff[NV];
-  uint32_t lds_st;   // this thread's store address within the tile (bytes)
-  int c8;
+  int c8, wave;
   __device__ __forceinline__ static uint32_t extent(int rmax, int ld, int K) { return ((uint32_t)(rmax - 1) * ld + K) * 2u; }
   __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid) {
-    const int row = tid >> 3;
-    c8 = (tid & 7) << 3;
+    wave = tid >> 6;
+    const int L = tid & 63, rowl = L >> 3, p = L & 7;
+    c8 = (p ^ rowl ^ (wave & 1)) << 3;
 #pragma unroll
-    for (int it = 0; it < NV; ++it)
-      voff[it] = (r0 + row + 32 * it < rmax) ? ((uint32_t)(r0 + row + 32 * it) * (uint32_t)ld + (uint32_t)c8) * 2u : kOob;
-    lds_st = row * PITCH + (tid & 7) * 16;
+    for (int it = 0; it < NV; ++it) {
+      const int row = r0 + 8 * (wave + 4 * it) + rowl;
+      voff[it] = row < rmax ? ((uint32_t)row * (uint32_t)ld + (uint32_t)c8) * 2u : kOob;
+    }
   }
-  __device__ __forceinline__ void load(half8_t (&v)[NV], __amdgpu_buffer_rsrc_t rsrc, int ld, int k0, int K) const {
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int ld, int k0, int K) const {
     const bool kv = k0 + c8 < K;  // only the last k-tile can fail this
 #pragma unroll
-    for (int it = 0; it < NV; ++it) v[it] = buf_load(rsrc, kv ? voff[it] + (uint32_t)k0 * 2u : kOob);
+    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, kv ? voff[it] + (uint32_t)k0 * 2u : kOob);
   }
-  __device__ __forceinline__ void store(const half8_t (&v)[NV], unsigned char* tile) const {
+  // per-lane fragment addresses, one per k-step (the swizzle is an XOR in the k-step bits)
+  struct Frag { uint32_t a[BK / 16]; };
+  __device__ __forceinline__ static Frag frag_init(int row0, int lane) {
+    Frag f;
+    const int h = (lane >> 5) ^ (lane & 7) ^ ((lane >> 3) & 1);
 #pragma unroll
-    for (int it = 0; it < NV; ++it) *reinterpret_cast<half8_t*>(tile + lds_st + it * 32 * PITCH) = v[it];
+    for (int s = 0; s < BK / 16; ++s) f.a[s] = (row0 + (lane & 31)) * 128 + (((h ^ (2 * s)) & 7) << 4);
+    return f;
   }
-  // fragment base for the wave's rows starting at `row0`: lane -> row lane%32, k-half lane/32
-  __device__ __forceinline__ static uint32_t frag_base(int row0, int lane) { return (row0 + (lane & 31)) * PITCH + (lane >> 5) * 16; }
-  // 8 consecutive k of MFMA tile i, k-step s
-  __device__ __forceinline__ static half8_t frag(const unsigned char* tile, uint32_t base, int i, int s) {
-    return *reinterpret_cast<const half8_t*>(tile + base + i * 32 * PITCH + s * 32);
+  __device__ __forceinline__ static half8_t frag(const unsigned char* tile, const Frag& f, int i, int s) {
+    return *reinterpret_cast<const half8_t*>(tile + f.a[s] + i * 32 * 128);
   }
 };
 
-// ---- transposed operand: memory [K][rows] (rows contiguous), LDS tile [BK][R] as in memory -------
+// ---- transposed operand: memory [K][rows] (rows contiguous), LDS tile [64 k][R] -------------------
+// Within k row k, slot q (16 bytes) holds chunk q ^ (y(k) << 1): the four k rows a 16-lane group of
+// the transposing read touches then lie in four different 32-byte bank segments.
 template <int R>
 struct TransOp {
   static constexpr int NV = R / 32;
-  static constexpr int PITCH = (R + 16) * 2;     // bytes per k row of the tile
-  static constexpr int BYTES = BK * PITCH;
-  static constexpr int CPR = R / 8;              // 16-byte chunks per k row
+  static constexpr int ROWB = R * 2;        // bytes per k row
+  static constexpr int BYTES = BK * ROWB;
+  static constexpr int CPR = R / 8;         // 16-byte chunks per k row
+  static constexpr int KPI = 64 / CPR;      // k rows per wave instruction
   uint32_t voff[NV];
-  uint32_t lds_st;
+  int wave;
+  __device__ __forceinline__ static int ysw(int k2) { return R == 128 ? ((k2 & 1) | ((k2 & 2) << 1)) : (k2 & 3); }
   __device__ __forceinline__ static uint32_t extent(int rmax, int ld, int K) { return ((uint32_t)(K - 1) * ld + rmax) * 2u; }
   __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid) {
-    const int k = tid / CPR, ch = tid % CPR;
-    const bool ok = r0 + ch * 8 < rmax;
+    wave = tid >> 6;
+    const int L = tid & 63, kl = L / CPR, slot = L % CPR;
+    const int cc = slot ^ (ysw(kl & 3) << 1);
+    const bool ok = r0 + cc * 8 < rmax;
 #pragma unroll
     for (int it = 0; it < NV; ++it)
-      voff[it] = ok ? ((uint32_t)(k + it * (kThreads / CPR)) * (uint32_t)ld + (uint32_t)(r0 + ch * 8)) * 2u : kOob;
-    lds_st = k * PITCH + ch * 16;
+      voff[it] = ok ? ((uint32_t)(KPI * (wave + 4 * it) + kl) * (uint32_t)ld + (uint32_t)(r0 + cc * 8)) * 2u : kOob;
   }
-  // rows k >= K lie beyond the buffer's extent and read as zero
-  __device__ __forceinline__ void load(half8_t (&v)[NV], __amdgpu_buffer_rsrc_t rsrc, int ld, int k0, int K) const {
+  // k rows >= K lie beyond the buffer's extent and arrive as zeros
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int ld, int k0, int K) const {
 #pragma unroll
-    for (int it = 0; it < NV; ++it) v[it] = buf_load(rsrc, voff[it] + (uint32_t)k0 * (uint32_t)ld * 2u);
+    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, voff[it] + (uint32_t)k0 * (uint32_t)ld * 2u);
   }
-  __device__ __forceinline__ void store(const half8_t (&v)[NV], unsigned char* tile) const {
-#pragma unroll
-    for (int it = 0; it < NV; ++it) *reinterpret_cast<half8_t*>(tile + lds_st + it * (kThreads / CPR) * PITCH) = v[it];
-  }
+  struct Frag { uint32_t a; };
   // 16-lane group q = lane/16 serves rows 16*(q&1).. of the MFMA tile and k-half q/2; lane i of the group
   // addresses k row i/4, row offset 4*(i%4) of its 4(k) x 16(row) block.
-  __device__ __forceinline__ static uint32_t frag_base(int row0, int lane) {
+  __device__ __forceinline__ static Frag frag_init(int row0, int lane) {
     const int q = lane >> 4, i = lane & 15;
-    return (8 * (q >> 1) + (i >> 2)) * PITCH + (row0 + 16 * (q & 1) + 4 * (i & 3)) * 2;
+    const int kk = 8 * (q >> 1) + (i >> 2);
+    const int r = row0 + 16 * (q & 1) + 4 * (i & 3);
+    const int cc = (r >> 3) ^ (ysw((i >> 2) & 3) << 1);
+    return Frag{(uint32_t)(kk * ROWB + cc * 16 + (r & 7) * 2)};
   }
-  __device__ __forceinline__ static half8_t frag(const unsigned char* tile, uint32_t base, int i, int s) {
-    const unsigned char* p = tile + base + s * 16 * PITCH + i * 64;
-    typedef short short8_t __attribute__((ext_vector_type(8)));
+  __device__ __forceinline__ static half8_t frag(const unsigned char* tile, const Frag& f, int i, int s) {
+    const unsigned char* p = tile + f.a + s * 16 * ROWB + i * 64;
     const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
-    const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 4 * PITCH));
+    const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 4 * ROWB));
     const short8_t r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(half8_t, r);
   }
@@ -135,38 +145,40 @@ template <int BM, int BN, bool AT, bool BT>
 struct Tile {
   using OpA = typename std::conditional<AT, TransOp<BM>, DirectOp<BM>>::type;
   using OpB = typename std::conditional<BT, TransOp<BN>, DirectOp<BN>>::type;
-  static constexpr int STAGE = OpA::BYTES + OpB::BYTES;
-  static constexpr int WN = BN / 2;
-  static constexpr int STAGING = 4 * 32 * (WN + 4) * 4;
-  static constexpr int SMEM = 2 * STAGE > STAGING ? 2 * STAGE : STAGING;
+  static constexpr int STAGE = OpA::BYTES + OpB::BYTES;   // (BM + BN) * 128 bytes
 };
 
 template <int BM, int BN, bool AT, bool BT>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
-  extern __shared__ __align__(16) unsigned char smem[];
   using T = Tile<BM, BN, AT, BT>;
   using OpA = typename T::OpA;
   using OpB = typename T::OpB;
-  constexpr int STAGE = T::STAGE;
+  // two separate arrays, so that the compiler can tell that fragment reads of one stage do not
+  // depend on the loads in flight into the other
+  __shared__ __align__(1024) unsigned char stage0[T::STAGE];
+  __shared__ __align__(1024) unsigned char stage1[T::STAGE];
   constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
   // Work-group -> tile.  Consecutive work-group ids go round-robin over the 8 XCDs; undo that so
-  // each XCD (own L2) gets a contiguous run of tiles, then sweep the smaller operand fastest.
+  // each XCD (own L2) gets a contiguous run of tiles.
   int pid = blockIdx.x;
   {
     const int nt = g.tiles_m * g.tiles_n, xcd = pid & 7, idx = pid >> 3;
     const int base = nt >> 3, rem = nt & 7;
     pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
+  // Grouped order: 8 tile rows are swept column by column, so the ~64 work-groups an XCD runs at a
+  // time form an 8 x 8 patch of tiles and each A / B panel they stream is shared by 8 of them in L2.
   int tm, tn;
-  if (g.tm_fast) {
-    tm = pid % g.tiles_m;
-    tn = pid / g.tiles_m;
-  } else {
-    tn = pid % g.tiles_n;
-    tm = pid / g.tiles_n;
+  {
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * g.tiles_n;
+    const int first = (pid / per_group) * GROUP;
+    const int rows = min(g.tiles_m - first, GROUP);
+    tm = first + (pid % per_group) % rows;
+    tn = (pid % per_group) / rows;
   }
   const int m0 = tm * BM, n0 = tn * BN;
 
@@ -184,20 +196,17 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
   opb.init(g.ldb, n0, g.N, tid);
   const __amdgpu_buffer_rsrc_t ra_src = make_rsrc(g.A, OpA::extent(g.M, g.lda, g.K));
   const __amdgpu_buffer_rsrc_t rb_src = make_rsrc(g.B, OpB::extent(g.N, g.ldb, g.K));
-  const uint32_t fa = OpA::frag_base(wm * WM, lane), fb = OpB::frag_base(wn * WN, lane);
-  half8_t ra0[OpA::NV], rb0[OpB::NV], ra1[OpA::NV], rb1[OpB::NV];
+  const typename OpA::Frag fa = OpA::frag_init(wm * WM, lane);
+  const typename OpB::Frag fb = OpB::frag_init(wn * WN, lane);
 
-  auto g2r = [&](half8_t (&ra)[OpA::NV], half8_t (&rb)[OpB::NV], int k0) {
-    opa.load(ra, ra_src, g.lda, k0, g.K);
-    opb.load(rb, rb_src, g.ldb, k0, g.K);
+  auto request = [&](unsigned char* stage, int k0) {  // asynchronous: tile k0 streams into `stage`
+    opa.load(ra_src, stage, g.lda, k0, g.K);
+    opb.load(rb_src, stage + OpA::BYTES, g.ldb, k0, g.K);
+    __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of the products they overlap with
   };
-  auto r2s = [&](const half8_t (&ra)[OpA::NV], const half8_t (&rb)[OpB::NV], int stage) {
-    opa.store(ra, smem + stage * STAGE);
-    opb.store(rb, smem + stage * STAGE + OpA::BYTES);
-  };
-  auto compute = [&](int stage) {
-    const unsigned char* As = smem + stage * STAGE;
-    const unsigned char* Bs = As + OpA::BYTES;
+  auto compute = [&](const unsigned char* stage) {
+    const unsigned char* As = stage;
+    const unsigned char* Bs = stage + OpA::BYTES;
 #pragma unroll
     for (int s = 0; s < BK / 16; ++s) {
       half8_t af[TM], bf[TN];
@@ -211,88 +220,90 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
   };
+  // all of this wave's loads into LDS have landed (vmcnt(0)); the barrier then publishes every wave's part
+  auto landed = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  };
 
-  // Software pipeline: LDS holds tile kt, registers hold tile kt+1 and (in flight) tile kt+2, so a
-  // global load has two tile computations to land.  The loop body is written twice so that the
-  // two register sets and the two LDS stages are addressed statically.
+  // A k-tile past the end reads zeros (its offsets are out of range) and multiplying it changes
+  // nothing, so the loop always runs in pairs and carries no edge conditions.
   const int nk = (g.K + BK - 1) / BK;
-  g2r(ra0, rb0, 0);
-  if (nk > 1) g2r(ra1, rb1, BK);
-  r2s(ra0, rb0, 0);
-  __syncthreads();
-  int kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    if (kt + 2 < nk) g2r(ra0, rb0, (kt + 2) * BK);
-    compute(0);
-    r2s(ra1, rb1, 1);
-    __syncthreads();
-    if (kt + 3 < nk) g2r(ra1, rb1, (kt + 3) * BK);
-    compute(1);
-    if (kt + 2 < nk) r2s(ra0, rb0, 0);
-    __syncthreads();
+  request(stage0, 0);
+  landed();
+  for (int kt = 0; kt < nk; kt += 2) {
+    request(stage1, (kt + 1) * BK);
+    compute(stage0);
+    landed();
+    request(stage0, (kt + 2) * BK);
+    compute(stage1);
+    landed();
   }
-  if (kt < nk) compute(0);  // odd number of k tiles: the last one sits in stage 0
-  __syncthreads();
 
   // ---- epilogue: accumulators -> per-wave LDS staging (fp32) -> row-wise 16-byte stores -------
-  constexpr int SP = WN + 4;  // staging row pitch in floats
-  float* stg = reinterpret_cast<float*>(smem) + wave * (32 * SP);
-  constexpr int CH = WN / 8;  // 8-column chunks per staged row
+  // staging width per pass: the wave's whole width if 4 waves x 32 rows of it fit one stage, else 32
+  constexpr int SW = (4 * 32 * WN * 4 <= T::STAGE) ? WN : 32;
+  static_assert(4 * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
+  float* stg = reinterpret_cast<float*>(stage1) + wave * (32 * SW);
+  constexpr int CH = SW / 8;  // 8-column chunks per staged row
   const GemmEpilogue& ep = g.ep;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    if (i) __syncthreads();
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int jg = 0; jg < WN / SW; ++jg) {
+      if (i || jg) __syncthreads();
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);  // MFMA 32x32 result layout
-        stg[row * SP + j * 32 + (lane & 31)] = acc[i][j][r];
-      }
-    __syncthreads();
+      for (int jj = 0; jj < SW / 32; ++jj)
 #pragma unroll
-    for (int it = 0; it < CH / 2; ++it) {
-      const int q = it * 64 + lane;
-      const int rl = q / CH, c8 = q % CH;
-      const int gr = m0 + wm * WM + i * 32 + rl, gc = n0 + wn * WN + c8 * 8;
-      if (gr < g.M && gc < g.N) {
-        float v[8];
-        const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + rl * SP + c8 * 8);
-        const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + rl * SP + c8 * 8 + 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          v[e] = lo[e];
-          v[4 + e] = hi[e];
+        for (int r = 0; r < 16; ++r) {
+          const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);  // MFMA 32x32 result layout
+          stg[row * SW + jj * 32 + (lane & 31)] = acc[i][jg * (SW / 32) + jj][r];
         }
-        if (ep.bias) {
-          const half8_t b = ld_half8(ep.bias + gc);
+      __syncthreads();
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += (float)b[e];
+      for (int it = 0; it < CH / 2; ++it) {
+        const int q = it * 64 + lane;
+        const int rl = q / CH, c8 = q % CH;
+        const int gr = m0 + wm * WM + i * 32 + rl, gc = n0 + wn * WN + jg * SW + c8 * 8;
+        if (gr < g.M && gc < g.N) {
+          float v[8];
+          const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + rl * SW + c8 * 8);
+          const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + rl * SW + c8 * 8 + 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[e] = lo[e];
+            v[4 + e] = hi[e];
+          }
+          if (ep.bias) {
+            const half8_t b = ld_half8(ep.bias + gc);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += (float)b[e];
+          }
+          if (ep.relu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+          }
+          if (ep.drop.thr) {
+            const uint32_t bits = drop_keep8(ep.drop, (uint32_t)gr, (uint32_t)gc >> 3);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = ((bits >> e) & 1u) ? v[e] * ep.drop.scale : 0.f;
+          }
+          const size_t off = (size_t)gr * g.ldc + gc;
+          if (ep.add) {
+            const half8_t a = ld_half8(ep.add + off);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += (float)a[e];
+          }
+          if (ep.relu_src) {
+            const half8_t h = ld_half8(ep.relu_src + off);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = ((float)h[e] > 0.f) ? v[e] * ep.mask_scale : 0.f;
+          }
+          half8_t o;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (half_t)v[e];
+          st_half8(g.C + off, o);
         }
-        if (ep.relu) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-        }
-        if (ep.drop.thr) {
-          const uint32_t bits = drop_keep8(ep.drop, (uint32_t)gr, (uint32_t)gc >> 3);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = ((bits >> e) & 1u) ? v[e] * ep.drop.scale : 0.f;
-        }
-        const size_t off = (size_t)gr * g.ldc + gc;
-        if (ep.add) {
-          const half8_t a = ld_half8(ep.add + off);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += (float)a[e];
-        }
-        if (ep.relu_src) {
-          const half8_t h = ld_half8(ep.relu_src + off);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = ((float)h[e] > 0.f) ? v[e] * ep.mask_scale : 0.f;
-        }
-        half8_t o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (half_t)v[e];
-        st_half8(g.C + off, o);
       }
     }
   }
@@ -300,14 +311,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
 
 template <int BM, int BN, bool AT, bool BT>
 int launch_variant(const GemmArgs& g, hipStream_t stream) {
-  constexpr int smem = Tile<BM, BN, AT, BT>::SMEM;
-  static bool big_lds_enabled = false;  // dynamic LDS beyond 64 KB has to be allowed once per kernel
-  if (smem > 64 * 1024 && !big_lds_enabled) {
-    NMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<BM, BN, AT, BT>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-    big_lds_enabled = true;
-  }
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT>), dim3(g.tiles_m * g.tiles_n), dim3(kThreads), smem, stream, g);
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT>), dim3(g.tiles_m * g.tiles_n), dim3(kThreads), 0, stream, g);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

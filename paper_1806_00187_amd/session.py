@@ -12,16 +12,25 @@ from . import binding as nmt
 
 
 class Session:
+    """n_pipes > 1 keeps that many sub-batches in flight: each pipe has its own library context (same
+    weights and optimizer buffers, own fp16 gradient buffer and workspace) and its own HIP stream, so
+    the forward pass of one sub-batch overlaps the backward pass of the previous one.  Accumulation
+    into the shared fp32 buffer is chained with events in sub-batch order, which keeps the sum
+    deterministic."""
+
     def __init__(self, model, weights, max_sentences=1024, max_len=256, act_dropout=0.0, label_smoothing=0.1, ln_eps=1e-5,
-                 seed=0, pad_id=1, device="cuda:0", optimizer=True):
+                 seed=0, pad_id=1, device="cuda:0", optimizer=True, n_pipes=1):
         """model: dict(enc_layers, dec_layers, d_model, n_heads, d_ff, vocab, dropout);
         weights: dict name -> float16 numpy array (initial fp16 weights = initial master values)."""
         self.device = torch.device(device)
         self.model = dict(model)
-        self.ctx = nmt.nmt_create(enc_layers=model["enc_layers"], dec_layers=model["dec_layers"], d_model=model["d_model"],
-                                  n_heads=model["n_heads"], d_ff=model["d_ff"], vocab=model["vocab"], pad_id=pad_id,
-                                  dropout=model.get("dropout", 0.0), act_dropout=act_dropout, label_smoothing=label_smoothing,
-                                  ln_eps=ln_eps, seed=seed, max_sentences=max_sentences, max_len=max_len)
+        self.n_pipes = n_pipes
+        cfg = dict(enc_layers=model["enc_layers"], dec_layers=model["dec_layers"], d_model=model["d_model"],
+                   n_heads=model["n_heads"], d_ff=model["d_ff"], vocab=model["vocab"], pad_id=pad_id,
+                   dropout=model.get("dropout", 0.0), act_dropout=act_dropout, label_smoothing=label_smoothing,
+                   ln_eps=ln_eps, seed=seed, max_sentences=max_sentences, max_len=max_len)
+        self.ctxs = [nmt.nmt_create(**cfg) for _ in range(n_pipes)]
+        self.ctx = self.ctxs[0]
         self.P = nmt.nmt_param_count(self.ctx)
         self.layout = {}
         for i in range(nmt.nmt_param_tensors(self.ctx)):
@@ -33,7 +42,8 @@ class Session:
             assert w.size == rows * cols, name
             flat[off:off + rows * cols] = w.reshape(-1)
         self.w16 = torch.from_numpy(flat).to(self.device)
-        self.g16 = torch.zeros(self.P, dtype=torch.float16, device=self.device)
+        self.g16s = [torch.zeros(self.P, dtype=torch.float16, device=self.device) for _ in range(n_pipes)]
+        self.g16 = self.g16s[0]
         if optimizer:
             self.master = self.w16.float()
             self.acc = torch.zeros(self.P, dtype=torch.float32, device=self.device)
@@ -41,28 +51,39 @@ class Session:
             self.v = torch.zeros_like(self.acc)
         else:
             self.master = self.acc = self.m = self.v = None
-        self.workspace = None
-        self.loss_sum = torch.zeros(1, dtype=torch.float32, device=self.device)
-        self.ntok = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.workspaces = [None] * n_pipes
+        self.loss_sums = [torch.zeros(1, dtype=torch.float32, device=self.device) for _ in range(n_pipes)]
+        self.ntoks = [torch.zeros(1, dtype=torch.int32, device=self.device) for _ in range(n_pipes)]
+        self.loss_sum, self.ntok = self.loss_sums[0], self.ntoks[0]
         self.flag = torch.zeros(1, dtype=torch.int32, device=self.device)
-        self._bind()
+        self.loss_tot = torch.zeros(1, dtype=torch.float32, device=self.device)
+        self.ntok_tot = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.streams = [torch.cuda.Stream(device=self.device) for _ in range(n_pipes)] if n_pipes > 1 else [None]
+        for p in range(n_pipes):
+            self._bind(p)
 
-    def _bind(self):
-        nmt.nmt_bind(self.ctx, self.w16, self.g16, self.master, self.acc, self.m, self.v, self.workspace)
+    def _bind(self, pipe=0):
+        nmt.nmt_bind(self.ctxs[pipe], self.w16, self.g16s[pipe], self.master, self.acc, self.m, self.v, self.workspaces[pipe])
+
+    @property
+    def workspace(self):
+        return self.workspaces[0]
 
     def close(self):
-        if self.ctx is not None:
+        if self.ctxs:
             torch.cuda.synchronize(self.device)
-            nmt.nmt_destroy(self.ctx)
-            self.ctx = None
+            for c in self.ctxs:
+                nmt.nmt_destroy(c)
+            self.ctxs, self.ctx = [], None
 
     def reserve(self, B, S, T):
         need = nmt.nmt_workspace_bytes(self.ctx, B, S, T)
-        if self.workspace is None or self.workspace.numel() < need:
-            torch.cuda.synchronize(self.device)
-            self.workspace = None
-            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
-            self._bind()
+        for p in range(self.n_pipes):
+            if self.workspaces[p] is None or self.workspaces[p].numel() < need:
+                torch.cuda.synchronize(self.device)
+                self.workspaces[p] = None
+                self.workspaces[p] = torch.empty(need, dtype=torch.uint8, device=self.device)
+                self._bind(p)
 
     def to_device(self, batch):
         """numpy micro-batch -> dict of int32 device tensors (+ optional uint32 sentence ids)."""
@@ -72,17 +93,17 @@ class Session:
         return out
 
     # ---- the five calls ----
-    def forward_loss(self, dbatch, loss_scale, step, micro=0, training=True):
+    def forward_loss(self, dbatch, loss_scale, step, micro=0, training=True, pipe=0):
         B, S = dbatch["src"].shape
         self.reserve(B, S, dbatch["tgt_in"].shape[1])
-        nmt.nmt_forward_loss(self.ctx, dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step, micro, self.loss_sum,
-                             self.ntok, sent_uid=dbatch.get("sent_uid"), training=training)
+        nmt.nmt_forward_loss(self.ctxs[pipe], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step, micro,
+                             self.loss_sums[pipe], self.ntoks[pipe], sent_uid=dbatch.get("sent_uid"), training=training)
 
-    def backward(self):
-        nmt.nmt_backward(self.ctx)
+    def backward(self, pipe=0):
+        nmt.nmt_backward(self.ctxs[pipe])
 
-    def accumulate(self, first):
-        nmt.nmt_accumulate(self.ctx, first)
+    def accumulate(self, first, pipe=0):
+        nmt.nmt_accumulate(self.ctxs[pipe], first)
 
     def check_overflow(self, inv_scale):
         nmt.nmt_check_overflow(self.ctx, inv_scale, self.flag)
@@ -91,21 +112,46 @@ class Session:
         nmt.nmt_adam_step(self.ctx, lr, betas[0], betas[1], eps, t, self.flag)
 
     # ---- one weight update from k micro-batches ----
-    def update(self, dbatches, loss_scale, lr, t, step=None, betas=(0.9, 0.98), eps=1e-8):
-        """Returns (loss_sum, n_tok, overflow flag).  Synchronises once, to read the three scalars."""
+    def update(self, dbatches, loss_scale, lr, t, step=None, betas=(0.9, 0.98), eps=1e-8, n_tok=None):
+        """Returns (loss_sum, n_tok, overflow flag).  n_tok (the number of non-pad target tokens of the
+        whole update) is known to whoever built the batches; if it is not passed it is read back from
+        the device, which costs one more synchronisation."""
         step = t if step is None else step
-        loss_tot = torch.zeros(1, dtype=torch.float32, device=self.device)
-        ntok_tot = torch.zeros(1, dtype=torch.int32, device=self.device)
-        for j, db in enumerate(dbatches):
-            self.forward_loss(db, loss_scale, step, j)
-            self.backward()
-            self.accumulate(j == 0)
-            loss_tot += self.loss_sum
-            ntok_tot += self.ntok
-        n_tok = int(ntok_tot.item())
+        main = torch.cuda.current_stream(self.device)
+        self.loss_tot.zero_()
+        self.ntok_tot.zero_()
+        if self.n_pipes == 1:
+            for j, db in enumerate(dbatches):
+                self.forward_loss(db, loss_scale, step, j)
+                self.backward()
+                self.accumulate(j == 0)
+                self.loss_tot += self.loss_sum
+                self.ntok_tot += self.ntok
+        else:
+            start = torch.cuda.Event()
+            start.record(main)
+            prev = None
+            for j, db in enumerate(dbatches):
+                p = j % self.n_pipes
+                s = self.streams[p]
+                if j < self.n_pipes:
+                    s.wait_event(start)            # the weights of this update are in place
+                with torch.cuda.stream(s):
+                    self.forward_loss(db, loss_scale, step, j, pipe=p)
+                    self.backward(pipe=p)
+                    if prev is not None:
+                        s.wait_event(prev)         # accumulate in sub-batch order
+                    self.accumulate(j == 0, pipe=p)
+                    self.loss_tot += self.loss_sums[p]
+                    self.ntok_tot += self.ntoks[p]
+                    prev = torch.cuda.Event()
+                    prev.record(s)
+            main.wait_event(prev)
+        if n_tok is None:
+            n_tok = int(self.ntok_tot.item())
         self.check_overflow(1.0 / (loss_scale * max(n_tok, 1)))
         self.adam_step(lr, t, betas, eps)
-        return float(loss_tot.item()), n_tok, int(self.flag.item())
+        return float(self.loss_tot.item()), n_tok, int(self.flag.item())
 
     # ---- views for tests ----
     def tensor(self, flat, name):
@@ -127,9 +173,9 @@ class Trainer:
     def lr(self):
         return self.peak_lr if self.constant_lr else nmt.nmt_lr_schedule(self.t, self.peak_lr, self.warmup)
 
-    def step(self, dbatches, scale_override=None):
+    def step(self, dbatches, scale_override=None, n_tok=None):
         scale = self.scale if scale_override is None else scale_override
-        loss, ntok, flag = self.s.update(dbatches, scale, self.lr(), self.t)
+        loss, ntok, flag = self.s.update(dbatches, scale, self.lr(), self.t, n_tok=n_tok)
         self.scale, self.clean = nmt.nmt_scaler_update(self.scale, self.clean, flag, self.window)
         if not flag:
             self.t += 1          # a skipped update advances neither Adam's step nor the schedule

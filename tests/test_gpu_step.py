@@ -247,3 +247,22 @@ def test_call_order_and_workspace_errors():
     assert e.value.code == A.binding.NMT_ENOMEM
     sess._bind()
     sess.close()
+
+
+def test_sub_batches_in_flight_give_bit_identical_updates():
+    """Two sub-batches in flight on separate streams (forward of one beside backward of the other)
+    accumulate in the same order as the serial schedule: every buffer ends up bit-identical."""
+    model = I.MODELS["tiny"]
+    weights = I.init_weights(seed=0, perturb=0.1, **model)
+    batches = [I.tiny_batch(seed=1001 + i, B=8 - i, S=16 - i, T=12 + i) for i in range(5)]
+    outs = []
+    for pipes in (1, 2, 3):
+        sess = Session(model, weights, max_sentences=8, n_pipes=pipes)
+        dbs = [sess.to_device(b) for b in batches]
+        res = [sess.update(dbs, 64.0, 5e-4, t) for t in (1, 2)]
+        outs.append((res, host(sess.acc).copy(), host(sess.master).copy(), host(sess.w16).copy(), host(sess.m).copy()))
+        sess.close()
+    for other in outs[1:]:
+        assert other[0] == outs[0][0]
+        for a, b in zip(other[1:], outs[0][1:]):
+            assert (a == b).all()
