@@ -73,7 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="big_accum", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pipes", type=int, default=2, help="sub-batches kept in flight on separate streams")
+    ap.add_argument("--pipes", type=int, default=3, help="sub-batches kept in flight on separate streams")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -155,7 +155,7 @@ def main():
         result["roofline"]["gemm"] = gemm_leg(model, shapes, k_micro, A, torch, log)
         result["hbm_kernels"] = hbm_leg(sess, torch)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(model, weights, batches[len(batches) // 2], k_micro, tokens_per_step, log)
+        result["cpu_baseline"] = cpu_baseline(model, weights, batches[len(batches) // 2], k_micro, tokens_per_step, tr.scale, log)
     sess.close()
     print(json.dumps(result))
 
@@ -261,7 +261,7 @@ def hbm_leg(sess, torch):
     return out
 
 
-def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, log):
+def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, loss_scale, log):
     """The fp64 numpy oracle timed on the host cores: forward + backward + fp16 rounding + accumulate
     on the first 24 sentences of one sub-batch, and overflow check + Adam over all parameters once;
     scaled to a whole update."""
@@ -281,12 +281,12 @@ def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, log):
     P16 = {k: v.astype(np.float64) for k, v in weights.items()}
     t0 = time.perf_counter()
     loss, n, cache = O.forward_loss(P16, cfg, sub["src"], sub["tgt_in"], sub["tgt_out"], step=1, micro=0)
-    g = O.to_fp16_storage(O.backward(P16, cfg, cache, 128.0))
+    g = O.to_fp16_storage(O.backward(P16, cfg, cache, loss_scale))
     acc = O.accumulate(None, g, True)
     t_micro = time.perf_counter() - t0
     del cache, g
     t0 = time.perf_counter()
-    flag, un = O.check_overflow(acc, 1.0 / (128.0 * n))
+    flag, un = O.check_overflow(acc, 1.0 / (loss_scale * n))
     m = {k: np.zeros_like(v) for k, v in P16.items()}
     v = {k: np.zeros_like(val) for k, val in P16.items()}
     O.adam_step(P16, m, v, un, 1e-3, 0.9, 0.98, 1e-8, 1, flag)
@@ -294,7 +294,7 @@ def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, log):
     per_token = t_micro / ntok
     total = per_token * tokens_per_update + t_update
     val = tokens_per_update / total
-    log(f"[bench] oracle: {t_micro:.1f}s for {ntok} tokens, {t_update:.1f}s for overflow check + Adam; {val:.1f} tok/s on {cores} threads")
+    log(f"[bench] oracle: {t_micro:.1f}s for {ntok} tokens, {t_update:.1f}s for overflow check + Adam (flag {flag}); {val:.1f} tok/s on {cores} threads")
     return {"value": val, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"fp64 numpy oracle: forward+backward+fp16 rounding+accumulate on the first {nb} sentences ({ntok} target tokens) of one "
                       f"sub-batch ({t_micro:.1f} s), overflow check + Adam over all parameters once ({t_update:.1f} s), scaled to one update of "
