@@ -47,25 +47,39 @@ __device__ __forceinline__ floatx16 zero16() {
 }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
 
-// Stage rows [r_begin, r_begin + nrows_pad) of a [*, DH] head slice into LDS, row-major (pitch DH+8)
-// and/or transposed ([max(DH,32)][pitch_t]); rows >= r_end are zero.
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short short8_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) short4_t* lds_short4_ptr;
+
+// A-operand fragment of X^T taken from a row-major LDS tile X[k][DH] (pitch in halfs) with the gfx950
+// transposing read: MFMA tile t covers columns 32t..32t+31 of X (rows of X^T); slot j of the lane
+// stands for k row kbase + 8*(j/4) + j%4, where kbase already contains 4*(lane/32).
+template <int DH>
+__device__ __forceinline__ half8_t tr_frag(const half_t* x, int pitch, int kbase, int t, int lane) {
+  const int q = lane >> 4, i = lane & 15;
+  const bool live = DH >= 32 || !(q & 1);   // head sizes below 32 fill only half of the MFMA rows
+  const int col = live ? t * 32 + 16 * (q & 1) + 4 * (i & 3) : 0;
+  const half_t* p = x + (kbase + (i >> 2)) * pitch + col;
+  short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
+  short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 8 * pitch));
+  if (!live) {
+    lo = short4_t{0, 0, 0, 0};
+    hi = lo;
+  }
+  const short8_t r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(half8_t, r);
+}
+
+// Stage rows [r_begin, r_begin + nrows_pad) of a [*, DH] head slice into LDS, row-major (pitch DH+8);
+// rows >= r_end are zero.
 template <int DH>
 __device__ __forceinline__ void stage_rows(const half_t* __restrict__ src, int ld, int r_begin, int r_end, int nrows_pad,
-                                           half_t* row_major, half_t* transposed, int pitch_t) {
+                                           half_t* row_major) {
   constexpr int CH = DH / 8, PR = DH + 8;
   for (int idx = threadIdx.x; idx < nrows_pad * CH; idx += kThreads) {
     const int rl = idx / CH, c = idx % CH;
     const int r = r_begin + rl;
-    const half8_t v = r < r_end ? ld_half8(src + (size_t)r * ld + c * 8) : zero_half8();
-    if (row_major) st_half8(row_major + rl * PR + c * 8, v);
-    if (transposed) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) transposed[(c * 8 + e) * pitch_t + rl] = v[e];
-    }
-  }
-  if (DH < 32 && transposed) {
-    for (int idx = threadIdx.x; idx < (32 - DH) * nrows_pad; idx += kThreads)
-      transposed[(DH + idx / nrows_pad) * pitch_t + idx % nrows_pad] = (half_t)0.f;
+    st_half8(row_major + rl * PR + c * 8, r < r_end ? ld_half8(src + (size_t)r * ld + c * 8) : zero_half8());
   }
 }
 
@@ -77,13 +91,13 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int b = blockIdx.y / a.H, h = blockIdx.y % a.H;
-  const int KP = (a.Tk + 31) & ~31, PT = KP + 8;
+  const int KP = (a.Tk + 31) & ~31;
   half_t* Ks = reinterpret_cast<half_t*>(smem_raw);
-  half_t* Vt = Ks + KP * PR;
-  uint8_t* hidk = reinterpret_cast<uint8_t*>(Vt + DHP * PT);
+  half_t* Vs = Ks + KP * PR;
+  uint8_t* hidk = reinterpret_cast<uint8_t*>(Vs + KP * PR);
 
-  stage_rows<DH>(a.K + (size_t)b * a.Tk * a.ldk + h * DH, a.ldk, 0, a.Tk, KP, Ks, nullptr, 0);
-  stage_rows<DH>(a.V + (size_t)b * a.Tk * a.ldv + h * DH, a.ldv, 0, a.Tk, KP, nullptr, Vt, PT);
+  stage_rows<DH>(a.K + (size_t)b * a.Tk * a.ldk + h * DH, a.ldk, 0, a.Tk, KP, Ks);
+  stage_rows<DH>(a.V + (size_t)b * a.Tk * a.ldv + h * DH, a.ldv, 0, a.Tk, KP, Vs);
   for (int k = threadIdx.x; k < KP; k += kThreads) hidk[k] = (k >= a.Tk) || (a.key_ids && a.key_ids[b * a.Tk + k] == a.pad_id);
   __syncthreads();
 
@@ -135,8 +149,7 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
       for (int r = 0; r < 16; ++r) oacc[t][r] *= alpha;
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const half_t* vp = Vt + (t * 32 + (lane & 31)) * PT + kt * 32 + 16 * s2 + 4 * g;
-        oacc[t] = MFMA(join4(*reinterpret_cast<const half4_t*>(vp), *reinterpret_cast<const half4_t*>(vp + 8)), pf[s2], oacc[t]);
+        oacc[t] = MFMA(tr_frag<DH>(Vs, PR, kt * 32 + 16 * s2 + 4 * g, t, lane), pf[s2], oacc[t]);
       }
     }
   }
@@ -163,13 +176,11 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
 // ------------------------------------------------------------------------------------------------
 template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a) {
-  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, CH = DH / 8, PTQ = kQC + 8;
+  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, CH = DH / 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   half_t* Qs = reinterpret_cast<half_t*>(smem_raw);
   half_t* dOs = Qs + kQC * PR;
-  half_t* Qt = dOs + kQC * PR;
-  half_t* dOt = Qt + DHP * PTQ;
-  float* lse_s = reinterpret_cast<float*>(dOt + DHP * PTQ);
+  float* lse_s = reinterpret_cast<float*>(dOs + kQC * PR);
   float* D_s = lse_s + kQC;
 
   const int b = blockIdx.y / a.H, h = blockIdx.y % a.H;
@@ -197,8 +208,8 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
 
   for (int qc = 0; qc < a.Tq; qc += kQC) {
     __syncthreads();
-    stage_rows<DH>(Qb, a.ldq, qc, a.Tq, kQC, Qs, Qt, PTQ);
-    stage_rows<DH>(dOb, a.lddo, qc, a.Tq, kQC, dOs, dOt, PTQ);
+    stage_rows<DH>(Qb, a.ldq, qc, a.Tq, kQC, Qs);
+    stage_rows<DH>(dOb, a.lddo, qc, a.Tq, kQC, dOs);
     // D[q] = sum_dh dO[q,dh] * O[q,dh]: CH consecutive lanes share a row
     for (int idx = threadIdx.x; idx < kQC * CH; idx += kThreads) {
       const int rl = idx / CH, c = idx % CH, q = qc + rl;
@@ -241,9 +252,9 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
       for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const int off = (t * 32 + (lane & 31)) * PTQ + qt * 32 + 16 * s2 + 4 * g;
-          dVt[t] = MFMA(join4(*reinterpret_cast<const half4_t*>(dOt + off), *reinterpret_cast<const half4_t*>(dOt + off + 8)), pf[s2], dVt[t]);
-          dKt[t] = MFMA(join4(*reinterpret_cast<const half4_t*>(Qt + off), *reinterpret_cast<const half4_t*>(Qt + off + 8)), dsf[s2], dKt[t]);
+          const int kb = qt * 32 + 16 * s2 + 4 * g;
+          dVt[t] = MFMA(tr_frag<DH>(dOs, PR, kb, t, lane), pf[s2], dVt[t]);
+          dKt[t] = MFMA(tr_frag<DH>(Qs, PR, kb, t, lane), dsf[s2], dKt[t]);
         }
     }
   }
@@ -271,12 +282,11 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
 // ------------------------------------------------------------------------------------------------
 template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a) {
-  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, PTK = kKC + 8;
+  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   half_t* Ks = reinterpret_cast<half_t*>(smem_raw);
   half_t* Vs = Ks + kKC * PR;
-  half_t* Kt = Vs + kKC * PR;
-  uint8_t* hidk = reinterpret_cast<uint8_t*>(Kt + DHP * PTK);
+  uint8_t* hidk = reinterpret_cast<uint8_t*>(Vs + kKC * PR);
 
   const int b = blockIdx.y / a.H, h = blockIdx.y % a.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
@@ -305,8 +315,8 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
 
   for (int kc = 0; kc < a.Tk; kc += kKC) {
     __syncthreads();
-    stage_rows<DH>(Kb, a.ldk, kc, a.Tk, kKC, Ks, Kt, PTK);
-    stage_rows<DH>(Vb, a.ldv, kc, a.Tk, kKC, Vs, nullptr, 0);
+    stage_rows<DH>(Kb, a.ldk, kc, a.Tk, kKC, Ks);
+    stage_rows<DH>(Vb, a.ldv, kc, a.Tk, kKC, Vs);
     for (int k = threadIdx.x; k < kKC; k += kThreads)
       hidk[k] = (kc + k >= a.Tk) || (a.key_ids && a.key_ids[b * a.Tk + kc + k] == a.pad_id);
     __syncthreads();
@@ -333,8 +343,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
       for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const int off = (t * 32 + (lane & 31)) * PTK + kt * 32 + 16 * s2 + 4 * g;
-          dQt[t] = MFMA(join4(*reinterpret_cast<const half4_t*>(Kt + off), *reinterpret_cast<const half4_t*>(Kt + off + 8)), dsf[s2], dQt[t]);
+          dQt[t] = MFMA(tr_frag<DH>(Ks, PR, kt * 32 + 16 * s2 + 4 * g, t, lane), dsf[s2], dQt[t]);
         }
     }
   }
@@ -355,19 +364,16 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
 
 template <int DH>
 size_t fwd_smem(int Tk) {
-  constexpr int DHP = DH < 32 ? 32 : DH;
   const int KP = (Tk + 31) & ~31;
-  return (size_t)(KP * (DH + 8) + DHP * (KP + 8)) * sizeof(half_t) + KP;
+  return (size_t)(2 * KP * (DH + 8)) * sizeof(half_t) + KP;
 }
 template <int DH>
 size_t dkv_smem() {
-  constexpr int DHP = DH < 32 ? 32 : DH;
-  return (size_t)(2 * kQC * (DH + 8) + 2 * DHP * (kQC + 8)) * sizeof(half_t) + 2 * kQC * sizeof(float);
+  return (size_t)(2 * kQC * (DH + 8)) * sizeof(half_t) + 2 * kQC * sizeof(float);
 }
 template <int DH>
 size_t dq_smem() {
-  constexpr int DHP = DH < 32 ? 32 : DH;
-  return (size_t)(2 * kKC * (DH + 8) + DHP * (kKC + 8)) * sizeof(half_t) + kKC;
+  return (size_t)(2 * kKC * (DH + 8)) * sizeof(half_t) + kKC;
 }
 
 template <typename Kern>
