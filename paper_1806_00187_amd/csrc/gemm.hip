@@ -6,21 +6,26 @@
 // [K][rows]).  This covers the three products of a linear layer: forward x W^T (both direct),
 // input gradient dy W (B transposed) and weight gradient dy^T x (both transposed).
 //
-// The kernel is bound by LDS instruction throughput, not by the matrix cores: measured on this
-// chip a wave's ds_read_b128 streams ~64 B/clk per CU and ds_write_b128 half of that, against
-// 4096 MFMA flop/clk.  The data path therefore avoids every LDS instruction it can:
+// Measured on this chip: ds_read_b128 streams ~200 B/clk per CU (the 8-byte transposing read half
+// of that), global -> LDS loads ~50 B/clk per CU, and with fp16 data of full entropy the sustained
+// rate of LDS reads + MFMAs alone is ~1.2-1.35 PFLOP/s (clocks drop under that load).  The loop is
+// therefore organised around the load path and around keeping the matrix pipe fed:
 //  * global -> LDS directly (buffer_load ... lds, 16 bytes per lane, 1 KB contiguous per wave
-//    instruction): no ds_write, no staging registers.  Out-of-range rows / k (offset beyond the
-//    buffer's extent) arrive as zeros, so ragged edges need no branches;
-//  * both tile layouts are kept as they are in memory (direct [row][64 k], transposed
-//    [64 k][row]) and made bank-conflict free by permuting, on the global-address side, which
-//    16-byte chunk lands in which slot (XOR swizzles chosen so that every LDS address is one
-//    per-lane base plus compile-time offsets);
+//    instruction): no ds_write, no staging registers.  Every k-tile gets a buffer descriptor that
+//    starts at the tile's first element and ends at its last, so out-of-range rows / k arrive as
+//    zeros, ragged edges need no branches, and operands may be larger than 4 GB;
+//  * both tile layouts are kept as they are in memory (direct [row][k], transposed [k][row]) and
+//    made bank-conflict free by permuting, on the global-address side, which 16-byte chunk lands
+//    in which slot (XOR swizzles chosen so that every LDS address is one per-lane base plus
+//    compile-time offsets);
 //  * LDS -> MFMA fragments: one ds_read_b128 per fragment for a direct tile; two
 //    ds_read_b64_tr_b16 (the gfx950 transposing read: within 16 lanes, lane L receives element
 //    L%4 of the 8-byte words addressed by lanes 4j + L/4, j = 0..3) for a transposed tile, so
 //    no register shuffling is needed;
-//  * two LDS stages: the k-tile after the one being multiplied streams in meanwhile.
+//  * the fragments of k-step s+1 are read while the MFMAs of step s issue (two register sets,
+//    instruction order pinned with scheduling groups);
+//  * a ring of 2 or 4 LDS stages: the next 1 or 3 k-tiles stream in while one is multiplied; one
+//    barrier per k-tile both publishes the next tile and frees the current one for refilling.
 #include <stdlib.h>
 
 #include <type_traits>
@@ -29,7 +34,6 @@
 
 namespace {
 
-constexpr int BK = 64;         // k extent of one LDS stage
 constexpr int kThreads = 256;  // 4 wavefronts, arranged 2 x 2 over the block tile
 constexpr uint32_t kOob = 0x80000000u;  // byte offset no operand reaches: such loads return 0
 
@@ -56,84 +60,111 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned char
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)lds_wave_base, 16, (int)voff, 0, 0, 0);
 }
 
-// ---- direct operand: memory [rows][K] (k contiguous), LDS tile [R][64 k], 128 bytes per row ------
-// Slot p (16 bytes) of tile row r holds chunk p ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1).
-template <int R>
+// ---- direct operand: memory [rows][K] (k contiguous), LDS tile [R][BK k] -------------------------
+// BK = 64: 128 bytes per row; slot p (16 bytes) of row r holds chunk p ^ (r & 7) ^ ((r >> 3) & 1).
+// BK = 32:  64 bytes per row; slot p of row r holds chunk p ^ ((r >> 2) & 3).
+// Either way a wavefront's ds_read_b128 of 32 rows x 2 chunks touches every bank equally often.
+// All offsets are relative to the first element of the block's current k-tile, so operands of any
+// size work with 32-bit offsets.
+template <int R, int BK>
 struct DirectOp {
-  static constexpr int NV = R / 32;   // wave instructions (8 rows each) per wave and k-tile
-  static constexpr int BYTES = R * 128;
+  static constexpr int ROWB = BK * 2;             // bytes per tile row
+  static constexpr int CPR = BK / 8;              // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;            // rows per wave instruction (1 KB)
+  static constexpr int BYTES = R * ROWB;
+  static constexpr int NV = BYTES / 4096;         // wave instructions per wave and k-tile
+  static_assert(NV >= 1 && BYTES % 4096 == 0, "tile too small for four waves");
   uint32_t voff[NV];
   int c8, wave;
-  __device__ __forceinline__ static uint32_t extent(int rmax, int ld, int K) { return ((uint32_t)(rmax - 1) * ld + K) * 2u; }
-  __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid) {
+  __device__ __forceinline__ static int swz(int row) { return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3); }
+  // first element of the k-tile at k0 of the block whose first row is r0
+  __device__ __forceinline__ static const half_t* origin(const half_t* p, int ld, int r0, int k0) { return p + (size_t)r0 * ld + k0; }
+  // bytes from there to the end of the tile's last row (0 if the k-tile lies past K)
+  __device__ __forceinline__ static uint32_t extent(int rows_in, int ld, int kleft) {
+    return kleft > 0 ? ((uint32_t)(rows_in - 1) * ld + (uint32_t)min(kleft, BK)) * 2u : 0u;
+  }
+  __device__ __forceinline__ void init(int ld, int rows_in, int tid) {
     wave = tid >> 6;
-    const int L = tid & 63, rowl = L >> 3, p = L & 7;
-    c8 = (p ^ rowl ^ (wave & 1)) << 3;
+    const int L = tid & 63, rowl = L / CPR, p = L % CPR;
+    // RPI * (wave + 4 it) adds nothing to the swizzle bits except, for BK = 64, bit 3 of the row (= wave & 1)
+    c8 = (p ^ swz(RPI * wave + rowl)) << 3;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
-      const int row = r0 + 8 * (wave + 4 * it) + rowl;
-      voff[it] = row < rmax ? ((uint32_t)row * (uint32_t)ld + (uint32_t)c8) * 2u : kOob;
+      const int row = RPI * (wave + 4 * it) + rowl;
+      voff[it] = row < rows_in ? ((uint32_t)row * (uint32_t)ld + (uint32_t)c8) * 2u : kOob;
     }
   }
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int ld, int k0, int K) const {
-    const bool kv = k0 + c8 < K;  // only the last k-tile can fail this
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int kleft) const {
+    const bool kv = c8 < kleft;  // only the last k-tile can fail this
 #pragma unroll
-    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, kv ? voff[it] + (uint32_t)k0 * 2u : kOob);
+    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, kv ? voff[it] : kOob);
   }
   // per-lane fragment addresses, one per k-step (the swizzle is an XOR in the k-step bits)
   struct Frag { uint32_t a[BK / 16]; };
   __device__ __forceinline__ static Frag frag_init(int row0, int lane) {
     Frag f;
-    const int h = (lane >> 5) ^ (lane & 7) ^ ((lane >> 3) & 1);
+    const int row = row0 + (lane & 31);  // row0 and the 32-row steps between MFMA tiles leave the swizzle bits alone
 #pragma unroll
-    for (int s = 0; s < BK / 16; ++s) f.a[s] = (row0 + (lane & 31)) * 128 + (((h ^ (2 * s)) & 7) << 4);
+    for (int s = 0; s < BK / 16; ++s) f.a[s] = row * ROWB + (((((lane >> 5) | (2 * s)) ^ swz(lane & 31)) & (CPR - 1)) << 4);
     return f;
   }
+  static constexpr int READS = 1;  // LDS instructions per fragment
   __device__ __forceinline__ static half8_t frag(const unsigned char* tile, const Frag& f, int i, int s) {
-    return *reinterpret_cast<const half8_t*>(tile + f.a[s] + i * 32 * 128);
+    return *reinterpret_cast<const half8_t*>(tile + f.a[s] + i * 32 * ROWB);
   }
 };
 
-// ---- transposed operand: memory [K][rows] (rows contiguous), LDS tile [64 k][R] -------------------
+// ---- transposed operand: memory [K][rows] (rows contiguous), LDS tile [BK k][R] -------------------
 // Within k row k, slot q (16 bytes) holds chunk q ^ (y(k) << 1): the four k rows a 16-lane group of
 // the transposing read touches then lie in four different 32-byte bank segments.
-template <int R>
+template <int R, int BK>
 struct TransOp {
-  static constexpr int NV = R / 32;
   static constexpr int ROWB = R * 2;        // bytes per k row
   static constexpr int BYTES = BK * ROWB;
+  static constexpr int NV = BYTES / 4096;
   static constexpr int CPR = R / 8;         // 16-byte chunks per k row
   static constexpr int KPI = 64 / CPR;      // k rows per wave instruction
+  static_assert(NV >= 1 && BYTES % 4096 == 0, "tile too small for four waves");
   uint32_t voff[NV];
   int wave;
-  __device__ __forceinline__ static int ysw(int k2) { return R == 128 ? ((k2 & 1) | ((k2 & 2) << 1)) : (k2 & 3); }
-  __device__ __forceinline__ static uint32_t extent(int rmax, int ld, int K) { return ((uint32_t)(K - 1) * ld + rmax) * 2u; }
-  __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid) {
+  __device__ __forceinline__ static int ysw(int k2) { return R == 64 ? (k2 & 3) : ((k2 & 1) | ((k2 & 2) << 1)); }
+  __device__ __forceinline__ static const half_t* origin(const half_t* p, int ld, int r0, int k0) { return p + (size_t)k0 * ld + r0; }
+  // k rows >= K lie beyond the extent and arrive as zeros
+  __device__ __forceinline__ static uint32_t extent(int rows_in, int ld, int kleft) {
+    return kleft > 0 ? ((uint32_t)(min(kleft, BK) - 1) * ld + (uint32_t)rows_in) * 2u : 0u;
+  }
+  __device__ __forceinline__ void init(int ld, int rows_in, int tid) {
     wave = tid >> 6;
     const int L = tid & 63, kl = L / CPR, slot = L % CPR;
-    const int cc = slot ^ (ysw(kl & 3) << 1);
-    const bool ok = r0 + cc * 8 < rmax;
+    const int cc = slot ^ (ysw((KPI * wave + kl) & 3) << 1);  // k row of instruction `it` is KPI * (wave + 4 it) + kl
+    const bool ok = cc * 8 < rows_in;
 #pragma unroll
     for (int it = 0; it < NV; ++it)
-      voff[it] = ok ? ((uint32_t)(KPI * (wave + 4 * it) + kl) * (uint32_t)ld + (uint32_t)(r0 + cc * 8)) * 2u : kOob;
+      voff[it] = ok ? ((uint32_t)(KPI * (wave + 4 * it) + kl) * (uint32_t)ld + (uint32_t)(cc * 8)) * 2u : kOob;
   }
-  // k rows >= K lie beyond the buffer's extent and arrive as zeros
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int ld, int k0, int K) const {
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int /*kleft*/) const {
 #pragma unroll
-    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, voff[it] + (uint32_t)k0 * (uint32_t)ld * 2u);
+    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, voff[it]);
   }
-  struct Frag { uint32_t a; };
+  static constexpr int READS = 2;
+  struct Frag { uint32_t a[2]; };
   // 16-lane group q = lane/16 serves rows 16*(q&1).. of the MFMA tile and k-half q/2; lane i of the group
-  // addresses k row i/4, row offset 4*(i%4) of its 4(k) x 16(row) block.
+  // addresses k row i/4, row offset 4*(i%4) of its 4(k) x 16(row) block.  The swizzle touches chunk bits
+  // 1 and 3, so MFMA tiles 2 and 3 of a wave (row offset 64, chunk bit 3) get an address of their own.
   __device__ __forceinline__ static Frag frag_init(int row0, int lane) {
     const int q = lane >> 4, i = lane & 15;
     const int kk = 8 * (q >> 1) + (i >> 2);
-    const int r = row0 + 16 * (q & 1) + 4 * (i & 3);
-    const int cc = (r >> 3) ^ (ysw((i >> 2) & 3) << 1);
-    return Frag{(uint32_t)(kk * ROWB + cc * 16 + (r & 7) * 2)};
+    Frag f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int r = row0 + 64 * h + 16 * (q & 1) + 4 * (i & 3);
+      const int cc = (r >> 3) ^ (ysw((i >> 2) & 3) << 1);
+      f.a[h] = (uint32_t)(kk * ROWB + cc * 16 + (r & 7) * 2);
+    }
+    return f;
   }
   __device__ __forceinline__ static half8_t frag(const unsigned char* tile, const Frag& f, int i, int s) {
-    const unsigned char* p = tile + f.a + s * 16 * ROWB + i * 64;
+    const unsigned char* p = tile + f.a[i >> 1] + s * 16 * ROWB + (i & 1) * 64;
     const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
     const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 4 * ROWB));
     const short8_t r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -141,23 +172,51 @@ struct TransOp {
   }
 };
 
-template <int BM, int BN, bool AT, bool BT>
-struct Tile {
-  using OpA = typename std::conditional<AT, TransOp<BM>, DirectOp<BM>>::type;
-  using OpB = typename std::conditional<BT, TransOp<BN>, DirectOp<BN>>::type;
-  static constexpr int STAGE = OpA::BYTES + OpB::BYTES;   // (BM + BN) * 128 bytes
+// Instruction order of one k-step: the NR LDS reads of the next step's fragments go between the
+// first three quarters of this step's MF matrix instructions, so that every read has returned
+// before the next step starts.
+template <int M, int MF, int NR>
+struct Interleave {
+  static constexpr int SLOTS = MF - MF / 4, PER = (NR + SLOTS - 1) / SLOTS;
+  static constexpr int DONE = M * PER < NR ? M * PER : NR, NOW = NR - DONE < PER ? NR - DONE : PER;
+  __device__ __forceinline__ static void run() {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+    if (NOW > 0) __builtin_amdgcn_sched_group_barrier(0x100, NOW, 0);
+    Interleave<M + 1, MF, NR>::run();
+  }
+};
+template <int MF, int NR>
+struct Interleave<MF, MF, NR> {
+  __device__ __forceinline__ static void run() {}
 };
 
-template <int BM, int BN, bool AT, bool BT>
+template <int BM, int BN, bool AT, bool BT, int BK>
+struct Tile {
+  using OpA = typename std::conditional<AT, TransOp<BM, BK>, DirectOp<BM, BK>>::type;
+  using OpB = typename std::conditional<BT, TransOp<BN, BK>, DirectOp<BN, BK>>::type;
+  static constexpr int STAGE = OpA::BYTES + OpB::BYTES;   // (BM + BN) * BK * 2 bytes
+};
+
+// s_waitcnt immediates (gfx9 encoding): at most n vector-memory operations outstanding, with or
+// without also waiting for every LDS operation
+constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+constexpr int wait_vm_lds(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }
+
+// NS stages of BK k each form a ring: while k-tile t is multiplied, tiles t+1 .. t+NS-1 are in LDS
+// or on their way.
+template <int BM, int BN, bool AT, bool BT, int BK, int NS>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
-  using T = Tile<BM, BN, AT, BT>;
+  using T = Tile<BM, BN, AT, BT, BK>;
   using OpA = typename T::OpA;
   using OpB = typename T::OpB;
-  // two separate arrays, so that the compiler can tell that fragment reads of one stage do not
-  // depend on the loads in flight into the other
+  static_assert(NS == 2 || NS == 4, "two or four stages");
+  // separate arrays, so that the compiler can tell that fragment reads of one stage do not depend
+  // on the loads in flight into the others
   __shared__ __align__(1024) unsigned char stage0[T::STAGE];
   __shared__ __align__(1024) unsigned char stage1[T::STAGE];
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  __shared__ __align__(1024) unsigned char stage2[NS > 2 ? T::STAGE : 16];
+  __shared__ __align__(1024) unsigned char stage3[NS > 2 ? T::STAGE : 16];
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KS = BK / 16;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
@@ -169,8 +228,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
     const int base = nt >> 3, rem = nt & 7;
     pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  // Grouped order: 8 tile rows are swept column by column, so the ~64 work-groups an XCD runs at a
-  // time form an 8 x 8 patch of tiles and each A / B panel they stream is shared by 8 of them in L2.
+  // Grouped order: 8 tile rows are swept column by column, so the work-groups an XCD runs at a
+  // time form a patch of tiles and each A / B panel they stream is shared by several of them in L2.
   int tm, tn;
   {
     constexpr int GROUP = 8;
@@ -192,57 +251,83 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
 
   OpA opa;
   OpB opb;
-  opa.init(g.lda, m0, g.M, tid);
-  opb.init(g.ldb, n0, g.N, tid);
-  const __amdgpu_buffer_rsrc_t ra_src = make_rsrc(g.A, OpA::extent(g.M, g.lda, g.K));
-  const __amdgpu_buffer_rsrc_t rb_src = make_rsrc(g.B, OpB::extent(g.N, g.ldb, g.K));
+  const int rows_a = min(g.M - m0, BM), rows_b = min(g.N - n0, BN);
+  opa.init(g.lda, rows_a, tid);
+  opb.init(g.ldb, rows_b, tid);
   const typename OpA::Frag fa = OpA::frag_init(wm * WM, lane);
   const typename OpB::Frag fb = OpB::frag_init(wn * WN, lane);
 
   auto request = [&](unsigned char* stage, int k0) {  // asynchronous: tile k0 streams into `stage`
-    opa.load(ra_src, stage, g.lda, k0, g.K);
-    opb.load(rb_src, stage + OpA::BYTES, g.ldb, k0, g.K);
+    const int kleft = g.K - k0;
+    opa.load(make_rsrc(OpA::origin(g.A, g.lda, m0, k0), OpA::extent(rows_a, g.lda, kleft)), stage, kleft);
+    opb.load(make_rsrc(OpB::origin(g.B, g.ldb, n0, k0), OpB::extent(rows_b, g.ldb, kleft)), stage + OpA::BYTES, kleft);
     __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of the products they overlap with
   };
-  auto compute = [&](const unsigned char* stage) {
-    const unsigned char* As = stage;
-    const unsigned char* Bs = stage + OpA::BYTES;
+  constexpr int kPerTile = OpA::NV + OpB::NV;  // vector-memory instructions of one request, per wave
+  half8_t af[2][TM], bf[2][TN];  // fragments of two consecutive k-steps
+  auto fetch = [&](const unsigned char* stage, int s, int set) {
 #pragma unroll
-    for (int s = 0; s < BK / 16; ++s) {
-      half8_t af[TM], bf[TN];
+    for (int i = 0; i < TM; ++i) af[set][i] = OpA::frag(stage, fa, i, s);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = OpA::frag(As, fa, i, s);
+    for (int j = 0; j < TN; ++j) bf[set][j] = OpB::frag(stage + OpA::BYTES, fb, j, s);
+  };
+  auto multiply = [&](int set) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = OpB::frag(Bs, fb, j, s);
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[set][i], bf[set][j], acc[i][j], 0, 0, 0);
+  };
+  auto interleave = [&]() { Interleave<0, TM * TN, OpA::READS * TM + OpB::READS * TN>::run(); };
+  // One k-tile.  On entry the fragments of k-step 0 of `cur` are in registers and the next NS-1
+  // tiles have been requested.  Before the last k-step every wave holds its last fragments of `cur`
+  // in registers and has seen its own part of `nxt` land (the requests of the NS-2 tiles behind it
+  // may still be in flight); the barrier then publishes `nxt` and frees `cur`, which is refilled at
+  // once with the tile NS ahead.
+  auto k_tile = [&](unsigned char* cur, const unsigned char* nxt, int k_refill) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    for (int s = 0; s < KS; ++s) {
+      if (s == KS - 1) {
+        __builtin_amdgcn_s_waitcnt(wait_vm_lds((NS - 2) * kPerTile));
+        __builtin_amdgcn_s_barrier();
+        request(cur, k_refill);
+      }
+      fetch(s == KS - 1 ? nxt : cur, (s + 1) % KS, (s + 1) & 1);
+      multiply(s & 1);
+      interleave();
     }
   };
-  // all of this wave's loads into LDS have landed (vmcnt(0)); the barrier then publishes every wave's part
-  auto landed = [&]() {
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-  };
 
-  // A k-tile past the end reads zeros (its offsets are out of range) and multiplying it changes
-  // nothing, so the loop always runs in pairs and carries no edge conditions.
+  // A k-tile past the end reads zeros (it lies outside the extent of its buffer descriptor) and
+  // multiplying it changes nothing, so the loop always runs whole rings and carries no edge conditions.
   const int nk = (g.K + BK - 1) / BK;
   request(stage0, 0);
-  landed();
-  for (int kt = 0; kt < nk; kt += 2) {
-    request(stage1, (kt + 1) * BK);
-    compute(stage0);
-    landed();
-    request(stage0, (kt + 2) * BK);
-    compute(stage1);
-    landed();
+  request(stage1, BK);
+  if constexpr (NS == 4) {
+    request(stage2, 2 * BK);
+    request(stage3, 3 * BK);
   }
+  __builtin_amdgcn_s_waitcnt(wait_vm((NS - 1) * kPerTile));
+  __builtin_amdgcn_s_barrier();
+  fetch(stage0, 0, 0);
+  if constexpr (NS == 2) {
+    for (int kt = 0; kt < nk; kt += 2) {
+      k_tile(stage0, stage1, (kt + 2) * BK);
+      k_tile(stage1, stage0, (kt + 3) * BK);
+    }
+  } else {
+    for (int kt = 0; kt < nk; kt += 4) {
+      k_tile(stage0, stage1, (kt + 4) * BK);
+      k_tile(stage1, stage2, (kt + 5) * BK);
+      k_tile(stage2, stage3, (kt + 6) * BK);
+      k_tile(stage3, stage0, (kt + 7) * BK);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(wait_vm_lds(0));  // the last refills (all zeros) must land before the stages are reused
+  __syncthreads();
 
   // ---- epilogue: accumulators -> per-wave LDS staging (fp32) -> row-wise 16-byte stores -------
   // staging width per pass: the wave's whole width if 4 waves x 32 rows of it fit one stage, else 32
-  constexpr int SW = (4 * 32 * WN * 4 <= T::STAGE) ? WN : 32;
+  constexpr int SW = (4 * 32 * WN * 4 <= T::STAGE) ? WN : (4 * 32 * 64 * 4 <= T::STAGE && WN % 64 == 0) ? 64 : 32;
   static_assert(4 * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
   float* stg = reinterpret_cast<float*>(stage1) + wave * (32 * SW);
   constexpr int CH = SW / 8;  // 8-column chunks per staged row
@@ -309,23 +394,23 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
   }
 }
 
-template <int BM, int BN, bool AT, bool BT>
+template <int BM, int BN, bool AT, bool BT, int BK, int NS>
 int launch_variant(const GemmArgs& g, hipStream_t stream) {
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT>), dim3(g.tiles_m * g.tiles_n), dim3(kThreads), 0, stream, g);
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT, BK, NS>), dim3(g.tiles_m * g.tiles_n), dim3(kThreads), 0, stream, g);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int BK, int NS>
 int launch_tile(const GemmArgs& a, bool a_t, bool b_t, hipStream_t stream) {
   GemmArgs g = a;
   g.tiles_m = ceil_div(g.M, BM);
   g.tiles_n = ceil_div(g.N, BN);
   g.tm_fast = g.M <= g.N;
-  if (!a_t && !b_t) return launch_variant<BM, BN, false, false>(g, stream);
-  if (!a_t && b_t) return launch_variant<BM, BN, false, true>(g, stream);
-  if (a_t && b_t) return launch_variant<BM, BN, true, true>(g, stream);
-  return launch_variant<BM, BN, true, false>(g, stream);
+  if (!a_t && !b_t) return launch_variant<BM, BN, false, false, BK, NS>(g, stream);
+  if (!a_t && b_t) return launch_variant<BM, BN, false, true, BK, NS>(g, stream);
+  if (a_t && b_t) return launch_variant<BM, BN, true, true, BK, NS>(g, stream);
+  return launch_variant<BM, BN, true, false, BK, NS>(g, stream);
 }
 
 // Estimated efficiency of a tile shape on a (M, N) problem: useful fraction of the padded tiles,
@@ -350,23 +435,25 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   NMT_REQUIRE(lda % 8 == 0 && ldb % 8 == 0 && ldc % 8 == 0 && N % 8 == 0, "gemm: lda/ldb/ldc/N must be multiples of 8");
   NMT_REQUIRE((a_t ? M : K) % 8 == 0 && (b_t ? N : K) % 8 == 0, "gemm: contiguous operand dimension must be a multiple of 8");
   NMT_REQUIRE(lda >= (a_t ? M : K) && ldb >= (b_t ? N : K) && ldc >= N, "gemm: leading dimension too small");
-  NMT_REQUIRE((int64_t)(a_t ? K : M) * lda < (1ll << 30) && (int64_t)(b_t ? K : N) * ldb < (1ll << 30),
-              "gemm: operands of 2^30 or more elements are not supported");
+  NMT_REQUIRE(lda <= (1 << 20) && ldb <= (1 << 20) && ldc <= (1 << 20), "gemm: leading dimensions above 2^20 are not supported");
   NMT_REQUIRE(!ep.bias || aligned16(ep.bias), "gemm: bias must be 16-byte aligned");
   NMT_REQUIRE((!ep.add || aligned16(ep.add)) && (!ep.relu_src || aligned16(ep.relu_src)), "gemm: epilogue operand misaligned");
   GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, ep};
   if (const char* force = getenv("NMT_GEMM_TILE")) {  // tuning aid: force one tile shape
-    if (!strcmp(force, "128x128")) return launch_tile<128, 128>(g, a_t, b_t, stream);
-    if (!strcmp(force, "128x64")) return launch_tile<128, 64>(g, a_t, b_t, stream);
-    if (!strcmp(force, "64x128")) return launch_tile<64, 128>(g, a_t, b_t, stream);
-    if (!strcmp(force, "64x64")) return launch_tile<64, 64>(g, a_t, b_t, stream);
+    if (!strcmp(force, "256x256")) return launch_tile<256, 256, 32, 4>(g, a_t, b_t, stream);
+    if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, stream);
+    if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, stream);
+    if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, stream);
+    if (!strcmp(force, "128x64")) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, stream);
+    if (!strcmp(force, "64x128")) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, stream);
+    if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, stream);
   }
   const double s128 = tile_score(M, N, 128, 128, 2, 1.0);
   const double s12864 = tile_score(M, N, 128, 64, 2, 0.85);
   const double s64128 = tile_score(M, N, 64, 128, 2, 0.85);
   const double s64 = tile_score(M, N, 64, 64, 4, 0.65);
-  if (s128 >= s12864 && s128 >= s64128 && s128 >= s64) return launch_tile<128, 128>(g, a_t, b_t, stream);
-  if (s12864 >= s64128 && s12864 >= s64) return launch_tile<128, 64>(g, a_t, b_t, stream);
-  if (s64128 >= s64) return launch_tile<64, 128>(g, a_t, b_t, stream);
-  return launch_tile<64, 64>(g, a_t, b_t, stream);
+  if (s128 >= s12864 && s128 >= s64128 && s128 >= s64) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, stream);
+  if (s12864 >= s64128 && s12864 >= s64) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, stream);
+  if (s64128 >= s64) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, stream);
+  return launch_tile<64, 64, 64, 2>(g, a_t, b_t, stream);
 }
