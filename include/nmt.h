@@ -88,7 +88,28 @@ int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_t* d_tgt_in
                      uint32_t step, uint32_t micro_idx, const uint32_t* d_sent_uid, int32_t training,
                      float* d_loss_sum, int32_t* d_ntok, void* stream);
 
-/* Backward pass in fp16 of the last nmt_forward_loss; writes every element of g16 with the
+/* The same for a group of n_seg (1 .. NMT_MAX_SEGMENTS) sub-batches of different padded shapes in
+ * one pass ("Training with Larger Batches": the gradients of the sub-batches of one update are
+ * summed; here the sum over the sub-batches of a group is already formed, in fp32, inside the
+ * weight-gradient products of the one backward pass that follows, before the gradient is rounded
+ * to fp16).  segs (host, read before the call returns) gives every sub-batch's B, S, T and micro
+ * index; the id buffers hold the sub-batches one after another (d_src: sum of B*S ids, d_tgt_in /
+ * d_tgt_out: sum of B*T ids) and d_sent_uid one entry per sentence in the same order (NULL: a
+ * sentence's index within its sub-batch).  Dropout masks, loss and gradients are those of the
+ * sub-batches processed one by one and accumulated.  *d_loss_sum and *d_ntok are totals over the
+ * group.  A group may hold at most 2^20 source and 2^20 target positions. */
+#define NMT_MAX_SEGMENTS 64
+typedef struct {
+  int32_t B, S, T;    /* sentences, padded source and target length */
+  uint32_t micro_idx; /* index of the sub-batch within its update (< 256): selects its dropout streams */
+} nmt_segment;
+int64_t nmt_workspace_bytes_group(const nmt_ctx* ctx, int32_t n_seg, const nmt_segment* segs /*host*/);
+int nmt_forward_loss_group(nmt_ctx* ctx, int32_t n_seg, const nmt_segment* segs /*host*/, const int32_t* d_src,
+                           const int32_t* d_tgt_in, const int32_t* d_tgt_out, float loss_scale, uint32_t step,
+                           const uint32_t* d_sent_uid, int32_t training, float* d_loss_sum, int32_t* d_ntok,
+                           void* stream);
+
+/* Backward pass in fp16 of the last nmt_forward_loss / nmt_forward_loss_group; writes every element of g16 with the
  * gradient of loss_scale * loss_sum ("perform the backward pass as usual"). */
 int nmt_backward(nmt_ctx* ctx, void* stream);
 
@@ -147,8 +168,8 @@ int nmt_op_gemm(const void* d_A, int32_t a_t, int32_t lda, const void* d_B, int3
                 float mask_scale, void* stream);
 
 /* Masked multi-head attention forward.  Q [B*Tq, *] with row stride ldq (head h at columns
- * h*dh..), K, V [B*Tk, *]; O [B*Tq, *]; d_lse fp32 [B, H, Tq] = log-sum-exp of the scaled
- * scores.  Key j of sentence b is hidden iff d_key_ids[b*Tk + j] == pad_id, or causal != 0 and
+ * h*dh..), K, V [B*Tk, *]; O [B*Tq, *]; d_lse fp32 = log-sum-exp of the scaled
+ * scores, stored [H, B*Tq] (head-major).  Key j of sentence b is hidden iff d_key_ids[b*Tk + j] == pad_id, or causal != 0 and
  * j > query index.  Scores are scaled by 1/sqrt(dh). */
 int nmt_op_attention_fwd(const void* d_Q, int32_t ldq, const void* d_K, int32_t ldk, const void* d_V,
                          int32_t ldv, void* d_O, int32_t ldo, float* d_lse, const int32_t* d_key_ids,

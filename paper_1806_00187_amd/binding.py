@@ -31,8 +31,13 @@ class nmt_dropout(C.Structure):
                 ("n_pos", C.c_int32), ("d_sent_uid", C.c_void_p)]
 
 
+class nmt_segment(C.Structure):
+    _fields_ = [("B", C.c_int32), ("S", C.c_int32), ("T", C.c_int32), ("micro_idx", C.c_uint32)]
+
+
 _P, _I32, _I64, _F, _U32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_uint32
 _DP = C.POINTER(nmt_dropout)
+_SP = C.POINTER(nmt_segment)
 
 _SIGNATURES = {
     "nmt_last_error": (C.c_char_p, []),
@@ -42,8 +47,10 @@ _SIGNATURES = {
     "nmt_param_tensors": (_I32, [_P]),
     "nmt_param_info": (C.c_int, [_P, _I32, C.POINTER(C.c_char_p), C.POINTER(_I64), C.POINTER(_I32), C.POINTER(_I32)]),
     "nmt_workspace_bytes": (_I64, [_P, _I32, _I32, _I32]),
+    "nmt_workspace_bytes_group": (_I64, [_P, _I32, _SP]),
     "nmt_bind": (C.c_int, [_P, _P, _P, _P, _P, _P, _P, _P, _I64]),
     "nmt_forward_loss": (C.c_int, [_P, _P, _P, _P, _I32, _I32, _I32, _F, _U32, _U32, _P, _I32, _P, _P, _P]),
+    "nmt_forward_loss_group": (C.c_int, [_P, _I32, _SP, _P, _P, _P, _F, _U32, _P, _I32, _P, _P, _P]),
     "nmt_backward": (C.c_int, [_P, _P]),
     "nmt_accumulate": (C.c_int, [_P, _I32, _P]),
     "nmt_check_overflow": (C.c_int, [_P, _F, _P, _P]),
@@ -149,6 +156,21 @@ def nmt_workspace_bytes(ctx, B, S, T):
     return n
 
 
+def _segments(segs):
+    """segs: sequence of (B, S, T, micro_idx)."""
+    arr = (nmt_segment * len(segs))()
+    for i, (B, S, T, micro) in enumerate(segs):
+        arr[i] = nmt_segment(B, S, T, micro)
+    return arr
+
+
+def nmt_workspace_bytes_group(ctx, segs):
+    n = load().nmt_workspace_bytes_group(ctx, len(segs), _segments(segs))
+    if n < 0:
+        _check(int(n))
+    return n
+
+
 def nmt_bind(ctx, w16, g16, master32=None, acc32=None, adam_m=None, adam_v=None, workspace=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().nmt_bind(ctx, _p(w16), _p(g16), _p(master32), _p(acc32), _p(adam_m), _p(adam_v), _p(workspace), ws_bytes))
@@ -161,6 +183,14 @@ def nmt_forward_loss(ctx, src, tgt_in, tgt_out, loss_scale, step, micro_idx, los
     T = tgt_in.shape[1]
     _check(load().nmt_forward_loss(ctx, _p(src), _p(tgt_in), _p(tgt_out), B, S, T, loss_scale, step, micro_idx, _p(sent_uid),
                                    1 if training else 0, _p(loss_sum), _p(ntok), _stream(stream)))
+
+
+def nmt_forward_loss_group(ctx, segs, src, tgt_in, tgt_out, loss_scale, step, loss_sum, ntok, sent_uid=None, training=True,
+                           stream=None):
+    """segs: sequence of (B, S, T, micro_idx); src / tgt_in / tgt_out: flat int32 tensors holding the sub-batches one after
+    another; sent_uid: one uint32 per sentence in the same order, or None."""
+    _check(load().nmt_forward_loss_group(ctx, len(segs), _segments(segs), _p(src), _p(tgt_in), _p(tgt_out), loss_scale, step,
+                                         _p(sent_uid), 1 if training else 0, _p(loss_sum), _p(ntok), _stream(stream)))
 
 
 def nmt_backward(ctx, stream=None):

@@ -27,8 +27,23 @@ struct AttnArgs {
   float* lse;
   const int32_t* key_ids;
   int ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv;
-  int pad_id, causal, B, H, Tq, Tk;
+  int pad_id, causal, B, H, Tq, Tk;  // with a sentence table: Tq, Tk are the largest lengths in it
+  const int4* tab;                   // per sentence (first query row, first key row, Tq, Tk), or nullptr
+  int Nq;                            // query rows in total: lse is [H, Nq]
 };
+
+// Rows and lengths of sentence b: from the table when several batches of different shapes are
+// stacked row-wise, else sentence b of one rectangular batch.
+struct Sent {
+  int q0, k0, Tq, Tk;
+};
+__device__ __forceinline__ Sent sentence(const AttnArgs& a, int b) {
+  if (a.tab) {
+    const int4 t = a.tab[b];
+    return Sent{t.x, t.y, t.z, t.w};
+  }
+  return Sent{b * a.Tq, b * a.Tk, a.Tq, a.Tk};
+}
 
 __device__ __forceinline__ half8_t join4(half4_t a, half4_t b) {
   half8_t r;
@@ -90,26 +105,28 @@ template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const int b = blockIdx.y / a.H, h = blockIdx.y % a.H;
-  const int KP = (a.Tk + 31) & ~31;
+  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+  const Sent se = sentence(a, b);
+  if ((int)blockIdx.y * 128 >= se.Tq) return;
+  const int KP = (se.Tk + 31) & ~31;
   half_t* Ks = reinterpret_cast<half_t*>(smem_raw);
   half_t* Vs = Ks + KP * PR;
   uint8_t* hidk = reinterpret_cast<uint8_t*>(Vs + KP * PR);
 
-  stage_rows<DH>(a.K + (size_t)b * a.Tk * a.ldk + h * DH, a.ldk, 0, a.Tk, KP, Ks);
-  stage_rows<DH>(a.V + (size_t)b * a.Tk * a.ldv + h * DH, a.ldv, 0, a.Tk, KP, Vs);
-  for (int k = threadIdx.x; k < KP; k += kThreads) hidk[k] = (k >= a.Tk) || (a.key_ids && a.key_ids[b * a.Tk + k] == a.pad_id);
+  stage_rows<DH>(a.K + (size_t)se.k0 * a.ldk + h * DH, a.ldk, 0, se.Tk, KP, Ks);
+  stage_rows<DH>(a.V + (size_t)se.k0 * a.ldv + h * DH, a.ldv, 0, se.Tk, KP, Vs);
+  for (int k = threadIdx.x; k < KP; k += kThreads) hidk[k] = (k >= se.Tk) || (a.key_ids && a.key_ids[se.k0 + k] == a.pad_id);
   __syncthreads();
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int q0 = blockIdx.x * 128 + wave * 32;
-  if (q0 >= a.Tq) return;
+  const int q0 = blockIdx.y * 128 + wave * 32;
+  if (q0 >= se.Tq) return;
   const int q = q0 + (lane & 31);
-  const bool qvalid = q < a.Tq;
+  const bool qvalid = q < se.Tq;
   half8_t qf[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s)
-    qf[s] = qvalid ? ld_half8(a.Q + (size_t)(b * a.Tq + q) * a.ldq + h * DH + s * 16 + g * 8) : zero_half8();
+    qf[s] = qvalid ? ld_half8(a.Q + (size_t)(se.q0 + q) * a.ldq + h * DH + s * 16 + g * 8) : zero_half8();
 
   const float sc = rsqrtf((float)DH) * kLog2e;
   float m = -1e30f, l = 0.f;
@@ -165,10 +182,10 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
         half4_t o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = (half_t)(oacc[t][4 * rq + e] * inv);
-        *reinterpret_cast<half4_t*>(a.Out + (size_t)(b * a.Tq + q) * a.ldo + h * DH + dh0) = o;
+        *reinterpret_cast<half4_t*>(a.Out + (size_t)(se.q0 + q) * a.ldo + h * DH + dh0) = o;
       }
     }
-  if (g == 0) a.lse[(size_t)(b * a.H + h) * a.Tq + q] = (m + log2f(l)) * kLn2;
+  if (g == 0) a.lse[(size_t)h * a.Nq + se.q0 + q] = (m + log2f(l)) * kLn2;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -183,17 +200,19 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
   float* lse_s = reinterpret_cast<float*>(dOs + kQC * PR);
   float* D_s = lse_s + kQC;
 
-  const int b = blockIdx.y / a.H, h = blockIdx.y % a.H;
+  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+  const Sent se = sentence(a, b);
+  if ((int)blockIdx.y * 128 >= se.Tk) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int k0 = blockIdx.x * 128 + wave * 32;
+  const int k0 = blockIdx.y * 128 + wave * 32;
   const int key = k0 + (lane & 31);
-  const bool kvalid = key < a.Tk;
-  const bool khid = !kvalid || (a.key_ids && a.key_ids[b * a.Tk + key] == a.pad_id);
+  const bool kvalid = key < se.Tk;
+  const bool khid = !kvalid || (a.key_ids && a.key_ids[se.k0 + key] == a.pad_id);
   half8_t kf[KS], vf[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
-    kf[s] = kvalid ? ld_half8(a.K + (size_t)(b * a.Tk + key) * a.ldk + h * DH + s * 16 + g * 8) : zero_half8();
-    vf[s] = kvalid ? ld_half8(a.V + (size_t)(b * a.Tk + key) * a.ldv + h * DH + s * 16 + g * 8) : zero_half8();
+    kf[s] = kvalid ? ld_half8(a.K + (size_t)(se.k0 + key) * a.ldk + h * DH + s * 16 + g * 8) : zero_half8();
+    vf[s] = kvalid ? ld_half8(a.V + (size_t)(se.k0 + key) * a.ldv + h * DH + s * 16 + g * 8) : zero_half8();
   }
   floatx16 dKt[DT], dVt[DT];
 #pragma unroll
@@ -202,19 +221,19 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
     dVt[t] = zero16();
   }
   const float scale = rsqrtf((float)DH), sc = scale * kLog2e;
-  const half_t* Qb = a.Q + (size_t)b * a.Tq * a.ldq + h * DH;
-  const half_t* dOb = a.dO + (size_t)b * a.Tq * a.lddo + h * DH;
-  const half_t* Ob = a.O + (size_t)b * a.Tq * a.ldo + h * DH;
+  const half_t* Qb = a.Q + (size_t)se.q0 * a.ldq + h * DH;
+  const half_t* dOb = a.dO + (size_t)se.q0 * a.lddo + h * DH;
+  const half_t* Ob = a.O + (size_t)se.q0 * a.ldo + h * DH;
 
-  for (int qc = 0; qc < a.Tq; qc += kQC) {
+  for (int qc = 0; qc < se.Tq; qc += kQC) {
     __syncthreads();
-    stage_rows<DH>(Qb, a.ldq, qc, a.Tq, kQC, Qs);
-    stage_rows<DH>(dOb, a.lddo, qc, a.Tq, kQC, dOs);
+    stage_rows<DH>(Qb, a.ldq, qc, se.Tq, kQC, Qs);
+    stage_rows<DH>(dOb, a.lddo, qc, se.Tq, kQC, dOs);
     // D[q] = sum_dh dO[q,dh] * O[q,dh]: CH consecutive lanes share a row
     for (int idx = threadIdx.x; idx < kQC * CH; idx += kThreads) {
       const int rl = idx / CH, c = idx % CH, q = qc + rl;
       float part = 0.f;
-      if (q < a.Tq) {
+      if (q < se.Tq) {
         const half8_t dv = ld_half8(dOb + (size_t)q * a.lddo + c * 8), ov = ld_half8(Ob + (size_t)q * a.ldo + c * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) part += (float)dv[e] * (float)ov[e];
@@ -223,12 +242,12 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
       for (int o = CH / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
       if (c == 0) {
         D_s[rl] = part;
-        lse_s[rl] = q < a.Tq ? a.lse[(size_t)(b * a.H + h) * a.Tq + q] : 0.f;
+        lse_s[rl] = q < se.Tq ? a.lse[(size_t)h * a.Nq + se.q0 + q] : 0.f;
       }
     }
     __syncthreads();
-    if (k0 >= a.Tk) continue;
-    const int nqt = (min(kQC, a.Tq - qc) + 31) / 32;
+    if (k0 >= se.Tk) continue;
+    const int nqt = (min(kQC, se.Tq - qc) + 31) / 32;
     for (int qt = 0; qt < nqt; ++qt) {
       if (a.causal && qc + qt * 32 + 31 < k0) continue;  // every query of the tile precedes every key
       floatx16 s = zero16(), dp = zero16();
@@ -243,7 +262,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
       for (int r = 0; r < 16; ++r) {
         const int ql = qt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
         const int q = qc + ql;
-        const bool hid = khid || q >= a.Tq || (a.causal && key > q);
+        const bool hid = khid || q >= se.Tq || (a.causal && key > q);
         const float p = hid ? 0.f : exp2f(s[r] * sc - lse_s[ql] * kLog2e);
         pf[r >> 3][r & 7] = (half_t)p;
         dsf[r >> 3][r & 7] = (half_t)(p * (dp[r] - D_s[ql]) * scale);
@@ -271,8 +290,8 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
           ok[e] = (half_t)dKt[t][4 * rq + e];
           ov[e] = (half_t)dVt[t][4 * rq + e];
         }
-        *reinterpret_cast<half4_t*>(a.dK + (size_t)(b * a.Tk + key) * a.lddk + h * DH + dh0) = ok;
-        *reinterpret_cast<half4_t*>(a.dV + (size_t)(b * a.Tk + key) * a.lddv + h * DH + dh0) = ov;
+        *reinterpret_cast<half4_t*>(a.dK + (size_t)(se.k0 + key) * a.lddk + h * DH + dh0) = ok;
+        *reinterpret_cast<half4_t*>(a.dV + (size_t)(se.k0 + key) * a.lddv + h * DH + dh0) = ov;
       }
     }
 }
@@ -288,40 +307,42 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
   half_t* Vs = Ks + kKC * PR;
   uint8_t* hidk = reinterpret_cast<uint8_t*>(Vs + kKC * PR);
 
-  const int b = blockIdx.y / a.H, h = blockIdx.y % a.H;
+  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+  const Sent se = sentence(a, b);
+  if ((int)blockIdx.y * 128 >= se.Tq) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int q0 = blockIdx.x * 128 + wave * 32;
+  const int q0 = blockIdx.y * 128 + wave * 32;
   const int q = q0 + (lane & 31);
-  const bool qvalid = q < a.Tq;
+  const bool qvalid = q < se.Tq;
   half8_t qf[KS], dof[KS];
   float Dq = 0.f;
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
     const int col = h * DH + s * 16 + g * 8;
-    qf[s] = qvalid ? ld_half8(a.Q + (size_t)(b * a.Tq + q) * a.ldq + col) : zero_half8();
-    dof[s] = qvalid ? ld_half8(a.dO + (size_t)(b * a.Tq + q) * a.lddo + col) : zero_half8();
-    const half8_t ov = qvalid ? ld_half8(a.O + (size_t)(b * a.Tq + q) * a.ldo + col) : zero_half8();
+    qf[s] = qvalid ? ld_half8(a.Q + (size_t)(se.q0 + q) * a.ldq + col) : zero_half8();
+    dof[s] = qvalid ? ld_half8(a.dO + (size_t)(se.q0 + q) * a.lddo + col) : zero_half8();
+    const half8_t ov = qvalid ? ld_half8(a.O + (size_t)(se.q0 + q) * a.ldo + col) : zero_half8();
 #pragma unroll
     for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)ov[e];
   }
   Dq += __shfl_xor(Dq, 32, kWave);
-  const float lse_q = qvalid ? a.lse[(size_t)(b * a.H + h) * a.Tq + q] * kLog2e : 0.f;
+  const float lse_q = qvalid ? a.lse[(size_t)h * a.Nq + se.q0 + q] * kLog2e : 0.f;
   const float scale = rsqrtf((float)DH), sc = scale * kLog2e;
   floatx16 dQt[DT];
 #pragma unroll
   for (int t = 0; t < DT; ++t) dQt[t] = zero16();
-  const half_t* Kb = a.K + (size_t)b * a.Tk * a.ldk + h * DH;
-  const half_t* Vb = a.V + (size_t)b * a.Tk * a.ldv + h * DH;
+  const half_t* Kb = a.K + (size_t)se.k0 * a.ldk + h * DH;
+  const half_t* Vb = a.V + (size_t)se.k0 * a.ldv + h * DH;
 
-  for (int kc = 0; kc < a.Tk; kc += kKC) {
+  for (int kc = 0; kc < se.Tk; kc += kKC) {
     __syncthreads();
-    stage_rows<DH>(Kb, a.ldk, kc, a.Tk, kKC, Ks);
-    stage_rows<DH>(Vb, a.ldv, kc, a.Tk, kKC, Vs);
+    stage_rows<DH>(Kb, a.ldk, kc, se.Tk, kKC, Ks);
+    stage_rows<DH>(Vb, a.ldv, kc, se.Tk, kKC, Vs);
     for (int k = threadIdx.x; k < kKC; k += kThreads)
-      hidk[k] = (kc + k >= a.Tk) || (a.key_ids && a.key_ids[b * a.Tk + kc + k] == a.pad_id);
+      hidk[k] = (kc + k >= se.Tk) || (a.key_ids && a.key_ids[se.k0 + kc + k] == a.pad_id);
     __syncthreads();
-    if (q0 >= a.Tq) continue;
-    const int nkt = (min(kKC, a.Tk - kc) + 31) / 32;
+    if (q0 >= se.Tq) continue;
+    const int nkt = (min(kKC, se.Tk - kc) + 31) / 32;
     for (int kt = 0; kt < nkt; ++kt) {
       if (a.causal && kc + kt * 32 > q0 + 31) break;  // every key of the tile follows every query
       floatx16 s = zero16(), dp = zero16();
@@ -357,7 +378,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
         half4_t o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = (half_t)dQt[t][4 * rq + e];
-        *reinterpret_cast<half4_t*>(a.dQ + (size_t)(b * a.Tq + q) * a.lddq + h * DH + dh0) = o;
+        *reinterpret_cast<half4_t*>(a.dQ + (size_t)(se.q0 + q) * a.lddq + h * DH + dh0) = o;
       }
     }
 }
@@ -388,7 +409,7 @@ int fwd_launch(const AttnArgs& a, hipStream_t stream) {
   const size_t smem = fwd_smem<DH>(a.Tk);
   NMT_REQUIRE(smem <= 160 * 1024, "attention: Tk=%d needs %zu bytes of LDS", a.Tk, smem);
   if (int rc = allow_big_lds(attn_fwd_kernel<DH>, smem)) return rc;
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3(ceil_div(a.Tq, 128), a.B * a.H), dim3(kThreads), smem, stream, a);
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3(a.B * a.H, ceil_div(a.Tq, 128)), dim3(kThreads), smem, stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -396,9 +417,9 @@ template <int DH>
 int bwd_launch(const AttnArgs& a, hipStream_t stream) {
   if (int rc = allow_big_lds(attn_bwd_dkv_kernel<DH>, dkv_smem<DH>())) return rc;
   if (int rc = allow_big_lds(attn_bwd_dq_kernel<DH>, dq_smem<DH>())) return rc;
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DH>, dim3(ceil_div(a.Tk, 128), a.B * a.H), dim3(kThreads), dkv_smem<DH>(), stream, a);
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DH>, dim3(a.B * a.H, ceil_div(a.Tk, 128)), dim3(kThreads), dkv_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3(ceil_div(a.Tq, 128), a.B * a.H), dim3(kThreads), dq_smem<DH>(), stream, a);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3(a.B * a.H, ceil_div(a.Tq, 128)), dim3(kThreads), dq_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -406,7 +427,8 @@ int bwd_launch(const AttnArgs& a, hipStream_t stream) {
 int check_common(const AttnArgs& a, int dh) {
   NMT_REQUIRE(a.B > 0 && a.H > 0 && a.Tq > 0 && a.Tk > 0, "attention: empty problem");
   NMT_REQUIRE(dh == 16 || dh == 32 || dh == 64 || dh == 128, "attention: head size %d not in {16,32,64,128}", dh);
-  NMT_REQUIRE(a.Tk <= 1024 && a.Tq <= 65535 && (int64_t)a.B * a.H <= 65535 * 1, "attention: Tk=%d / B*H=%d out of range", a.Tk, a.B * a.H);
+  NMT_REQUIRE(a.Tk <= 1024 && a.Tq <= 65535 && (int64_t)a.B * a.H < (1ll << 31), "attention: Tk=%d / B*H out of range", a.Tk);
+  NMT_REQUIRE(a.tab ? a.Nq > 0 : a.Nq == a.B * a.Tq, "attention: inconsistent number of query rows");
   NMT_REQUIRE(a.ldq % 8 == 0 && a.ldk % 8 == 0 && a.ldv % 8 == 0 && a.ldo % 8 == 0, "attention: row strides must be multiples of 8");
   NMT_REQUIRE(a.ldq >= a.H * dh && a.ldk >= a.H * dh && a.ldv >= a.H * dh && a.ldo >= a.H * dh, "attention: row stride smaller than H*dh");
   NMT_REQUIRE(aligned16(a.Q) && aligned16(a.K) && aligned16(a.V), "attention: Q/K/V must be 16-byte aligned");
@@ -417,15 +439,16 @@ int check_common(const AttnArgs& a, int dh) {
 
 int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O, int ldo,
                          float* lse, const int32_t* key_ids, int pad_id, int causal, int B, int H, int dh, int Tq, int Tk,
-                         hipStream_t stream) {
+                         const int4* sent_tab, int n_q_rows, hipStream_t stream) {
   AttnArgs a = {};
+  a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
   a.Q = Q; a.K = K; a.V = V; a.Out = O; a.lse = lse; a.key_ids = key_ids;
   a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.ldo = ldo;
   a.pad_id = pad_id; a.causal = causal; a.B = B; a.H = H; a.Tq = Tq; a.Tk = Tk;
   NMT_REQUIRE(Q && K && V && O && lse, "attention_fwd: null pointer");
   if (int rc = check_common(a, dh)) return rc;
   NMT_REQUIRE(aligned16(O), "attention_fwd: O must be 16-byte aligned");
-  NMT_REQUIRE(!causal || Tq == Tk, "attention_fwd: the causal mask needs Tq == Tk");
+  NMT_REQUIRE(!causal || Tq == Tk, "attention_fwd: the causal mask needs Tq == Tk");  // (per sentence, with a table)
   switch (dh) {
     case 16: return fwd_launch<16>(a, stream);
     case 32: return fwd_launch<32>(a, stream);
@@ -437,8 +460,9 @@ int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
 int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, const half_t* O, int ldo,
                          const half_t* dO, int lddo, const float* lse, half_t* dQ, int lddq, half_t* dK, int lddk, half_t* dV,
                          int lddv, const int32_t* key_ids, int pad_id, int causal, int B, int H, int dh, int Tq, int Tk,
-                         hipStream_t stream) {
+                         const int4* sent_tab, int n_q_rows, hipStream_t stream) {
   AttnArgs a = {};
+  a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.lse = const_cast<float*>(lse); a.key_ids = key_ids;
   a.dQ = dQ; a.dK = dK; a.dV = dV;
   a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.ldo = ldo; a.lddo = lddo; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;

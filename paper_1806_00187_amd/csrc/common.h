@@ -70,7 +70,10 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1
   return c;
 }
 
-// Device-side dropout description (built on the host from nmt_dropout).
+// Device-side dropout description (built on the host from nmt_dropout).  Row r of an activation
+// belongs to sentence `uid` at position `pos` of sub-batch `micro`: either r / n_pos, r % n_pos and
+// the micro index in c3 (one rectangular batch), or, when `rowkey` is set, rowkey[r] =
+// (uid, pos | micro << 16) (several batches of different shapes stacked row-wise).
 struct DropDev {
   uint32_t k0, k1;      // Philox key = seed
   uint32_t c3;          // step << 8 | micro
@@ -79,16 +82,30 @@ struct DropDev {
   float scale;          // 1 / (1 - p)
   int32_t n_pos;        // rows per sentence
   const uint32_t* uid;  // per-sentence ids or nullptr
+  const uint2* rowkey;  // per-row (uid, pos | micro << 16) or nullptr
 };
 
 DropDev make_drop(const nmt_dropout* d);  // host; d == nullptr or p <= 0 gives thr = 0
 
+// Position within its sentence of row `row`.
+__device__ __forceinline__ uint32_t drop_row_pos(const DropDev& dd, uint32_t row) {
+  return dd.rowkey ? (dd.rowkey[row].y & 0xFFFFu) : row % (uint32_t)dd.n_pos;
+}
+
 // Keep decisions of the 8 columns [8*grp, 8*grp+8) of row `row`: bit i set = column 8*grp+i kept.
 __device__ __forceinline__ uint32_t drop_keep8(const DropDev& dd, uint32_t row, uint32_t grp) {
-  const uint32_t sent = row / (uint32_t)dd.n_pos;
-  const uint32_t pos = row - sent * (uint32_t)dd.n_pos;
-  const uint32_t uid = dd.uid ? dd.uid[sent] : sent;
-  const uint4 w = philox4x32_10(make_uint4(grp, uid, dd.site_hi | pos, dd.c3), dd.k0, dd.k1);
+  uint32_t uid, pos, c3 = dd.c3;
+  if (dd.rowkey) {
+    const uint2 rk = dd.rowkey[row];
+    uid = rk.x;
+    pos = rk.y & 0xFFFFu;
+    c3 = (c3 & 0xFFFFFF00u) | (rk.y >> 16);
+  } else {
+    const uint32_t sent = row / (uint32_t)dd.n_pos;
+    pos = row - sent * (uint32_t)dd.n_pos;
+    uid = dd.uid ? dd.uid[sent] : sent;
+  }
+  const uint4 w = philox4x32_10(make_uint4(grp, uid, dd.site_hi | pos, c3), dd.k0, dd.k1);
   const uint32_t words[4] = {w.x, w.y, w.z, w.w};
   uint32_t bits = 0;
 #pragma unroll
@@ -121,11 +138,12 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
 
 int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O,
                          int ldo, float* lse, const int32_t* key_ids, int pad_id, int causal, int B, int H,
-                         int dh, int Tq, int Tk, hipStream_t stream);
+                         int dh, int Tq, int Tk, const int4* sent_tab, int n_q_rows, hipStream_t stream);
 int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv,
                          const half_t* O, int ldo, const half_t* dO, int lddo, const float* lse, half_t* dQ,
                          int lddq, half_t* dK, int lddk, half_t* dV, int lddv, const int32_t* key_ids, int pad_id,
-                         int causal, int B, int H, int dh, int Tq, int Tk, hipStream_t stream);
+                         int causal, int B, int H, int dh, int Tq, int Tk, const int4* sent_tab, int n_q_rows,
+                         hipStream_t stream);
 
 int launch_residual_layernorm_fwd(const half_t* sub, const half_t* resid, const half_t* gamma, const half_t* beta,
                                   half_t* out, float* stats, int rows, int d, float eps, const DropDev& drop,
@@ -149,4 +167,15 @@ int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipSt
 int launch_check_overflow(float* acc, int64_t n, float inv_scale, int32_t* flag, hipStream_t stream);
 int launch_adam(float* master, float* m, float* v, const float* g, half_t* w16, int64_t n, float lr, float b1,
                 float b2, float eps, int t, const int32_t* flag, hipStream_t stream);
+// Shapes of the sub-batches stacked row-wise in one pass (passed to the table kernel by value).
+struct SegmentList {
+  int n;
+  int B[NMT_MAX_SEGMENTS], S[NMT_MAX_SEGMENTS], T[NMT_MAX_SEGMENTS];
+  uint32_t micro[NMT_MAX_SEGMENTS];
+};
+// Row keys (uid, pos | micro << 16) of all source / target rows and the per-sentence attention
+// tables (first query row, first key row, Tq, Tk) for encoder self-, decoder self- and
+// encoder-decoder attention.  uid == nullptr: a sentence's id is its index within its sub-batch.
+int launch_build_tables(const SegmentList& segs, int n_sent, const uint32_t* uid, uint2* rk_src, uint2* rk_tgt, int4* tab_ss,
+                        int4* tab_tt, int4* tab_ts, hipStream_t stream);
 int launch_dropout_mask(uint8_t* keep, int rows, int n_cols, const DropDev& drop, hipStream_t stream);

@@ -59,6 +59,7 @@ struct EncP { AttnP attn; LnP ln1; FfnP ffn; LnP ln2; };
 struct DecP { AttnP self; LnP ln1; AttnP cross; LnP ln2; FfnP ffn; LnP ln3; };
 
 // dropout sites: a site id selects an independent random stream
+constexpr int kMaxSegments = NMT_MAX_SEGMENTS;
 constexpr uint32_t kSiteEmbSrc = 0, kSiteEmbTgt = 1;
 constexpr uint32_t kKindSelfRes = 0, kKindCrossRes = 1, kKindFfnAct = 2, kKindFfnRes = 3;
 inline uint32_t layer_site(int layer_index, uint32_t kind) { return 16u * (1u + (uint32_t)layer_index) + kind; }
@@ -68,6 +69,7 @@ inline uint32_t layer_site(int layer_index, uint32_t kind) { return 16u * (1u + 
 struct EncW { int64_t qkv, o, s1, x1, h, s2, x2, lse, st1, st2; };
 struct DecW { int64_t qkv, o1, s1, x1, lse1, q, kv, o2, s2, x2, lse2, h, s3, x3, st1, st2, st3; };
 struct Plan {
+  int64_t rk_src, rk_tgt, tab_ss, tab_tt, tab_ts;  // row keys (dropout, positions) and per-sentence attention tables
   int64_t x0, y0, logits, rowloss;
   std::vector<EncW> enc;
   std::vector<DecW> dec;
@@ -91,10 +93,9 @@ struct nmt_ctx {
   int64_t ws_bytes = 0;
   // state of the last forward pass
   bool have_fwd = false;
-  int B = 0, S = 0, T = 0, training = 0;
+  int Bt = 0, Ns = 0, Nt = 0, maxS = 0, maxT = 0, training = 0;  // sentences, source / target rows, longest sides
   float loss_scale = 1.f;
-  uint32_t step = 0, micro = 0;
-  const uint32_t* uid = nullptr;
+  uint32_t step = 0;
   const int32_t *src = nullptr, *tgt_in = nullptr, *tgt_out = nullptr;
   Plan plan;
   // second stream for the weight-gradient kernels of the backward pass (created on first use)
@@ -137,10 +138,16 @@ void add_ffn(nmt_ctx* c, const std::string& pre, FfnP& f) {
   f.b2 = add_tensor(c, pre + "b2", 1, d);
 }
 
-int64_t plan_workspace(const nmt_ctx* c, int B, int S, int T, Plan& p) {
+// Totals of a group of sub-batches stacked row-wise.
+struct GroupDims {
+  int64_t Bt = 0, Ns = 0, Nt = 0;
+  int maxS = 0, maxT = 0;
+};
+
+int64_t plan_workspace(const nmt_ctx* c, const GroupDims& gd, Plan& p) {
   const nmt_config& k = c->cfg;
   const int64_t d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads;
-  const int64_t Ns = (int64_t)B * S, Nt = (int64_t)B * T, Nm = Ns > Nt ? Ns : Nt;
+  const int64_t B = gd.Bt, Ns = gd.Ns, Nt = gd.Nt, Nm = Ns > Nt ? Ns : Nt;
   int64_t cur = 0;
   auto take = [&](int64_t bytes) {
     const int64_t off = cur;
@@ -148,6 +155,11 @@ int64_t plan_workspace(const nmt_ctx* c, int B, int S, int T, Plan& p) {
     return off;
   };
   const int64_t h2 = sizeof(half_t), f4 = sizeof(float);
+  p.rk_src = take(Ns * (int64_t)sizeof(uint2));
+  p.rk_tgt = take(Nt * (int64_t)sizeof(uint2));
+  p.tab_ss = take(B * (int64_t)sizeof(int4));
+  p.tab_tt = take(B * (int64_t)sizeof(int4));
+  p.tab_ts = take(B * (int64_t)sizeof(int4));
   p.x0 = take(Ns * d * h2);
   p.y0 = take(Nt * d * h2);
   p.enc.resize(k.enc_layers);
@@ -159,7 +171,7 @@ int64_t plan_workspace(const nmt_ctx* c, int B, int S, int T, Plan& p) {
     e.h = take(Ns * F * h2);
     e.s2 = take(Ns * d * h2);
     e.x2 = take(Ns * d * h2);
-    e.lse = take((int64_t)B * H * S * f4);
+    e.lse = take(H * Ns * f4);
     e.st1 = take(Ns * 2 * f4);
     e.st2 = take(Ns * 2 * f4);
   }
@@ -169,13 +181,13 @@ int64_t plan_workspace(const nmt_ctx* c, int B, int S, int T, Plan& p) {
     e.o1 = take(Nt * d * h2);
     e.s1 = take(Nt * d * h2);
     e.x1 = take(Nt * d * h2);
-    e.lse1 = take((int64_t)B * H * T * f4);
+    e.lse1 = take(H * Nt * f4);
     e.q = take(Nt * d * h2);
     e.kv = take(Ns * 2 * d * h2);
     e.o2 = take(Nt * d * h2);
     e.s2 = take(Nt * d * h2);
     e.x2 = take(Nt * d * h2);
-    e.lse2 = take((int64_t)B * H * T * f4);
+    e.lse2 = take(H * Nt * f4);
     e.h = take(Nt * F * h2);
     e.s3 = take(Nt * d * h2);
     e.x3 = take(Nt * d * h2);
@@ -204,10 +216,23 @@ int64_t plan_workspace(const nmt_ctx* c, int B, int S, int T, Plan& p) {
   return cur;
 }
 
-int check_shape(const nmt_ctx* c, int B, int S, int T) {
+int check_group(const nmt_ctx* c, int n_seg, const nmt_segment* segs, GroupDims& gd) {
   NMT_REQUIRE(c, "null context");
-  NMT_REQUIRE(B >= 1 && B <= c->cfg.max_sentences, "B=%d outside [1, max_sentences=%d]", B, c->cfg.max_sentences);
-  NMT_REQUIRE(S >= 1 && S <= c->cfg.max_len && T >= 1 && T <= c->cfg.max_len, "S=%d / T=%d outside [1, max_len=%d]", S, T, c->cfg.max_len);
+  NMT_REQUIRE(segs && n_seg >= 1 && n_seg <= kMaxSegments, "number of sub-batches %d outside [1, %d]", n_seg, kMaxSegments);
+  gd = GroupDims{};
+  for (int i = 0; i < n_seg; ++i) {
+    const nmt_segment& s = segs[i];
+    NMT_REQUIRE(s.B >= 1 && s.B <= c->cfg.max_sentences, "sub-batch %d: B=%d outside [1, max_sentences=%d]", i, s.B, c->cfg.max_sentences);
+    NMT_REQUIRE(s.S >= 1 && s.S <= c->cfg.max_len && s.T >= 1 && s.T <= c->cfg.max_len, "sub-batch %d: S=%d / T=%d outside [1, max_len=%d]", i,
+                s.S, s.T, c->cfg.max_len);
+    NMT_REQUIRE(s.micro_idx < 256u, "sub-batch %d: micro_idx must be < 256", i);
+    gd.Bt += s.B;
+    gd.Ns += (int64_t)s.B * s.S;
+    gd.Nt += (int64_t)s.B * s.T;
+    gd.maxS = s.S > gd.maxS ? s.S : gd.maxS;
+    gd.maxT = s.T > gd.maxT ? s.T : gd.maxT;
+  }
+  NMT_REQUIRE(gd.Ns <= (1 << 20) && gd.Nt <= (1 << 20), "more than 2^20 positions in one pass");
   return NMT_OK;
 }
 
@@ -290,10 +315,15 @@ extern "C" int nmt_param_info(const nmt_ctx* ctx, int32_t idx, const char** name
   return NMT_OK;
 }
 
-extern "C" int64_t nmt_workspace_bytes(const nmt_ctx* ctx, int32_t B, int32_t S, int32_t T) {
-  if (check_shape(ctx, B, S, T) != NMT_OK) return NMT_EINVAL;
+extern "C" int64_t nmt_workspace_bytes_group(const nmt_ctx* ctx, int32_t n_seg, const nmt_segment* segs) {
+  GroupDims gd;
+  if (check_group(ctx, n_seg, segs, gd) != NMT_OK) return NMT_EINVAL;
   Plan p;
-  return plan_workspace(ctx, B, S, T, p);
+  return plan_workspace(ctx, gd, p);
+}
+extern "C" int64_t nmt_workspace_bytes(const nmt_ctx* ctx, int32_t B, int32_t S, int32_t T) {
+  const nmt_segment seg = {B, S, T, 0u};
+  return nmt_workspace_bytes_group(ctx, 1, &seg);
 }
 
 extern "C" int nmt_bind(nmt_ctx* ctx, void* d_w16, void* d_g16, float* d_master32, float* d_acc32, float* d_adam_m,
@@ -328,9 +358,12 @@ struct Run {
   T* ws(int64_t off) const { return reinterpret_cast<T*>(c->ws + off); }
   half_t* w(int64_t off) const { return c->w16 + off; }
   half_t* g(int64_t off) const { return c->g16 + off; }
-  DropDev drop(uint32_t site, int n_pos, float p) const {
-    nmt_dropout d = {c->training ? p : 0.f, site, c->step, c->micro, c->cfg.seed, n_pos, c->uid};
-    return make_drop(&d);
+  // dropout stream `site` over source (tgt == false) or target rows
+  DropDev drop(uint32_t site, bool tgt, float p) const {
+    nmt_dropout d = {c->training ? p : 0.f, site, c->step, 0u, c->cfg.seed, 1, nullptr};
+    DropDev dd = make_drop(&d);
+    dd.rowkey = ws<uint2>(tgt ? c->plan.rk_tgt : c->plan.rk_src);
+    return dd;
   }
   // y[N, out] = x[N, in] W^T + b   (W stored [out, in])
   int linear(const half_t* x, int N, int in, int64_t W, int64_t b, int out, half_t* y, GemmEpilogue ep = {}) const {
@@ -353,55 +386,75 @@ extern "C" int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_
                                 int32_t B, int32_t S, int32_t T, float loss_scale, uint32_t step, uint32_t micro_idx,
                                 const uint32_t* d_sent_uid, int32_t training, float* d_loss_sum, int32_t* d_ntok,
                                 void* stream) {
-  NMT_TRY(check_shape(ctx, B, S, T));
+  const nmt_segment seg = {B, S, T, micro_idx};
+  return nmt_forward_loss_group(ctx, 1, &seg, d_src, d_tgt_in, d_tgt_out, loss_scale, step, d_sent_uid, training, d_loss_sum, d_ntok,
+                                stream);
+}
+
+extern "C" int nmt_forward_loss_group(nmt_ctx* ctx, int32_t n_seg, const nmt_segment* segs, const int32_t* d_src,
+                                      const int32_t* d_tgt_in, const int32_t* d_tgt_out, float loss_scale, uint32_t step,
+                                      const uint32_t* d_sent_uid, int32_t training, float* d_loss_sum, int32_t* d_ntok,
+                                      void* stream) {
+  GroupDims gd;
+  NMT_TRY(check_group(ctx, n_seg, segs, gd));
   nmt_ctx* c = ctx;
   c->have_fwd = false;
   NMT_REQUIRE(d_src && d_tgt_in && d_tgt_out && d_loss_sum && d_ntok, "nmt_forward_loss: null pointer");
   NMT_REQUIRE(c->w16 && c->g16, "nmt_forward_loss: nmt_bind has not been called");
   NMT_REQUIRE(loss_scale > 0.f && isfinite(loss_scale), "nmt_forward_loss: loss_scale must be positive and finite");
-  NMT_REQUIRE(step < (1u << 24) && micro_idx < 256u, "nmt_forward_loss: step must be < 2^24 and micro_idx < 256");
-  if (plan_workspace(c, B, S, T, c->plan) > c->ws_bytes) {
+  NMT_REQUIRE(step < (1u << 24), "nmt_forward_loss: step must be < 2^24");
+  if (plan_workspace(c, gd, c->plan) > c->ws_bytes) {
     nmt_set_error("nmt_forward_loss: workspace of %lld bytes is smaller than the %lld needed", (long long)c->ws_bytes, (long long)c->plan.total);
     return NMT_ENOMEM;
   }
-  c->B = B; c->S = S; c->T = T;
-  c->loss_scale = loss_scale; c->step = step; c->micro = micro_idx; c->uid = d_sent_uid; c->training = training != 0;
+  c->Bt = (int)gd.Bt; c->Ns = (int)gd.Ns; c->Nt = (int)gd.Nt; c->maxS = gd.maxS; c->maxT = gd.maxT;
+  c->loss_scale = loss_scale; c->step = step; c->training = training != 0;
   c->src = d_src; c->tgt_in = d_tgt_in; c->tgt_out = d_tgt_out;
 
   const nmt_config& k = c->cfg;
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
-  const int Ns = B * S, Nt = B * T;
+  const int Bt = c->Bt, Ns = c->Ns, Nt = c->Nt, maxS = c->maxS, maxT = c->maxT;
   const Plan& p = c->plan;
   const Run r{c, static_cast<hipStream_t>(stream)};
   hipStream_t st = r.st;
+  const int4 *tab_ss = r.ws<int4>(p.tab_ss), *tab_tt = r.ws<int4>(p.tab_tt), *tab_ts = r.ws<int4>(p.tab_ts);
+  {
+    SegmentList sl = {};
+    sl.n = n_seg;
+    for (int i = 0; i < n_seg; ++i) {
+      sl.B[i] = segs[i].B; sl.S[i] = segs[i].S; sl.T[i] = segs[i].T; sl.micro[i] = segs[i].micro_idx;
+    }
+    NMT_TRY(launch_build_tables(sl, Bt, d_sent_uid, r.ws<uint2>(p.rk_src), r.ws<uint2>(p.rk_tgt), r.ws<int4>(p.tab_ss),
+                                r.ws<int4>(p.tab_tt), r.ws<int4>(p.tab_ts), st));
+  }
 
   // ---- encoder ----
   half_t* x = r.ws<half_t>(p.x0);
-  NMT_TRY(launch_embed_fwd(d_src, r.w(c->embed), x, Ns, d, V, r.drop(kSiteEmbSrc, S, k.dropout), st));
+  NMT_TRY(launch_embed_fwd(d_src, r.w(c->embed), x, Ns, d, V, r.drop(kSiteEmbSrc, false, k.dropout), st));
   for (int l = 0; l < k.enc_layers; ++l) {
     const EncP& P = c->enc[l];
     const EncW& W = p.enc[l];
     half_t* qkv = r.ws<half_t>(W.qkv);
     NMT_TRY(r.linear(x, Ns, d, P.attn.wqkv, P.attn.bqkv, 3 * d, qkv));
     NMT_TRY(launch_attention_fwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, r.ws<half_t>(W.o), d, r.ws<float>(W.lse), d_src,
-                                 k.pad_id, 0, B, H, dh, S, S, st));
+                                 k.pad_id, 0, Bt, H, dh, maxS, maxS, tab_ss, Ns, st));
     NMT_TRY(r.linear(r.ws<half_t>(W.o), Ns, d, P.attn.wo, P.attn.bo, d, r.ws<half_t>(W.s1)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s1), x, r.w(P.ln1.g), r.w(P.ln1.b), r.ws<half_t>(W.x1), r.ws<float>(W.st1),
-                                          Ns, d, k.ln_eps, r.drop(layer_site(l, kKindSelfRes), S, k.dropout), st));
+                                          Ns, d, k.ln_eps, r.drop(layer_site(l, kKindSelfRes), false, k.dropout), st));
     GemmEpilogue act;
     act.relu = 1;
-    act.drop = r.drop(layer_site(l, kKindFfnAct), S, k.act_dropout);
+    act.drop = r.drop(layer_site(l, kKindFfnAct), false, k.act_dropout);
     NMT_TRY(r.linear(r.ws<half_t>(W.x1), Ns, d, P.ffn.w1, P.ffn.b1, F, r.ws<half_t>(W.h), act));
     NMT_TRY(r.linear(r.ws<half_t>(W.h), Ns, F, P.ffn.w2, P.ffn.b2, d, r.ws<half_t>(W.s2)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s2), r.ws<half_t>(W.x1), r.w(P.ln2.g), r.w(P.ln2.b), r.ws<half_t>(W.x2),
-                                          r.ws<float>(W.st2), Ns, d, k.ln_eps, r.drop(layer_site(l, kKindFfnRes), S, k.dropout), st));
+                                          r.ws<float>(W.st2), Ns, d, k.ln_eps, r.drop(layer_site(l, kKindFfnRes), false, k.dropout), st));
     x = r.ws<half_t>(W.x2);
   }
   const half_t* enc_out = x;
 
   // ---- decoder ----
   half_t* y = r.ws<half_t>(p.y0);
-  NMT_TRY(launch_embed_fwd(d_tgt_in, r.w(c->embed), y, Nt, d, V, r.drop(kSiteEmbTgt, T, k.dropout), st));
+  NMT_TRY(launch_embed_fwd(d_tgt_in, r.w(c->embed), y, Nt, d, V, r.drop(kSiteEmbTgt, true, k.dropout), st));
   for (int l = 0; l < k.dec_layers; ++l) {
     const DecP& P = c->dec[l];
     const DecW& W = p.dec[l];
@@ -409,25 +462,25 @@ extern "C" int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_
     half_t* qkv = r.ws<half_t>(W.qkv);
     NMT_TRY(r.linear(y, Nt, d, P.self.wqkv, P.self.bqkv, 3 * d, qkv));
     NMT_TRY(launch_attention_fwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, r.ws<half_t>(W.o1), d, r.ws<float>(W.lse1), d_tgt_in,
-                                 k.pad_id, 1, B, H, dh, T, T, st));
+                                 k.pad_id, 1, Bt, H, dh, maxT, maxT, tab_tt, Nt, st));
     NMT_TRY(r.linear(r.ws<half_t>(W.o1), Nt, d, P.self.wo, P.self.bo, d, r.ws<half_t>(W.s1)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s1), y, r.w(P.ln1.g), r.w(P.ln1.b), r.ws<half_t>(W.x1), r.ws<float>(W.st1),
-                                          Nt, d, k.ln_eps, r.drop(layer_site(li, kKindSelfRes), T, k.dropout), st));
+                                          Nt, d, k.ln_eps, r.drop(layer_site(li, kKindSelfRes), true, k.dropout), st));
     half_t* kv = r.ws<half_t>(W.kv);
     NMT_TRY(r.linear(r.ws<half_t>(W.x1), Nt, d, P.cross.wq, P.cross.bq, d, r.ws<half_t>(W.q)));
     NMT_TRY(r.linear(enc_out, Ns, d, P.cross.wkv, P.cross.bkv, 2 * d, kv));
     NMT_TRY(launch_attention_fwd(r.ws<half_t>(W.q), d, kv, 2 * d, kv + d, 2 * d, r.ws<half_t>(W.o2), d, r.ws<float>(W.lse2), d_src,
-                                 k.pad_id, 0, B, H, dh, T, S, st));
+                                 k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, st));
     NMT_TRY(r.linear(r.ws<half_t>(W.o2), Nt, d, P.cross.wo, P.cross.bo, d, r.ws<half_t>(W.s2)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s2), r.ws<half_t>(W.x1), r.w(P.ln2.g), r.w(P.ln2.b), r.ws<half_t>(W.x2),
-                                          r.ws<float>(W.st2), Nt, d, k.ln_eps, r.drop(layer_site(li, kKindCrossRes), T, k.dropout), st));
+                                          r.ws<float>(W.st2), Nt, d, k.ln_eps, r.drop(layer_site(li, kKindCrossRes), true, k.dropout), st));
     GemmEpilogue act;
     act.relu = 1;
-    act.drop = r.drop(layer_site(li, kKindFfnAct), T, k.act_dropout);
+    act.drop = r.drop(layer_site(li, kKindFfnAct), true, k.act_dropout);
     NMT_TRY(r.linear(r.ws<half_t>(W.x2), Nt, d, P.ffn.w1, P.ffn.b1, F, r.ws<half_t>(W.h), act));
     NMT_TRY(r.linear(r.ws<half_t>(W.h), Nt, F, P.ffn.w2, P.ffn.b2, d, r.ws<half_t>(W.s3)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s3), r.ws<half_t>(W.x2), r.w(P.ln3.g), r.w(P.ln3.b), r.ws<half_t>(W.x3),
-                                          r.ws<float>(W.st3), Nt, d, k.ln_eps, r.drop(layer_site(li, kKindFfnRes), T, k.dropout), st));
+                                          r.ws<float>(W.st3), Nt, d, k.ln_eps, r.drop(layer_site(li, kKindFfnRes), true, k.dropout), st));
     y = r.ws<half_t>(W.x3);
   }
 
@@ -464,9 +517,8 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_done[1], hipEventDisableTiming));
   }
   const nmt_config& k = c->cfg;
-  const int B = c->B, S = c->S, T = c->T;
+  const int Bt = c->Bt, Ns = c->Ns, Nt = c->Nt, maxS = c->maxS, maxT = c->maxT;
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
-  const int Ns = B * S, Nt = B * T;
   const Plan& p = c->plan;
   hipStream_t st = static_cast<hipStream_t>(stream), sd = c->side;
   const Run r{c, st};   // input-gradient chain
@@ -474,6 +526,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   const bool dropping = c->training && k.dropout > 0.f;
   const float act_scale = (c->training && k.act_dropout > 0.f) ? 1.f / (1.f - k.act_dropout) : 1.f;
   half_t* dO = r.ws<half_t>(p.dO);
+  const int4 *tab_ss = r.ws<int4>(p.tab_ss), *tab_tt = r.ws<int4>(p.tab_tt), *tab_ts = r.ws<int4>(p.tab_ts);
   float* lnpart = r.ws<float>(p.lnpart);
   float* cspart = r.ws<float>(p.cspart);  // used on the second stream only
 
@@ -505,11 +558,11 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   };
 
   // feed-forward sub-layer: out = LN(x_in + drop(relu(x_in W1^T + b1) W2^T + b2)); dx holds d out on entry, d x_in on exit
-  auto ffn_bwd = [&](half_t* dx, int N, int n_pos, const half_t* x_in, const half_t* hact, const half_t* sub, const float* stats,
+  auto ffn_bwd = [&](half_t* dx, int N, bool tgt, const half_t* x_in, const half_t* hact, const half_t* sub, const float* stats,
                      const FfnP& f, const LnP& ln, uint32_t site_res) -> int {
     NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, sub, x_in, r.w(ln.g), stats, dy, dym, r.g(ln.g), r.g(ln.b), r.g(f.b2), lnpart, N, d,
-                                          r.drop(site_res, n_pos, k.dropout), st));
+                                          r.drop(site_res, tgt, k.dropout), st));
     NMT_TRY(fork());
     NMT_TRY(w.wgrad(dsub, N, d, hact, F, f.w2));
     GemmEpilogue relu_bwd;
@@ -525,17 +578,18 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     return end_sublayer();
   };
   // self-attention sub-layer (fused q, k, v projection)
-  auto self_bwd = [&](half_t* dx, int N, int n_pos, const half_t* x_in, const half_t* qkv, const half_t* o, const float* lse,
+  auto self_bwd = [&](half_t* dx, int N, bool tgt, const half_t* x_in, const half_t* qkv, const half_t* o, const float* lse,
                       const half_t* sub, const float* stats, const AttnP& a, const LnP& ln, uint32_t site_res, const int32_t* key_ids,
                       int causal) -> int {
     NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, sub, x_in, r.w(ln.g), stats, dy, dym, r.g(ln.g), r.g(ln.b), r.g(a.bo), lnpart, N, d,
-                                          r.drop(site_res, n_pos, k.dropout), st));
+                                          r.drop(site_res, tgt, k.dropout), st));
     NMT_TRY(fork());
     NMT_TRY(w.wgrad(dsub, N, d, o, d, a.wo));
     NMT_TRY(r.dgrad(dsub, N, d, a.wo, d, dO));
     NMT_TRY(launch_attention_bwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, o, d, dO, d, lse, dqkv, 3 * d, dqkv + d, 3 * d,
-                                 dqkv + 2 * d, 3 * d, key_ids, k.pad_id, causal, B, H, dh, n_pos, n_pos, st));
+                                 dqkv + 2 * d, 3 * d, key_ids, k.pad_id, causal, Bt, H, dh, tgt ? maxT : maxS, tgt ? maxT : maxS,
+                                 tgt ? tab_tt : tab_ss, N, st));
     NMT_TRY(fork());
     NMT_TRY(launch_colsum(dqkv, 3 * d, w.g(a.bqkv), cspart, N, 3 * d, sd));
     NMT_TRY(w.wgrad(dqkv, N, 3 * d, x_in, d, a.wqkv));
@@ -563,19 +617,19 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     const DecW& W = p.dec[l];
     const int li = k.enc_layers + l;
     const half_t* x_in = l ? r.ws<half_t>(p.dec[l - 1].x3) : r.ws<half_t>(p.y0);
-    NMT_TRY(ffn_bwd(dx, Nt, T, r.ws<half_t>(W.x2), r.ws<half_t>(W.h), r.ws<half_t>(W.s3), r.ws<float>(W.st3), P.ffn, P.ln3,
+    NMT_TRY(ffn_bwd(dx, Nt, true, r.ws<half_t>(W.x2), r.ws<half_t>(W.h), r.ws<half_t>(W.s3), r.ws<float>(W.st3), P.ffn, P.ln3,
                     layer_site(li, kKindFfnRes)));
     // encoder-decoder attention
     NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, r.ws<half_t>(W.s2), r.ws<half_t>(W.x1), r.w(P.ln2.g), r.ws<float>(W.st2), dy, dym,
                                           r.g(P.ln2.g), r.g(P.ln2.b), r.g(P.cross.bo), lnpart, Nt, d,
-                                          r.drop(layer_site(li, kKindCrossRes), T, k.dropout), st));
+                                          r.drop(layer_site(li, kKindCrossRes), true, k.dropout), st));
     NMT_TRY(fork());
     NMT_TRY(w.wgrad(dsub, Nt, d, r.ws<half_t>(W.o2), d, P.cross.wo));
     NMT_TRY(r.dgrad(dsub, Nt, d, P.cross.wo, d, dO));
     const half_t* kv = r.ws<half_t>(W.kv);
     NMT_TRY(launch_attention_bwd(r.ws<half_t>(W.q), d, kv, 2 * d, kv + d, 2 * d, r.ws<half_t>(W.o2), d, dO, d, r.ws<float>(W.lse2), dq, d,
-                                 dkv, 2 * d, dkv + d, 2 * d, c->src, k.pad_id, 0, B, H, dh, T, S, st));
+                                 dkv, 2 * d, dkv + d, 2 * d, c->src, k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, st));
     NMT_TRY(fork());
     NMT_TRY(launch_colsum(dq, d, w.g(P.cross.bq), cspart, Nt, d, sd));
     NMT_TRY(launch_colsum(dkv, 2 * d, w.g(P.cross.bkv), cspart, Ns, 2 * d, sd));
@@ -589,7 +643,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_TRY(r.dgrad(dkv, Ns, 2 * d, P.cross.wkv, d, denc, accum));
     NMT_TRY(end_sublayer());
     // masked self-attention
-    NMT_TRY(self_bwd(dx, Nt, T, x_in, r.ws<half_t>(W.qkv), r.ws<half_t>(W.o1), r.ws<float>(W.lse1), r.ws<half_t>(W.s1),
+    NMT_TRY(self_bwd(dx, Nt, true, x_in, r.ws<half_t>(W.qkv), r.ws<half_t>(W.o1), r.ws<float>(W.lse1), r.ws<half_t>(W.s1),
                      r.ws<float>(W.st1), P.self, P.ln1, layer_site(li, kKindSelfRes), c->tgt_in, 1));
   }
   const half_t* dx_dec0 = dx;
@@ -599,16 +653,16 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     const EncP& P = c->enc[l];
     const EncW& W = p.enc[l];
     const half_t* x_in = l ? r.ws<half_t>(p.enc[l - 1].x2) : r.ws<half_t>(p.x0);
-    NMT_TRY(ffn_bwd(denc, Ns, S, r.ws<half_t>(W.x1), r.ws<half_t>(W.h), r.ws<half_t>(W.s2), r.ws<float>(W.st2), P.ffn, P.ln2,
+    NMT_TRY(ffn_bwd(denc, Ns, false, r.ws<half_t>(W.x1), r.ws<half_t>(W.h), r.ws<half_t>(W.s2), r.ws<float>(W.st2), P.ffn, P.ln2,
                     layer_site(l, kKindFfnRes)));
-    NMT_TRY(self_bwd(denc, Ns, S, x_in, r.ws<half_t>(W.qkv), r.ws<half_t>(W.o), r.ws<float>(W.lse), r.ws<half_t>(W.s1),
+    NMT_TRY(self_bwd(denc, Ns, false, x_in, r.ws<half_t>(W.qkv), r.ws<half_t>(W.o), r.ws<float>(W.lse), r.ws<half_t>(W.s1),
                      r.ws<float>(W.st1), P.attn, P.ln1, layer_site(l, kKindSelfRes), c->src, 0));
   }
 
   // ---- join, then the embeddings: both id streams add into the row gradients of the shared matrix ----
   NMT_HIP_CHECK(hipEventRecord(c->ev_join, sd));
   NMT_HIP_CHECK(hipStreamWaitEvent(st, c->ev_join, 0));
-  NMT_TRY(launch_embed_bwd(c->src, denc, Ns, r.drop(kSiteEmbSrc, S, k.dropout), c->tgt_in, dx_dec0, Nt, r.drop(kSiteEmbTgt, T, k.dropout),
+  NMT_TRY(launch_embed_bwd(c->src, denc, Ns, r.drop(kSiteEmbSrc, false, k.dropout), c->tgt_in, dx_dec0, Nt, r.drop(kSiteEmbTgt, true, k.dropout),
                            r.g(c->embed), d, V, r.ws<int32_t>(p.embscratch), st));
   return NMT_OK;
 }
@@ -672,7 +726,7 @@ extern "C" int nmt_op_attention_fwd(const void* d_Q, int32_t ldq, const void* d_
                                     void* d_O, int32_t ldo, float* d_lse, const int32_t* d_key_ids, int32_t pad_id, int32_t causal,
                                     int32_t B, int32_t H, int32_t dh, int32_t Tq, int32_t Tk, void* stream) {
   return launch_attention_fwd(static_cast<const half_t*>(d_Q), ldq, static_cast<const half_t*>(d_K), ldk, static_cast<const half_t*>(d_V),
-                              ldv, static_cast<half_t*>(d_O), ldo, d_lse, d_key_ids, pad_id, causal, B, H, dh, Tq, Tk,
+                              ldv, static_cast<half_t*>(d_O), ldo, d_lse, d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, nullptr, 0,
                               static_cast<hipStream_t>(stream));
 }
 extern "C" int nmt_op_attention_bwd(const void* d_Q, int32_t ldq, const void* d_K, int32_t ldk, const void* d_V, int32_t ldv,
@@ -683,7 +737,7 @@ extern "C" int nmt_op_attention_bwd(const void* d_Q, int32_t ldq, const void* d_
   return launch_attention_bwd(static_cast<const half_t*>(d_Q), ldq, static_cast<const half_t*>(d_K), ldk, static_cast<const half_t*>(d_V),
                               ldv, static_cast<const half_t*>(d_O), ldo, static_cast<const half_t*>(d_dO), lddo, d_lse,
                               static_cast<half_t*>(d_dQ), lddq, static_cast<half_t*>(d_dK), lddk, static_cast<half_t*>(d_dV), lddv,
-                              d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, static_cast<hipStream_t>(stream));
+                              d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int nmt_op_residual_layernorm_fwd(const void* d_sub, const void* d_resid, const void* d_gamma, const void* d_beta,

@@ -37,7 +37,7 @@ __global__ void __launch_bounds__(kThreads) embed_fwd_kernel(const int32_t* __re
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
   float v[8];
   unpack8(ld_half8(E + (size_t)id * d + c * 8), v);
-  const float pos = (float)(row % drop.n_pos);
+  const float pos = (float)drop_row_pos(drop, (uint32_t)row);
   const float sq = sqrtf((float)d);
   const float k = -logf(10000.f) / (float)d;
 #pragma unroll
@@ -547,6 +547,33 @@ int ln_nch(int d) { return d <= 512 ? 1 : (d <= 1024 ? 2 : 4); }
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------------
+// Row keys and sentence tables of a group of sub-batches: one thread per sentence.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) build_tables_kernel(const SegmentList sl, int n_sent, const uint32_t* __restrict__ uid,
+                                                               uint2* __restrict__ rk_src, uint2* __restrict__ rk_tgt,
+                                                               int4* __restrict__ tab_ss, int4* __restrict__ tab_tt,
+                                                               int4* __restrict__ tab_ts) {
+  const int sb = blockIdx.x * kThreads + threadIdx.x;
+  if (sb >= n_sent) return;
+  int seg = 0, first = 0, src0 = 0, tgt0 = 0;  // first sentence / source row / target row of the segment
+  while (seg + 1 < sl.n && sb >= first + sl.B[seg]) {
+    first += sl.B[seg];
+    src0 += sl.B[seg] * sl.S[seg];
+    tgt0 += sl.B[seg] * sl.T[seg];
+    ++seg;
+  }
+  const int b = sb - first, S = sl.S[seg], T = sl.T[seg];
+  const int srow = src0 + b * S, trow = tgt0 + b * T;
+  const uint32_t id = uid ? uid[sb] : (uint32_t)b;
+  const uint32_t hi = sl.micro[seg] << 16;
+  tab_ss[sb] = make_int4(srow, srow, S, S);
+  tab_tt[sb] = make_int4(trow, trow, T, T);
+  tab_ts[sb] = make_int4(trow, srow, T, S);
+  for (int t = 0; t < S; ++t) rk_src[srow + t] = make_uint2(id, hi | (uint32_t)t);
+  for (int t = 0; t < T; ++t) rk_tgt[trow + t] = make_uint2(id, hi | (uint32_t)t);
+}
+
 // ================================================================================================
 // launchers
 // ================================================================================================
@@ -678,6 +705,16 @@ int launch_dropout_mask(uint8_t* keep, int rows, int n_cols, const DropDev& drop
   NMT_REQUIRE(!drop.thr || drop.n_pos > 0, "dropout_mask: positions per sentence must be positive");
   const int64_t n = (int64_t)rows * ((n_cols + 7) / 8);
   hipLaunchKernelGGL(dropout_mask_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, keep, rows, n_cols, drop);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int launch_build_tables(const SegmentList& segs, int n_sent, const uint32_t* uid, uint2* rk_src, uint2* rk_tgt, int4* tab_ss,
+                        int4* tab_tt, int4* tab_ts, hipStream_t stream) {
+  NMT_REQUIRE(segs.n >= 1 && segs.n <= NMT_MAX_SEGMENTS && n_sent > 0, "build_tables: bad segment list");
+  NMT_REQUIRE(rk_src && rk_tgt && tab_ss && tab_tt && tab_ts, "build_tables: null pointer");
+  hipLaunchKernelGGL(build_tables_kernel, dim3(ceil_div(n_sent, kThreads)), dim3(kThreads), 0, stream, segs, n_sent, uid, rk_src, rk_tgt,
+                     tab_ss, tab_tt, tab_ts);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

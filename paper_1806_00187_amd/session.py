@@ -76,8 +76,9 @@ class Session:
                 nmt.nmt_destroy(c)
             self.ctxs, self.ctx = [], None
 
-    def reserve(self, B, S, T):
-        need = nmt.nmt_workspace_bytes(self.ctx, B, S, T)
+    def reserve(self, B, S=None, T=None):
+        """Workspace for one (B, S, T) batch, or for a group given as a list of (B, S, T, micro)."""
+        need = nmt.nmt_workspace_bytes_group(self.ctx, B) if S is None else nmt.nmt_workspace_bytes(self.ctx, B, S, T)
         for p in range(self.n_pipes):
             if self.workspaces[p] is None or self.workspaces[p].numel() < need:
                 torch.cuda.synchronize(self.device)
@@ -92,8 +93,30 @@ class Session:
             out["sent_uid"] = torch.from_numpy(np.ascontiguousarray(batch["sent_uid"]).astype(np.int64).astype(np.int32)).to(self.device)
         return out
 
+    @staticmethod
+    def group(dbatches, size):
+        """Stacks consecutive device sub-batches into groups of `size` that one forward / backward pass
+        processes together; sub-batch j keeps micro index j (its dropout streams)."""
+        out = []
+        for g0 in range(0, len(dbatches), size):
+            chunk = dbatches[g0:g0 + size]
+            grp = {"segs": [(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1], g0 + i) for i, b in enumerate(chunk)]}
+            for k in ("src", "tgt_in", "tgt_out"):
+                grp[k] = torch.cat([b[k].reshape(-1) for b in chunk])
+            uids = [b.get("sent_uid") for b in chunk]
+            assert all(u is None for u in uids) or all(u is not None for u in uids)
+            grp["sent_uid"] = None if uids[0] is None else torch.cat(uids)
+            out.append(grp)
+        return out
+
     # ---- the five calls ----
     def forward_loss(self, dbatch, loss_scale, step, micro=0, training=True, pipe=0):
+        """dbatch: one device sub-batch (2-D id tensors), or a group made by Session.group (then `micro` is unused)."""
+        if "segs" in dbatch:
+            self.reserve(dbatch["segs"])
+            nmt.nmt_forward_loss_group(self.ctxs[pipe], dbatch["segs"], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale,
+                                       step, self.loss_sums[pipe], self.ntoks[pipe], sent_uid=dbatch.get("sent_uid"), training=training)
+            return
         B, S = dbatch["src"].shape
         self.reserve(B, S, dbatch["tgt_in"].shape[1])
         nmt.nmt_forward_loss(self.ctxs[pipe], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step, micro,
@@ -113,7 +136,8 @@ class Session:
 
     # ---- one weight update from k micro-batches ----
     def update(self, dbatches, loss_scale, lr, t, step=None, betas=(0.9, 0.98), eps=1e-8, n_tok=None):
-        """Returns (loss_sum, n_tok, overflow flag).  n_tok (the number of non-pad target tokens of the
+        """dbatches: device sub-batches (sub-batch j gets micro index j) or groups made by Session.group.
+        Returns (loss_sum, n_tok, overflow flag).  n_tok (the number of non-pad target tokens of the
         whole update) is known to whoever built the batches; if it is not passed it is read back from
         the device, which costs one more synchronisation."""
         step = t if step is None else step

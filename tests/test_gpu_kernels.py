@@ -123,7 +123,7 @@ def test_attention_forward_and_backward_match_oracle(B, H, dh, Tq, Tk, causal):
     kv = dev16(np.concatenate([k, v], axis=1))
     dO_np = f16(np.random.default_rng(9).normal(size=(B * Tq, d)))
     o = torch.zeros(B * Tq, d, dtype=torch.float16, device=DEV)
-    lse = torch.zeros(B, H, Tq, dtype=torch.float32, device=DEV)
+    lse = torch.zeros(H, B, Tq, dtype=torch.float32, device=DEV)  # head-major: [H, B*Tq]
     ids = devi(key_ids)
     A.nmt_op_attention_fwd(qkv_q, 3 * d, kv, 2 * d, kv[:, d:], 2 * d, o, d, lse, ids, 1, causal, B, H, dh, Tq, Tk)
     assert_close16(host(o), o_ref, "attention output", rel=3e-3, l2=1.5e-3)
@@ -132,7 +132,7 @@ def test_attention_forward_and_backward_match_oracle(B, H, dh, Tq, Tk, causal):
     a = np.where(masked[:, None], -np.inf, a)
     mx = a.max(-1)
     lse_ref = mx + np.log(np.exp(a - mx[..., None]).sum(-1))
-    assert np.abs(host(lse) - lse_ref).max() < 2e-3
+    assert np.abs(host(lse).transpose(1, 0, 2) - lse_ref).max() < 2e-3
     # backward, fed with the oracle's forward output rounded to fp16
     dq_ref, dk_ref, dv_ref = O.attention_bwd(dO_np, saved, B, Tq, Tk, H)
     dq = torch.zeros(B * Tq, d, dtype=torch.float16, device=DEV)

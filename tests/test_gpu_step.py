@@ -266,3 +266,61 @@ def test_sub_batches_in_flight_give_bit_identical_updates():
         assert other[0] == outs[0][0]
         for a, b in zip(other[1:], outs[0][1:]):
             assert (a == b).all()
+
+
+def test_group_of_sub_batches_in_one_pass_matches_the_oracle_accumulation():
+    """Three sub-batches of different padded shapes stacked into one forward / backward pass: loss,
+    token count and the gradient (rounded to fp16 once, after the sum) against the oracle's per
+    sub-batch gradients accumulated; then the same update as the one-by-one path within rounding."""
+    model = dict(I.MODELS["tiny"], dropout=0.1)
+    weights = I.init_weights(seed=21, perturb=0.05, **model)
+    shapes = [(5, 9, 7), (3, 14, 12), (8, 4, 6)]
+    batches = [I.tiny_batch(seed=300 + i, B=B, S=S, T=T, vocab=model["vocab"], short_by=2) for i, (B, S, T) in enumerate(shapes)]
+    uids = [np.arange(100 * i, 100 * i + b["src"].shape[0], dtype=np.uint32) for i, b in enumerate(batches)]
+    cfg = _oracle_cfg(model, act_dropout=0.1, seed=5)
+    P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    loss_scale, step = 64.0, 3
+    acc, loss_ref, ntok_ref, allow = None, 0.0, 0, []
+    for j, mb in enumerate(batches):
+        l, n, cache = O.forward_loss(P16, cfg, mb["src"], mb["tgt_in"], mb["tgt_out"], training=True, step=step, micro=j, sent_uid=uids[j])
+        g = O.backward(P16, cfg, cache, loss_scale)
+        allow.append(_gate_allowance(P16, cfg, cache, loss_scale, g))
+        acc = O.accumulate(acc, g, j == 0)
+        loss_ref += l
+        ntok_ref += n
+    want = O.to_fp16_storage(acc)
+    allow_acc = {k: float(np.sqrt(sum(a[k] ** 2 for a in allow))) for k in allow[0]}
+
+    sess = Session(model, weights, act_dropout=0.1, seed=5, max_sentences=8)
+    try:
+        dbs = [sess.to_device(dict(mb, sent_uid=uids[j])) for j, mb in enumerate(batches)]
+        (grp,) = Session.group(dbs, 3)
+        sess.forward_loss(grp, loss_scale, step)
+        sess.backward()
+        assert int(sess.ntok.item()) == ntok_ref
+        assert abs(float(sess.loss_sum.item()) - loss_ref) / loss_ref <= LOSS_TOL
+        worst = _check_grads(sess, sess.g16, want, model["d_model"], "group g16", allow_acc)
+        print("group of 3: worst gradient rel-L2", worst)
+        g_group = host(sess.g16).astype(np.float64)
+        # one by one through the same library
+        for j, db in enumerate(dbs):
+            sess.forward_loss(db, loss_scale, step, j)
+            sess.backward()
+            sess.accumulate(j == 0)
+        g_single = host(sess.acc).astype(np.float64)
+        assert rel_l2(g_group, g_single) <= 5e-3
+    finally:
+        sess.close()
+
+
+def test_group_entry_point_rejects_bad_segment_lists():
+    model = I.MODELS["tiny"]
+    sess = Session(model, I.init_weights(seed=1, **model), max_sentences=4, max_len=16)
+    try:
+        ids = torch.full((64,), 5, dtype=torch.int32, device="cuda")
+        for segs in ([], [(5, 4, 4, 0)], [(2, 17, 4, 0)], [(2, 4, 4, 256)], [(1, 2, 2, 0)] * 65):
+            with pytest.raises(A.NmtError) as e:
+                A.nmt_forward_loss_group(sess.ctx, segs, ids, ids, ids, 1.0, 1, sess.loss_sum, sess.ntok)
+            assert e.value.code == A.NMT_EINVAL
+    finally:
+        sess.close()
