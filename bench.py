@@ -42,10 +42,10 @@ def model_flops(model, B, S, T):
     return 3 * (enc + dec + 2 * Nt * d * V)
 
 
-def gemm_shapes(model, B, S, T):
-    """(M, N, K, a_t, b_t, count) of every GEMM launch of one sub-batch's forward + backward."""
+def gemm_shapes(model, Ns, Nt):
+    """(M, N, K, a_t, b_t, count) of every GEMM launch of one forward + backward pass over Ns source
+    and Nt target positions."""
     d, F, V, Le, Ld = model["d_model"], model["d_ff"], model["vocab"], model["enc_layers"], model["dec_layers"]
-    Ns, Nt = B * S, B * T
     out = []
 
     def linear(N, n_in, n_out, count, wgrad=True, dgrad=True):
@@ -74,6 +74,7 @@ def main():
     ap.add_argument("--workload", default="big_accum", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pipes", type=int, default=3, help="sub-batches kept in flight on separate streams")
+    ap.add_argument("--group", type=int, default=1, help="sub-batches stacked into one forward/backward pass")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -99,10 +100,18 @@ def main():
     shapes = [(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1]) for b in batches]
     ntoks = [int((b["tgt_out"] != I.PAD).sum()) for b in batches]
     log(f"[bench] inputs ready in {time.time() - t0:.1f}s; sub-batch shapes (B,S,T): {shapes}")
-    sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256, n_pipes=max(1, min(args.pipes, k_micro)))
+    group = max(1, min(args.group, k_micro))
+    n_pass = -(-k_micro // group)
+    sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256, n_pipes=max(1, min(args.pipes, n_pass)))
     dbatches = [sess.to_device(b) for b in batches]
-    for b, s, t in shapes:
-        sess.reserve(b, s, t)
+    if group > 1:
+        dbatches = Session.group(dbatches, group)      # ids of a group's sub-batches back to back, still resident in HBM
+        for g in dbatches:
+            sess.reserve(g["segs"])
+    else:
+        for b, s, t in shapes:
+            sess.reserve(b, s, t)
+    pass_rows = [(sum(b * s for b, s, _ in shapes[i:i + group]), sum(b * t for b, _, t in shapes[i:i + group])) for i in range(0, k_micro, group)]
     tr = Trainer(sess, peak_lr=1e-3, warmup=4000, init_scale=128.0)
 
     # warm-up: also lets the dynamic loss scale settle (an overflowing update is skipped and halves it)
@@ -143,7 +152,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "micro_batches_per_update": k_micro,
                    "target_tokens_per_update": tokens_per_step, "padded_shapes_BST": shapes, "loss_scale": tr.scale,
-                   "overflow_updates_in_timed_region": int(sum(flags)), "sub_batches_in_flight": sess.n_pipes, "wall_ms_per_step": wall * 1e3 / args.steps},
+                   "overflow_updates_in_timed_region": int(sum(flags)), "sub_batches_per_pass": group, "passes_in_flight": sess.n_pipes, "wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": {"bound": "mfma", "kernel": "whole update (every launch of the timed region)", "achieved": achieved_tflops,
                      "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_FP16_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_update": flops_step},
@@ -152,7 +161,7 @@ def main():
 
     if not args.no_legs:
         result["phases_ms_per_update"] = phase_leg(sess, tr, dbatches, ntoks, torch)
-        result["roofline"]["gemm"] = gemm_leg(model, shapes, k_micro, A, torch, log)
+        result["roofline"]["gemm"] = gemm_leg(model, pass_rows, A, torch, log)
         result["hbm_kernels"] = hbm_leg(sess, torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(model, weights, batches[len(batches) // 2], k_micro, tokens_per_step, tr.scale, log)
@@ -200,11 +209,11 @@ def phase_leg(sess, tr, dbatches, ntoks, torch):
     return acc
 
 
-def gemm_leg(model, shapes, k_micro, A, torch, log):
+def gemm_leg(model, pass_rows, A, torch, log):
     """Every distinct GEMM of the update timed alone through nmt_op_gemm (HIP events, 10 launches
     each): algorithmic FLOPs / summed average durations = achieved rate of the GEMM kernel."""
     agg = {}
-    for s in shapes:
+    for s in pass_rows:
         for (M, N, K, a_t, b_t, count) in gemm_shapes(model, *s):
             key = (M, N, K, a_t, b_t)
             agg[key] = agg.get(key, 0) + count

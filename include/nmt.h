@@ -167,6 +167,14 @@ int nmt_op_gemm(const void* d_A, int32_t a_t, int32_t lda, const void* d_B, int3
                 int32_t relu, const nmt_dropout* drop, const void* d_add, const void* d_relu_src,
                 float mask_scale, void* stream);
 
+/* The same product without epilogue, with the contraction cut into `splits` (1..64; 0 = chosen by
+ * the library) equal pieces whose fp32 partial results go to d_partial (partial_floats >= splits *
+ * M * N floats, 16-byte aligned) and are summed in increasing k order by a second kernel: the form
+ * used for weight gradients, whose contraction runs over all positions of a pass. */
+int nmt_op_gemm_splitk(const void* d_A, int32_t a_t, int32_t lda, const void* d_B, int32_t b_t, int32_t ldb,
+                       void* d_C, int32_t ldc, int32_t M, int32_t N, int32_t K, float* d_partial,
+                       int64_t partial_floats, int32_t splits, void* stream);
+
 /* Masked multi-head attention forward.  Q [B*Tq, *] with row stride ldq (head h at columns
  * h*dh..), K, V [B*Tk, *]; O [B*Tq, *]; d_lse fp32 = log-sum-exp of the scaled
  * scores, stored [H, B*Tq] (head-major).  Key j of sentence b is hidden iff d_key_ids[b*Tk + j] == pad_id, or causal != 0 and

@@ -133,8 +133,11 @@ struct GemmEpilogue {
   const half_t* relu_src = nullptr;
   float mask_scale = 1.f;
 };
+// partial: optional fp32 scratch of partial_floats floats for cutting the contraction into `splits`
+// pieces summed by a second kernel (splits == 0: the launcher decides; needs an empty epilogue).
 int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc,
-                int M, int N, int K, const GemmEpilogue& ep, hipStream_t stream);
+                int M, int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial = nullptr,
+                int64_t partial_floats = 0, int splits = 1);
 
 int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O,
                          int ldo, float* lse, const int32_t* key_ids, int pad_id, int causal, int B, int H,

@@ -49,6 +49,10 @@ struct GemmArgs {
   int lda, ldb, ldc, M, N, K;
   int tiles_m, tiles_n, tm_fast;
   GemmEpilogue ep;
+  // split-K: work-group (tile, z) contracts k in [z * k_chunk, min(K, (z + 1) * k_chunk)) and writes its
+  // fp32 tile to partial[z][M][N]; partial == nullptr: one work-group per tile, epilogue, fp16 result
+  float* partial;
+  int k_chunk;
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const half_t* p, uint32_t bytes) {
@@ -257,8 +261,10 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
   const typename OpA::Frag fa = OpA::frag_init(wm * WM, lane);
   const typename OpB::Frag fb = OpB::frag_init(wn * WN, lane);
 
+  const int k_base = g.partial ? (int)blockIdx.y * g.k_chunk : 0;
+  const int k_end = g.partial ? min(g.K, k_base + g.k_chunk) : g.K;
   auto request = [&](unsigned char* stage, int k0) {  // asynchronous: tile k0 streams into `stage`
-    const int kleft = g.K - k0;
+    const int kleft = k_end - k0;
     opa.load(make_rsrc(OpA::origin(g.A, g.lda, m0, k0), OpA::extent(rows_a, g.lda, kleft)), stage, kleft);
     opb.load(make_rsrc(OpB::origin(g.B, g.ldb, n0, k0), OpB::extent(rows_b, g.ldb, kleft)), stage + OpA::BYTES, kleft);
     __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of the products they overlap with
@@ -299,27 +305,27 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
 
   // A k-tile past the end reads zeros (it lies outside the extent of its buffer descriptor) and
   // multiplying it changes nothing, so the loop always runs whole rings and carries no edge conditions.
-  const int nk = (g.K + BK - 1) / BK;
-  request(stage0, 0);
-  request(stage1, BK);
+  const int nk = (k_end - k_base + BK - 1) / BK;
+  request(stage0, k_base);
+  request(stage1, k_base + BK);
   if constexpr (NS == 4) {
-    request(stage2, 2 * BK);
-    request(stage3, 3 * BK);
+    request(stage2, k_base + 2 * BK);
+    request(stage3, k_base + 3 * BK);
   }
   __builtin_amdgcn_s_waitcnt(wait_vm((NS - 1) * kPerTile));
   __builtin_amdgcn_s_barrier();
   fetch(stage0, 0, 0);
   if constexpr (NS == 2) {
     for (int kt = 0; kt < nk; kt += 2) {
-      k_tile(stage0, stage1, (kt + 2) * BK);
-      k_tile(stage1, stage0, (kt + 3) * BK);
+      k_tile(stage0, stage1, k_base + (kt + 2) * BK);
+      k_tile(stage1, stage0, k_base + (kt + 3) * BK);
     }
   } else {
     for (int kt = 0; kt < nk; kt += 4) {
-      k_tile(stage0, stage1, (kt + 4) * BK);
-      k_tile(stage1, stage2, (kt + 5) * BK);
-      k_tile(stage2, stage3, (kt + 6) * BK);
-      k_tile(stage3, stage0, (kt + 7) * BK);
+      k_tile(stage0, stage1, k_base + (kt + 4) * BK);
+      k_tile(stage1, stage2, k_base + (kt + 5) * BK);
+      k_tile(stage2, stage3, k_base + (kt + 6) * BK);
+      k_tile(stage3, stage0, k_base + (kt + 7) * BK);
     }
   }
   __builtin_amdgcn_s_waitcnt(wait_vm_lds(0));  // the last refills (all zeros) must land before the stages are reused
@@ -354,6 +360,12 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
           float v[8];
           const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + rl * SW + c8 * 8);
           const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + rl * SW + c8 * 8 + 4);
+          if (g.partial) {
+            float* dst = g.partial + ((size_t)blockIdx.y * g.M + gr) * g.N + gc;
+            *reinterpret_cast<floatx4*>(dst) = lo;
+            *reinterpret_cast<floatx4*>(dst + 4) = hi;
+            continue;
+          }
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             v[e] = lo[e];
@@ -394,23 +406,59 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
   }
 }
 
+// C[m, n] = fp16(sum_z partial[z][m][n]), 8 columns per thread, splits summed in increasing order
+__global__ void __launch_bounds__(kThreads) splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N,
+                                                                half_t* __restrict__ C, int ldc) {
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int chunks = N >> 3;
+  if (gid >= (int64_t)M * chunks) return;
+  const int row = (int)(gid / chunks), c8 = (int)(gid % chunks);
+  const size_t off = (size_t)row * N + c8 * 8, plane = (size_t)M * N;
+  floatx4 lo = *reinterpret_cast<const floatx4*>(partial + off), hi = *reinterpret_cast<const floatx4*>(partial + off + 4);
+  for (int z = 1; z < splits; ++z) {
+    lo += *reinterpret_cast<const floatx4*>(partial + z * plane + off);
+    hi += *reinterpret_cast<const floatx4*>(partial + z * plane + off + 4);
+  }
+  half8_t o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    o[e] = (half_t)lo[e];
+    o[4 + e] = (half_t)hi[e];
+  }
+  st_half8(C + (size_t)row * ldc + c8 * 8, o);
+}
+
 template <int BM, int BN, bool AT, bool BT, int BK, int NS>
-int launch_variant(const GemmArgs& g, hipStream_t stream) {
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT, BK, NS>), dim3(g.tiles_m * g.tiles_n), dim3(kThreads), 0, stream, g);
+int launch_variant(const GemmArgs& g, int splits, hipStream_t stream) {
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT, BK, NS>), dim3(g.tiles_m * g.tiles_n, splits), dim3(kThreads), 0, stream, g);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 
 template <int BM, int BN, int BK, int NS>
-int launch_tile(const GemmArgs& a, bool a_t, bool b_t, hipStream_t stream) {
+int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t stream) {
   GemmArgs g = a;
   g.tiles_m = ceil_div(g.M, BM);
   g.tiles_n = ceil_div(g.N, BN);
   g.tm_fast = g.M <= g.N;
-  if (!a_t && !b_t) return launch_variant<BM, BN, false, false, BK, NS>(g, stream);
-  if (!a_t && b_t) return launch_variant<BM, BN, false, true, BK, NS>(g, stream);
-  if (a_t && b_t) return launch_variant<BM, BN, true, true, BK, NS>(g, stream);
-  return launch_variant<BM, BN, true, false, BK, NS>(g, stream);
+  if (splits > 1) {
+    g.k_chunk = (int)round_up(ceil_div(g.K, splits), BK);
+    splits = ceil_div(g.K, g.k_chunk);  // no empty split
+  }
+  if (splits <= 1) {
+    g.partial = nullptr;
+    splits = 1;
+  }
+  int rc;
+  if (!a_t && !b_t) rc = launch_variant<BM, BN, false, false, BK, NS>(g, splits, stream);
+  else if (!a_t && b_t) rc = launch_variant<BM, BN, false, true, BK, NS>(g, splits, stream);
+  else if (a_t && b_t) rc = launch_variant<BM, BN, true, true, BK, NS>(g, splits, stream);
+  else rc = launch_variant<BM, BN, true, false, BK, NS>(g, splits, stream);
+  if (rc != NMT_OK || splits == 1) return rc;
+  const int64_t n = (int64_t)g.M * (g.N / 8);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, g.partial, splits, g.M, g.N, g.C, g.ldc);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
 }
 
 // Estimated efficiency of a tile shape on a (M, N) problem: useful fraction of the padded tiles,
@@ -428,7 +476,7 @@ double tile_score(int M, int N, int bm, int bn, int per_cu, double shape_eff) {
 }  // namespace
 
 int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc, int M,
-                int N, int K, const GemmEpilogue& ep, hipStream_t stream) {
+                int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial, int64_t partial_floats, int splits) {
   NMT_REQUIRE(M > 0 && N > 0 && K > 0, "gemm: empty problem M=%d N=%d K=%d", M, N, K);
   NMT_REQUIRE(A && B && C, "gemm: null operand");
   NMT_REQUIRE(aligned16(A) && aligned16(B) && aligned16(C), "gemm: operands must be 16-byte aligned");
@@ -438,22 +486,41 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   NMT_REQUIRE(lda <= (1 << 20) && ldb <= (1 << 20) && ldc <= (1 << 20), "gemm: leading dimensions above 2^20 are not supported");
   NMT_REQUIRE(!ep.bias || aligned16(ep.bias), "gemm: bias must be 16-byte aligned");
   NMT_REQUIRE((!ep.add || aligned16(ep.add)) && (!ep.relu_src || aligned16(ep.relu_src)), "gemm: epilogue operand misaligned");
-  GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, ep};
-  if (const char* force = getenv("NMT_GEMM_TILE")) {  // tuning aid: force one tile shape
-    if (!strcmp(force, "256x256")) return launch_tile<256, 256, 32, 4>(g, a_t, b_t, stream);
-    if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, stream);
-    if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, stream);
-    if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, stream);
-    if (!strcmp(force, "128x64")) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, stream);
-    if (!strcmp(force, "64x128")) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, stream);
-    if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, stream);
+  NMT_REQUIRE(splits >= 0 && splits <= 64, "gemm: number of k splits %d outside [0, 64]", splits);
+  const bool plain = !ep.bias && !ep.relu && !ep.drop.thr && !ep.add && !ep.relu_src;
+  NMT_REQUIRE(splits <= 1 || (partial && plain), "gemm: splitting k needs a partial-sum buffer and no epilogue");
+  NMT_REQUIRE(!partial || (reinterpret_cast<uintptr_t>(partial) & 15u) == 0, "gemm: partial-sum buffer must be 16-byte aligned");
+  GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, ep, partial, 0};
+  const int64_t plane = (int64_t)M * N;
+  if (splits == 0) {  // choose: a short, wide problem (a weight gradient over many positions) is cut along k
+    splits = 1;
+    if (partial && plain) {
+      const int64_t tiles = (int64_t)ceil_div(M, 128) * ceil_div(N, 128);
+      int want = (int)((768 + tiles - 1) / tiles);   // about three work-groups per compute unit
+      want = want < K / 2048 ? want : K / 2048;      // and at least 2048 k per split
+      want = want < 64 ? want : 64;
+      if (want >= 2 && plane * want <= partial_floats) splits = want;
+      else if (want >= 2 && partial_floats / plane >= 2) splits = (int)(partial_floats / plane);
+    }
   }
+  NMT_REQUIRE(splits == 1 || plane * splits <= partial_floats, "gemm: partial-sum buffer of %lld floats too small for %d splits",
+              (long long)partial_floats, splits);
+  if (const char* force = getenv("NMT_GEMM_TILE")) {  // tuning aid: force one tile shape
+    if (!strcmp(force, "256x256")) return launch_tile<256, 256, 32, 4>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "128x64")) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "64x128")) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, splits, stream);
+  }
+  if (splits > 1) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
   const double s128 = tile_score(M, N, 128, 128, 2, 1.0);
   const double s12864 = tile_score(M, N, 128, 64, 2, 0.85);
   const double s64128 = tile_score(M, N, 64, 128, 2, 0.85);
   const double s64 = tile_score(M, N, 64, 64, 4, 0.65);
-  if (s128 >= s12864 && s128 >= s64128 && s128 >= s64) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, stream);
-  if (s12864 >= s64128 && s12864 >= s64) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, stream);
-  if (s64128 >= s64) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, stream);
-  return launch_tile<64, 64, 64, 2>(g, a_t, b_t, stream);
+  if (s128 >= s12864 && s128 >= s64128 && s128 >= s64) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, 1, stream);
+  if (s12864 >= s64128 && s12864 >= s64) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, 1, stream);
+  if (s64128 >= s64) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, 1, stream);
+  return launch_tile<64, 64, 64, 2>(g, a_t, b_t, 1, stream);
 }

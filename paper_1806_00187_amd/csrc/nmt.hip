@@ -60,6 +60,7 @@ struct DecP { AttnP self; LnP ln1; AttnP cross; LnP ln2; FfnP ffn; LnP ln3; };
 
 // dropout sites: a site id selects an independent random stream
 constexpr int kMaxSegments = NMT_MAX_SEGMENTS;
+constexpr int64_t kWgradPartialFloats = 16ll << 20;
 constexpr uint32_t kSiteEmbSrc = 0, kSiteEmbTgt = 1;
 constexpr uint32_t kKindSelfRes = 0, kKindCrossRes = 1, kKindFfnAct = 2, kKindFfnRes = 3;
 inline uint32_t layer_site(int layer_index, uint32_t kind) { return 16u * (1u + (uint32_t)layer_index) + kind; }
@@ -73,7 +74,7 @@ struct Plan {
   int64_t x0, y0, logits, rowloss;
   std::vector<EncW> enc;
   std::vector<DecW> dec;
-  int64_t dx_dec, dx_enc, dy[2], dym[2], dO, dqkv[2], dh[2], dq[2], dkv[2], lnpart, cspart, embscratch;
+  int64_t dx_dec, dx_enc, dy[2], dym[2], dO, dqkv[2], dh[2], dq[2], dkv[2], lnpart, cspart, embscratch, wgpart, wgpart_floats;
   int64_t total;
 };
 
@@ -212,6 +213,9 @@ int64_t plan_workspace(const nmt_ctx* c, const GroupDims& gd, Plan& p) {
   const int64_t widest = F > 3 * d ? F : 3 * d;
   p.cspart = take(colsum_scratch_floats((int)widest) * f4);
   p.embscratch = take(embed_bwd_scratch_ints((int)V, (int)(Ns + Nt)) * (int64_t)sizeof(int32_t));
+  // fp32 partial sums of weight-gradient products cut along the (long) position axis
+  p.wgpart_floats = Nm >= 4096 ? kWgradPartialFloats : 0;
+  p.wgpart = take(p.wgpart_floats * f4);
   p.total = cur;
   return cur;
 }
@@ -376,7 +380,8 @@ struct Run {
   }
   // gW[out, in] = dy^T x
   int wgrad(const half_t* dy, int N, int out, const half_t* x, int in, int64_t gW) const {
-    return launch_gemm(dy, true, out, x, true, in, c->g16 + gW, in, out, in, N, GemmEpilogue{}, st);
+    return launch_gemm(dy, true, out, x, true, in, c->g16 + gW, in, out, in, N, GemmEpilogue{}, st,
+                       c->plan.wgpart_floats ? ws<float>(c->plan.wgpart) : nullptr, c->plan.wgpart_floats, 0);
   }
 };
 
@@ -720,6 +725,15 @@ extern "C" int nmt_op_gemm(const void* d_A, int32_t a_t, int32_t lda, const void
   ep.mask_scale = mask_scale;
   return launch_gemm(static_cast<const half_t*>(d_A), a_t != 0, lda, static_cast<const half_t*>(d_B), b_t != 0, ldb,
                      static_cast<half_t*>(d_C), ldc, M, N, K, ep, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int nmt_op_gemm_splitk(const void* d_A, int32_t a_t, int32_t lda, const void* d_B, int32_t b_t, int32_t ldb, void* d_C,
+                                  int32_t ldc, int32_t M, int32_t N, int32_t K, float* d_partial, int64_t partial_floats,
+                                  int32_t splits, void* stream) {
+  NMT_REQUIRE(d_partial && partial_floats > 0, "nmt_op_gemm_splitk: the partial-sum buffer is required");
+  return launch_gemm(static_cast<const half_t*>(d_A), a_t != 0, lda, static_cast<const half_t*>(d_B), b_t != 0, ldb,
+                     static_cast<half_t*>(d_C), ldc, M, N, K, GemmEpilogue{}, static_cast<hipStream_t>(stream), d_partial, partial_floats,
+                     splits);
 }
 
 extern "C" int nmt_op_attention_fwd(const void* d_Q, int32_t ldq, const void* d_K, int32_t ldk, const void* d_V, int32_t ldv,

@@ -54,6 +54,19 @@ def test_gemm_matches_oracle(M, N, K, mode):
     assert_close16(host(dC), Am @ Bm.T, f"gemm {mode} {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,N,K,splits", [(136, 264, 3003, 3), (256, 128, 8192, 0), (64, 64, 4500, 64), (1024, 512, 6000, 5)])
+def test_gemm_split_along_k_matches_oracle(M, N, K, splits):
+    """Weight-gradient form (both operands stored [K, rows]) with the contraction cut into pieces."""
+    rng = np.random.default_rng(M + N + K)
+    Am, Bm = f16(rng.normal(size=(M, K))), f16(rng.normal(size=(N, K)) / math.sqrt(K))
+    dC = torch.full((M, N + 8), float("nan"), dtype=torch.float16, device=DEV)
+    part = torch.full((max(splits, 8) * M * N,), float("nan"), dtype=torch.float32, device=DEV)
+    A.nmt_op_gemm_splitk(dev16(Am.T), 1, M, dev16(Bm.T), 1, N, dC, N + 8, M, N, K, part, splits)
+    assert_close16(host(dC)[:, :N], Am @ Bm.T, f"split-k gemm {M}x{N}x{K}/{splits}")
+    with pytest.raises(A.NmtError):
+        A.nmt_op_gemm_splitk(dev16(Am.T), 1, M, dev16(Bm.T), 1, N, dC, N + 8, M, N, K, part[: M * N], 2)
+
+
 def test_gemm_epilogues_match_oracle():
     rng = np.random.default_rng(5)
     M, N, K, n_pos = 3 * 50, 256, 64, 50
