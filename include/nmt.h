@@ -226,9 +226,10 @@ int nmt_op_colsum(const void* d_src, int32_t ld, void* d_dst, float* d_partial, 
 
 /* Embedding backward: d_gE[v, :] = fp16(float(d_gE[v, :]) + sqrt(d) * sum over positions r with
  * ids[r] == v of dropout-masked d_dx[r, :]), for two id streams (source then target) at once.
- * Deterministic: positions are summed in increasing order.  d_scratch: int32 scratch of
- * nmt_op_embed_bwd_scratch(vocab, rows_a + rows_b) int32 elements. */
-int64_t nmt_op_embed_bwd_scratch(int32_t vocab, int32_t rows_total);
+ * Deterministic: every sum is formed in a fixed order (increasing position within blocks of 64
+ * positions of an id, then block after block).  d_scratch: 16-byte aligned int32 scratch of
+ * nmt_op_embed_bwd_scratch(vocab, rows_a + rows_b, d) int32 elements.  vocab <= 65536. */
+int64_t nmt_op_embed_bwd_scratch(int32_t vocab, int32_t rows_total, int32_t d);
 int nmt_op_embed_bwd(const int32_t* d_ids_a, const void* d_dx_a, int32_t rows_a, const nmt_dropout* drop_a,
                      const int32_t* d_ids_b, const void* d_dx_b, int32_t rows_b, const nmt_dropout* drop_b,
                      void* d_gE, int32_t d, int32_t vocab, int32_t* d_scratch, void* stream);

@@ -69,7 +69,7 @@ _SIGNATURES = {
     "nmt_op_softmax_xent": (C.c_int, [_P, _P, _P, _I32, _I32, _I32, _F, _F, _P, _P, _P]),
     "nmt_op_colsum_scratch": (_I64, [_I32]),
     "nmt_op_colsum": (C.c_int, [_P, _I32, _P, _P, _I32, _I32, _P]),
-    "nmt_op_embed_bwd_scratch": (_I64, [_I32, _I32]),
+    "nmt_op_embed_bwd_scratch": (_I64, [_I32, _I32, _I32]),
     "nmt_op_embed_bwd": (C.c_int, [_P, _P, _I32, _DP, _P, _P, _I32, _DP, _P, _I32, _I32, _P, _P]),
     "nmt_op_accumulate": (C.c_int, [_P, _P, _I64, _I32, _P]),
     "nmt_op_check_overflow": (C.c_int, [_P, _I64, _F, _P, _P]),
@@ -275,8 +275,8 @@ def nmt_op_colsum(src, ld, dst, partial, rows, cols, stream=None):
     _check(load().nmt_op_colsum(_p(src), ld, _p(dst), _p(partial), rows, cols, _stream(stream)))
 
 
-def nmt_op_embed_bwd_scratch(vocab, rows_total):
-    return load().nmt_op_embed_bwd_scratch(vocab, rows_total)
+def nmt_op_embed_bwd_scratch(vocab, rows_total, d):
+    return load().nmt_op_embed_bwd_scratch(vocab, rows_total, d)
 
 
 def nmt_op_embed_bwd(ids_a, dx_a, rows_a, drop_a, ids_b, dx_b, rows_b, drop_b, gE, d, vocab, scratch, stream=None):

@@ -1,7 +1,14 @@
 // Fused masked multi-head attention for gfx950: forward with online softmax, and backward as two
 // kernels (dK/dV: a wavefront owns 32 keys and sweeps the queries; dQ: a wavefront owns 32 queries
-// and sweeps the keys).  K/V (or Q/dO) tiles of one (sentence, head) live in LDS; scores never go
-// to memory.  All products run on 32x32x16 fp16 MFMAs.
+// and sweeps the keys).  Scores never go to memory.  All products run on 32x32x16 fp16 MFMAs.
+//
+// Sentences here are short (tens of positions), so the unit of work is small: ONE WAVEFRONT per
+// (sentence, head, 32-row tile), four heads of a sentence per work-group, and no work-group
+// barrier anywhere.  Operands whose contraction index is contiguous in memory (Q, K, V, dO rows
+// against the head dimension) are loaded from global memory straight into MFMA operand registers,
+// 16 bytes per lane.  An operand that is contracted over its row index (V in P V, K in dS K, Q and
+// dO in dS^T Q and P^T dO) passes through a wavefront-private 32-row LDS tile and comes back through
+// the transposing LDS read.
 //
 // Register layouts (v_mfma_f32_32x32x16_f16, D = A x B): A lane l holds row l%32, k = 8*(l/32)+j;
 // B lane l holds column l%32, same k; D lane l holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4
@@ -18,8 +25,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kQC = 64;   // queries staged per pass of the dK/dV kernel
-constexpr int kKC = 128;  // keys staged per pass of the dQ kernel
 
 struct AttnArgs {
   const half_t *Q, *K, *V, *O, *dO;
@@ -45,15 +50,6 @@ __device__ __forceinline__ Sent sentence(const AttnArgs& a, int b) {
   return Sent{b * a.Tq, b * a.Tk, a.Tq, a.Tk};
 }
 
-__device__ __forceinline__ half8_t join4(half4_t a, half4_t b) {
-  half8_t r;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    r[e] = a[e];
-    r[4 + e] = b[e];
-  }
-  return r;
-}
 __device__ __forceinline__ floatx16 zero16() {
   floatx16 z;
 #pragma unroll
@@ -85,65 +81,95 @@ __device__ __forceinline__ half8_t tr_frag(const half_t* x, int pitch, int kbase
   return __builtin_bit_cast(half8_t, r);
 }
 
-// Stage rows [r_begin, r_begin + nrows_pad) of a [*, DH] head slice into LDS, row-major (pitch DH+8);
-// rows >= r_end are zero.
+// The wavefront's own work item: sentence b, head h, 32-row tile `tile`.
+struct Item {
+  int b, h, tile;
+  bool live;
+};
+__device__ __forceinline__ Item work_item(const AttnArgs& a) {
+  const int hg = (a.H + 3) >> 2;  // groups of four heads
+  Item it;
+  it.b = blockIdx.x / hg;
+  it.h = (blockIdx.x % hg) * 4 + (threadIdx.x >> 6);
+  it.tile = blockIdx.y;
+  it.live = it.h < a.H;
+  return it;
+}
+
+// 32 rows of a [*, DH] head slice as MFMA operand registers: lane l gets row row0 + l%32, columns
+// 16*s + 8*(l/32) .. +7 for every k-step s; rows >= row_end are zero.
 template <int DH>
-__device__ __forceinline__ void stage_rows(const half_t* __restrict__ src, int ld, int r_begin, int r_end, int nrows_pad,
-                                           half_t* row_major) {
-  constexpr int CH = DH / 8, PR = DH + 8;
-  for (int idx = threadIdx.x; idx < nrows_pad * CH; idx += kThreads) {
-    const int rl = idx / CH, c = idx % CH;
-    const int r = r_begin + rl;
-    st_half8(row_major + rl * PR + c * 8, r < r_end ? ld_half8(src + (size_t)r * ld + c * 8) : zero_half8());
-  }
+__device__ __forceinline__ void load_rows(const half_t* __restrict__ base, int ld, int row0, int row_end, int lane, half8_t (&f)[DH / 16]) {
+  const int row = row0 + (lane & 31);
+  const half_t* p = base + (size_t)row * ld + 8 * (lane >> 5);
+#pragma unroll
+  for (int s = 0; s < DH / 16; ++s) f[s] = row < row_end ? ld_half8(p + s * 16) : zero_half8();
+}
+// The same registers written to the wavefront's LDS tile in row-major order (pitch DH+8 halfs).
+template <int DH>
+__device__ __forceinline__ void put_rows(half_t* tile, int lane, const half8_t (&f)[DH / 16]) {
+  half_t* p = tile + (lane & 31) * (DH + 8) + 8 * (lane >> 5);
+#pragma unroll
+  for (int s = 0; s < DH / 16; ++s) st_half8(p + s * 16, f[s]);
+}
+// Orders the wavefront's LDS accesses: what other lanes wrote before is visible after (LDS
+// instructions of one wavefront execute in order; this keeps the compiler from reordering them).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// Bit k of the result: key row0 + k (k < 32) is hidden from every query (padding or past the end).
+__device__ __forceinline__ uint32_t hidden_keys(const AttnArgs& a, const Sent& se, int row0, int lane) {
+  const int key = row0 + (lane & 31);
+  const bool hid = key >= se.Tk || (a.key_ids && a.key_ids[se.k0 + key] == a.pad_id);
+  return (uint32_t)__ballot(hid);
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward
+// forward: the wavefront owns 32 queries
 // ------------------------------------------------------------------------------------------------
 template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-  const Sent se = sentence(a, b);
-  if ((int)blockIdx.y * 128 >= se.Tq) return;
-  const int KP = (se.Tk + 31) & ~31;
-  half_t* Ks = reinterpret_cast<half_t*>(smem_raw);
-  half_t* Vs = Ks + KP * PR;
-  uint8_t* hidk = reinterpret_cast<uint8_t*>(Vs + KP * PR);
-
-  stage_rows<DH>(a.K + (size_t)se.k0 * a.ldk + h * DH, a.ldk, 0, se.Tk, KP, Ks);
-  stage_rows<DH>(a.V + (size_t)se.k0 * a.ldv + h * DH, a.ldv, 0, se.Tk, KP, Vs);
-  for (int k = threadIdx.x; k < KP; k += kThreads) hidk[k] = (k >= se.Tk) || (a.key_ids && a.key_ids[se.k0 + k] == a.pad_id);
-  __syncthreads();
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int q0 = blockIdx.y * 128 + wave * 32;
+  const Item it = work_item(a);
+  if (!it.live) return;
+  const Sent se = sentence(a, it.b);
+  const int q0 = it.tile * 32;
   if (q0 >= se.Tq) return;
+  const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
+  half_t* Vs = reinterpret_cast<half_t*>(smem_raw) + (threadIdx.x >> 6) * (32 * PR);
+  const half_t* Kb = a.K + (size_t)se.k0 * a.ldk + h * DH;
+  const half_t* Vb = a.V + (size_t)se.k0 * a.ldv + h * DH;
+
   const int q = q0 + (lane & 31);
   const bool qvalid = q < se.Tq;
   half8_t qf[KS];
-#pragma unroll
-  for (int s = 0; s < KS; ++s)
-    qf[s] = qvalid ? ld_half8(a.Q + (size_t)(se.q0 + q) * a.ldq + h * DH + s * 16 + g * 8) : zero_half8();
+  load_rows<DH>(a.Q + (size_t)se.q0 * a.ldq + h * DH, a.ldq, q0, se.Tq, lane, qf);
 
   const float sc = rsqrtf((float)DH) * kLog2e;
   float m = -1e30f, l = 0.f;
   floatx16 oacc[DT];
 #pragma unroll
   for (int t = 0; t < DT; ++t) oacc[t] = zero16();
-  int nkt = KP / 32;
+  int nkt = (se.Tk + 31) >> 5;
   if (a.causal) nkt = min(nkt, (q0 + 31) / 32 + 1);
   for (int kt = 0; kt < nkt; ++kt) {
+    half8_t kf[KS], vf[KS];
+    load_rows<DH>(Kb, a.ldk, kt * 32, se.Tk, lane, kf);
+    load_rows<DH>(Vb, a.ldv, kt * 32, se.Tk, lane, vf);
+    const uint32_t hm = hidden_keys(a, se, kt * 32, lane);
+    wave_sync();  // the previous tile's reads are done
+    put_rows<DH>(Vs, lane, vf);
     floatx16 s = zero16();
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s = MFMA(ld_half8(Ks + (kt * 32 + (lane & 31)) * PR + ks * 16 + g * 8), qf[ks], s);
+    for (int ks = 0; ks < KS; ++ks) s = MFMA(kf[ks], qf[ks], s);
     float tmax = -1e30f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int key = kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-      const bool hid = hidk[key] || (a.causal && key > q);
+      const int kl = 8 * (r >> 2) + 4 * g + (r & 3);
+      const bool hid = ((hm >> kl) & 1u) || (a.causal && kt * 32 + kl > q);
       s[r] = hid ? -INFINITY : s[r] * sc;
       tmax = fmaxf(tmax, s[r]);
     }
@@ -160,14 +186,13 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
       pf[r >> 3][r & 7] = (half_t)p;
     }
     l = l * alpha + psum;
+    wave_sync();  // the V tile is in LDS
 #pragma unroll
     for (int t = 0; t < DT; ++t) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[t][r] *= alpha;
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        oacc[t] = MFMA(tr_frag<DH>(Vs, PR, kt * 32 + 16 * s2 + 4 * g, t, lane), pf[s2], oacc[t]);
-      }
+      for (int s2 = 0; s2 < 2; ++s2) oacc[t] = MFMA(tr_frag<DH>(Vs, PR, 16 * s2 + 4 * g, t, lane), pf[s2], oacc[t]);
     }
   }
   l += __shfl_xor(l, 32, kWave);
@@ -189,31 +214,31 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, dK and dV
+// backward, dK and dV: the wavefront owns 32 keys
 // ------------------------------------------------------------------------------------------------
 template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a) {
-  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, CH = DH / 8;
+  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
+  constexpr int WAVE_LDS = 2 * 32 * PR * 2 + 2 * 32 * 4;  // Q and dO tiles, lse and D of the tile's queries
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  half_t* Qs = reinterpret_cast<half_t*>(smem_raw);
-  half_t* dOs = Qs + kQC * PR;
-  float* lse_s = reinterpret_cast<float*>(dOs + kQC * PR);
-  float* D_s = lse_s + kQC;
+  const Item it = work_item(a);
+  if (!it.live) return;
+  const Sent se = sentence(a, it.b);
+  const int k0 = it.tile * 32;
+  if (k0 >= se.Tk) return;
+  const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
+  unsigned char* mine = smem_raw + (threadIdx.x >> 6) * WAVE_LDS;
+  half_t* Qs = reinterpret_cast<half_t*>(mine);
+  half_t* dOs = Qs + 32 * PR;
+  float* lse_s = reinterpret_cast<float*>(dOs + 32 * PR);
+  float* D_s = lse_s + 32;
 
-  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-  const Sent se = sentence(a, b);
-  if ((int)blockIdx.y * 128 >= se.Tk) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int k0 = blockIdx.y * 128 + wave * 32;
   const int key = k0 + (lane & 31);
   const bool kvalid = key < se.Tk;
   const bool khid = !kvalid || (a.key_ids && a.key_ids[se.k0 + key] == a.pad_id);
   half8_t kf[KS], vf[KS];
-#pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    kf[s] = kvalid ? ld_half8(a.K + (size_t)(se.k0 + key) * a.ldk + h * DH + s * 16 + g * 8) : zero_half8();
-    vf[s] = kvalid ? ld_half8(a.V + (size_t)(se.k0 + key) * a.ldv + h * DH + s * 16 + g * 8) : zero_half8();
-  }
+  load_rows<DH>(a.K + (size_t)se.k0 * a.ldk + h * DH, a.ldk, k0, se.Tk, lane, kf);
+  load_rows<DH>(a.V + (size_t)se.k0 * a.ldv + h * DH, a.ldv, k0, se.Tk, lane, vf);
   floatx16 dKt[DT], dVt[DT];
 #pragma unroll
   for (int t = 0; t < DT; ++t) {
@@ -224,58 +249,60 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
   const half_t* Qb = a.Q + (size_t)se.q0 * a.ldq + h * DH;
   const half_t* dOb = a.dO + (size_t)se.q0 * a.lddo + h * DH;
   const half_t* Ob = a.O + (size_t)se.q0 * a.ldo + h * DH;
+  const float* lse_b = a.lse + (size_t)h * a.Nq + se.q0;
 
-  for (int qc = 0; qc < se.Tq; qc += kQC) {
-    __syncthreads();
-    stage_rows<DH>(Qb, a.ldq, qc, se.Tq, kQC, Qs);
-    stage_rows<DH>(dOb, a.lddo, qc, se.Tq, kQC, dOs);
-    // D[q] = sum_dh dO[q,dh] * O[q,dh]: CH consecutive lanes share a row
-    for (int idx = threadIdx.x; idx < kQC * CH; idx += kThreads) {
-      const int rl = idx / CH, c = idx % CH, q = qc + rl;
-      float part = 0.f;
-      if (q < se.Tq) {
-        const half8_t dv = ld_half8(dOb + (size_t)q * a.lddo + c * 8), ov = ld_half8(Ob + (size_t)q * a.ldo + c * 8);
+  const int nqt = (se.Tq + 31) >> 5;
+  for (int qt = a.causal ? k0 >> 5 : 0; qt < nqt; ++qt) {  // causal: earlier query tiles precede every key of this tile
+    half8_t qf[KS], dof[KS], of[KS];
+    load_rows<DH>(Qb, a.ldq, qt * 32, se.Tq, lane, qf);
+    load_rows<DH>(dOb, a.lddo, qt * 32, se.Tq, lane, dof);
+    load_rows<DH>(Ob, a.ldo, qt * 32, se.Tq, lane, of);
+    const int ql = qt * 32 + (lane & 31);
+    const float lse_q = ql < se.Tq ? lse_b[ql] * kLog2e : 0.f;
+    // D[q] = sum_dh dO[q,dh] * O[q,dh]: lanes l and l+32 hold the two halves of row q
+    float Dq = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) part += (float)dv[e] * (float)ov[e];
-      }
+    for (int s = 0; s < KS; ++s)
 #pragma unroll
-      for (int o = CH / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
-      if (c == 0) {
-        D_s[rl] = part;
-        lse_s[rl] = q < se.Tq ? a.lse[(size_t)h * a.Nq + se.q0 + q] : 0.f;
-      }
+      for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)of[s][e];
+    Dq += __shfl_xor(Dq, 32, kWave);
+    wave_sync();  // the previous tile's reads are done
+    put_rows<DH>(Qs, lane, qf);
+    put_rows<DH>(dOs, lane, dof);
+    if (g == 0) {
+      lse_s[lane] = lse_q;
+      D_s[lane] = Dq;
     }
-    __syncthreads();
-    if (k0 >= se.Tk) continue;
-    const int nqt = (min(kQC, se.Tq - qc) + 31) / 32;
-    for (int qt = 0; qt < nqt; ++qt) {
-      if (a.causal && qc + qt * 32 + 31 < k0) continue;  // every query of the tile precedes every key
-      floatx16 s = zero16(), dp = zero16();
+    floatx16 s = zero16(), dp = zero16();
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int off = (qt * 32 + (lane & 31)) * PR + ks * 16 + g * 8;
-        s = MFMA(ld_half8(Qs + off), kf[ks], s);
-        dp = MFMA(ld_half8(dOs + off), vf[ks], dp);
-      }
-      half8_t pf[2], dsf[2];
+    for (int ks = 0; ks < KS; ++ks) {
+      s = MFMA(qf[ks], kf[ks], s);
+      dp = MFMA(dof[ks], vf[ks], dp);
+    }
+    wave_sync();  // tiles and row statistics are in LDS
+    half8_t pf[2], dsf[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int ql = qt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        const int q = qc + ql;
-        const bool hid = khid || q >= se.Tq || (a.causal && key > q);
-        const float p = hid ? 0.f : exp2f(s[r] * sc - lse_s[ql] * kLog2e);
+    for (int rq = 0; rq < 4; ++rq) {
+      const floatx4 l4 = *reinterpret_cast<const floatx4*>(lse_s + 8 * rq + 4 * g);
+      const floatx4 d4 = *reinterpret_cast<const floatx4*>(D_s + 8 * rq + 4 * g);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * rq + e;
+        const int qq = qt * 32 + 8 * rq + 4 * g + e;
+        const bool hid = khid || qq >= se.Tq || (a.causal && key > qq);
+        const float p = hid ? 0.f : exp2f(s[r] * sc - l4[e]);
         pf[r >> 3][r & 7] = (half_t)p;
-        dsf[r >> 3][r & 7] = (half_t)(p * (dp[r] - D_s[ql]) * scale);
+        dsf[r >> 3][r & 7] = (half_t)(p * (dp[r] - d4[e]) * scale);
       }
-#pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const int kb = qt * 32 + 16 * s2 + 4 * g;
-          dVt[t] = MFMA(tr_frag<DH>(dOs, PR, kb, t, lane), pf[s2], dVt[t]);
-          dKt[t] = MFMA(tr_frag<DH>(Qs, PR, kb, t, lane), dsf[s2], dKt[t]);
-        }
     }
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const int kb = 16 * s2 + 4 * g;
+        dVt[t] = MFMA(tr_frag<DH>(dOs, PR, kb, t, lane), pf[s2], dVt[t]);
+        dKt[t] = MFMA(tr_frag<DH>(Qs, PR, kb, t, lane), dsf[s2], dKt[t]);
+      }
   }
   if (!kvalid) return;
 #pragma unroll
@@ -297,34 +324,31 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, dQ
+// backward, dQ: the wavefront owns 32 queries
 // ------------------------------------------------------------------------------------------------
 template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  half_t* Ks = reinterpret_cast<half_t*>(smem_raw);
-  half_t* Vs = Ks + kKC * PR;
-  uint8_t* hidk = reinterpret_cast<uint8_t*>(Vs + kKC * PR);
+  const Item it = work_item(a);
+  if (!it.live) return;
+  const Sent se = sentence(a, it.b);
+  const int q0 = it.tile * 32;
+  if (q0 >= se.Tq) return;
+  const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
+  half_t* Ks = reinterpret_cast<half_t*>(smem_raw) + (threadIdx.x >> 6) * (32 * PR);
 
-  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-  const Sent se = sentence(a, b);
-  if ((int)blockIdx.y * 128 >= se.Tq) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int q0 = blockIdx.y * 128 + wave * 32;
   const int q = q0 + (lane & 31);
   const bool qvalid = q < se.Tq;
-  half8_t qf[KS], dof[KS];
+  half8_t qf[KS], dof[KS], of[KS];
+  load_rows<DH>(a.Q + (size_t)se.q0 * a.ldq + h * DH, a.ldq, q0, se.Tq, lane, qf);
+  load_rows<DH>(a.dO + (size_t)se.q0 * a.lddo + h * DH, a.lddo, q0, se.Tq, lane, dof);
+  load_rows<DH>(a.O + (size_t)se.q0 * a.ldo + h * DH, a.ldo, q0, se.Tq, lane, of);
   float Dq = 0.f;
 #pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    const int col = h * DH + s * 16 + g * 8;
-    qf[s] = qvalid ? ld_half8(a.Q + (size_t)(se.q0 + q) * a.ldq + col) : zero_half8();
-    dof[s] = qvalid ? ld_half8(a.dO + (size_t)(se.q0 + q) * a.lddo + col) : zero_half8();
-    const half8_t ov = qvalid ? ld_half8(a.O + (size_t)(se.q0 + q) * a.ldo + col) : zero_half8();
+  for (int s = 0; s < KS; ++s)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)ov[e];
-  }
+    for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)of[s][e];
   Dq += __shfl_xor(Dq, 32, kWave);
   const float lse_q = qvalid ? a.lse[(size_t)h * a.Nq + se.q0 + q] * kLog2e : 0.f;
   const float scale = rsqrtf((float)DH), sc = scale * kLog2e;
@@ -334,39 +358,34 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
   const half_t* Kb = a.K + (size_t)se.k0 * a.ldk + h * DH;
   const half_t* Vb = a.V + (size_t)se.k0 * a.ldv + h * DH;
 
-  for (int kc = 0; kc < se.Tk; kc += kKC) {
-    __syncthreads();
-    stage_rows<DH>(Kb, a.ldk, kc, se.Tk, kKC, Ks);
-    stage_rows<DH>(Vb, a.ldv, kc, se.Tk, kKC, Vs);
-    for (int k = threadIdx.x; k < kKC; k += kThreads)
-      hidk[k] = (kc + k >= se.Tk) || (a.key_ids && a.key_ids[se.k0 + kc + k] == a.pad_id);
-    __syncthreads();
-    if (q0 >= se.Tq) continue;
-    const int nkt = (min(kKC, se.Tk - kc) + 31) / 32;
-    for (int kt = 0; kt < nkt; ++kt) {
-      if (a.causal && kc + kt * 32 > q0 + 31) break;  // every key of the tile follows every query
-      floatx16 s = zero16(), dp = zero16();
+  int nkt = (se.Tk + 31) >> 5;
+  if (a.causal) nkt = min(nkt, (q0 + 31) / 32 + 1);  // later key tiles follow every query of this tile
+  for (int kt = 0; kt < nkt; ++kt) {
+    half8_t kf[KS], vf[KS];
+    load_rows<DH>(Kb, a.ldk, kt * 32, se.Tk, lane, kf);
+    load_rows<DH>(Vb, a.ldv, kt * 32, se.Tk, lane, vf);
+    const uint32_t hm = hidden_keys(a, se, kt * 32, lane);
+    wave_sync();  // the previous tile's reads are done
+    put_rows<DH>(Ks, lane, kf);
+    floatx16 s = zero16(), dp = zero16();
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int off = (kt * 32 + (lane & 31)) * PR + ks * 16 + g * 8;
-        s = MFMA(ld_half8(Ks + off), qf[ks], s);
-        dp = MFMA(ld_half8(Vs + off), dof[ks], dp);
-      }
-      half8_t dsf[2];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kl = kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        const bool hid = hidk[kl] || (a.causal && kc + kl > q);
-        const float p = hid ? 0.f : exp2f(s[r] * sc - lse_q);
-        dsf[r >> 3][r & 7] = (half_t)(p * (dp[r] - Dq) * scale);
-      }
-#pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          dQt[t] = MFMA(tr_frag<DH>(Ks, PR, kt * 32 + 16 * s2 + 4 * g, t, lane), dsf[s2], dQt[t]);
-        }
+    for (int ks = 0; ks < KS; ++ks) {
+      s = MFMA(kf[ks], qf[ks], s);
+      dp = MFMA(vf[ks], dof[ks], dp);
     }
+    half8_t dsf[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kl = 8 * (r >> 2) + 4 * g + (r & 3);
+      const bool hid = ((hm >> kl) & 1u) || (a.causal && kt * 32 + kl > q);
+      const float p = hid ? 0.f : exp2f(s[r] * sc - lse_q);
+      dsf[r >> 3][r & 7] = (half_t)(p * (dp[r] - Dq) * scale);
+    }
+    wave_sync();  // the K tile is in LDS
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) dQt[t] = MFMA(tr_frag<DH>(Ks, PR, 16 * s2 + 4 * g, t, lane), dsf[s2], dQt[t]);
   }
   if (!qvalid) return;
 #pragma unroll
@@ -384,18 +403,9 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
 }
 
 template <int DH>
-size_t fwd_smem(int Tk) {
-  const int KP = (Tk + 31) & ~31;
-  return (size_t)(2 * KP * (DH + 8)) * sizeof(half_t) + KP;
-}
+constexpr size_t tile_smem() { return (size_t)4 * 32 * (DH + 8) * sizeof(half_t); }   // one 32-row tile per wavefront
 template <int DH>
-size_t dkv_smem() {
-  return (size_t)(2 * kQC * (DH + 8)) * sizeof(half_t) + 2 * kQC * sizeof(float);
-}
-template <int DH>
-size_t dq_smem() {
-  return (size_t)(2 * kKC * (DH + 8)) * sizeof(half_t) + kKC;
-}
+constexpr size_t dkv_smem() { return (size_t)4 * (2 * 32 * (DH + 8) * sizeof(half_t) + 2 * 32 * sizeof(float)); }
 
 template <typename Kern>
 int allow_big_lds(Kern kern, size_t bytes) {
@@ -406,20 +416,18 @@ int allow_big_lds(Kern kern, size_t bytes) {
 
 template <int DH>
 int fwd_launch(const AttnArgs& a, hipStream_t stream) {
-  const size_t smem = fwd_smem<DH>(a.Tk);
-  NMT_REQUIRE(smem <= 160 * 1024, "attention: Tk=%d needs %zu bytes of LDS", a.Tk, smem);
-  if (int rc = allow_big_lds(attn_fwd_kernel<DH>, smem)) return rc;
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3(a.B * a.H, ceil_div(a.Tq, 128)), dim3(kThreads), smem, stream, a);
+  const dim3 grid(a.B * ((a.H + 3) / 4), ceil_div(a.Tq, 32));
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, grid, dim3(kThreads), tile_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 template <int DH>
 int bwd_launch(const AttnArgs& a, hipStream_t stream) {
   if (int rc = allow_big_lds(attn_bwd_dkv_kernel<DH>, dkv_smem<DH>())) return rc;
-  if (int rc = allow_big_lds(attn_bwd_dq_kernel<DH>, dq_smem<DH>())) return rc;
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DH>, dim3(a.B * a.H, ceil_div(a.Tk, 128)), dim3(kThreads), dkv_smem<DH>(), stream, a);
+  const int groups = a.B * ((a.H + 3) / 4);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3(groups, ceil_div(a.Tq, 32)), dim3(kThreads), tile_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3(a.B * a.H, ceil_div(a.Tq, 128)), dim3(kThreads), dq_smem<DH>(), stream, a);
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DH>, dim3(groups, ceil_div(a.Tk, 32)), dim3(kThreads), dkv_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -427,7 +435,7 @@ int bwd_launch(const AttnArgs& a, hipStream_t stream) {
 int check_common(const AttnArgs& a, int dh) {
   NMT_REQUIRE(a.B > 0 && a.H > 0 && a.Tq > 0 && a.Tk > 0, "attention: empty problem");
   NMT_REQUIRE(dh == 16 || dh == 32 || dh == 64 || dh == 128, "attention: head size %d not in {16,32,64,128}", dh);
-  NMT_REQUIRE(a.Tk <= 1024 && a.Tq <= 65535 && (int64_t)a.B * a.H < (1ll << 31), "attention: Tk=%d / B*H out of range", a.Tk);
+  NMT_REQUIRE(a.Tk <= (1 << 20) && a.Tq <= (1 << 20) && (int64_t)a.B * a.H < (1ll << 31), "attention: Tq=%d / Tk=%d / B*H out of range", a.Tq, a.Tk);
   NMT_REQUIRE(a.tab ? a.Nq > 0 : a.Nq == a.B * a.Tq, "attention: inconsistent number of query rows");
   NMT_REQUIRE(a.ldq % 8 == 0 && a.ldk % 8 == 0 && a.ldv % 8 == 0 && a.ldo % 8 == 0, "attention: row strides must be multiples of 8");
   NMT_REQUIRE(a.ldq >= a.H * dh && a.ldk >= a.H * dh && a.ldv >= a.H * dh && a.ldo >= a.H * dh, "attention: row stride smaller than H*dh");

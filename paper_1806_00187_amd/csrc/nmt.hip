@@ -2,6 +2,7 @@
 // (forward + loss, backward, accumulate, overflow check, Adam) behind the C ABI.
 #include <math.h>
 #include <stdarg.h>
+#include <stdlib.h>
 
 #include <string>
 #include <vector>
@@ -212,7 +213,7 @@ int64_t plan_workspace(const nmt_ctx* c, const GroupDims& gd, Plan& p) {
   p.lnpart = take(layernorm_bwd_scratch_floats((int)d) * f4);
   const int64_t widest = F > 3 * d ? F : 3 * d;
   p.cspart = take(colsum_scratch_floats((int)widest) * f4);
-  p.embscratch = take(embed_bwd_scratch_ints((int)V, (int)(Ns + Nt)) * (int64_t)sizeof(int32_t));
+  p.embscratch = take(embed_bwd_scratch_ints((int)V, (int)(Ns + Nt), (int)d) * (int64_t)sizeof(int32_t));
   // fp32 partial sums of weight-gradient products cut along the (long) position axis
   p.wgpart_floats = Nm >= 4096 ? kWgradPartialFloats : 0;
   p.wgpart = take(p.wgpart_floats * f4);
@@ -526,6 +527,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
   const Plan& p = c->plan;
   hipStream_t st = static_cast<hipStream_t>(stream), sd = c->side;
+  if (getenv("NMT_ONE_STREAM")) sd = st;  // profiling aid: no overlap, so per-kernel times are those of kernels running alone
   const Run r{c, st};   // input-gradient chain
   const Run w{c, sd};   // weight gradients
   const bool dropping = c->training && k.dropout > 0.f;
@@ -797,8 +799,8 @@ extern "C" int nmt_op_colsum(const void* d_src, int32_t ld, void* d_dst, float* 
                        static_cast<hipStream_t>(stream));
 }
 
-extern "C" int64_t nmt_op_embed_bwd_scratch(int32_t vocab, int32_t rows_total) {
-  return (vocab > 0 && rows_total > 0) ? embed_bwd_scratch_ints(vocab, rows_total) : NMT_EINVAL;
+extern "C" int64_t nmt_op_embed_bwd_scratch(int32_t vocab, int32_t rows_total, int32_t d) {
+  return (vocab > 0 && rows_total > 0 && d > 0) ? embed_bwd_scratch_ints(vocab, rows_total, d) : NMT_EINVAL;
 }
 extern "C" int nmt_op_embed_bwd(const int32_t* d_ids_a, const void* d_dx_a, int32_t rows_a, const nmt_dropout* drop_a,
                                 const int32_t* d_ids_b, const void* d_dx_b, int32_t rows_b, const nmt_dropout* drop_b, void* d_gE,

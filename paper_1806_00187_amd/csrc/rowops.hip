@@ -414,11 +414,17 @@ __global__ void __launch_bounds__(1024) loss_reduce_kernel(const float* __restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// Embedding backward.  A counting sort of the token positions by id (histogram, scan, stable rank)
-// yields, per vocabulary row, the list of positions that used it; one block per distinct id then
-// sums those gradient rows in a fixed order and adds them to the row already holding the output
-// projection's weight gradient.
+// Embedding backward.  The token positions of both id streams are sorted by id with a stable two-pass
+// radix sort (8 bits per pass), so every vocabulary row's positions are contiguous and in increasing
+// order.  The sorted list is cut into segments of kEmbSeg entries; one block per segment sums the
+// gradient rows of each run of equal ids.  A run that holds all positions of its id is added to the
+// row of the shared matrix at once; runs of ids that spill over segment borders leave fp32 partial
+// sums, which a second kernel adds up in segment order.  The order of every sum is fixed, so results
+// do not depend on scheduling.
 // ------------------------------------------------------------------------------------------------
+constexpr int kEmbSeg = 64;        // sorted entries per block of the row-summing kernel
+constexpr int kSortPerBlock = 1024;  // entries per block of a radix pass
+
 __global__ void fill_int_kernel(int32_t* p, int n, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -432,10 +438,11 @@ __global__ void __launch_bounds__(kThreads) emb_hist_kernel(const int32_t* a, in
   if (i < na + nb) atomicAdd(&cnt[id_at(a, na, b, i, vocab)], 1);
 }
 // exclusive scan of cnt[0..V) into start[0..V]; single block of 1024 threads
-__global__ void __launch_bounds__(1024) emb_scan_kernel(const int32_t* __restrict__ cnt, int32_t* __restrict__ start, int V) {
+// (start may be cnt itself)
+__global__ void __launch_bounds__(1024) emb_scan_kernel(const int32_t* cnt, int32_t* start, int V) {
   __shared__ int sh[1024];
   const int per = (V + 1023) / 1024;
-  const int lo = threadIdx.x * per, hi = min(V, lo + per);
+  const int lo = min(V, (int)threadIdx.x * per), hi = min(V, lo + per);
   int s = 0;
   for (int i = lo; i < hi; ++i) s += cnt[i];
   sh[threadIdx.x] = s;
@@ -448,87 +455,153 @@ __global__ void __launch_bounds__(1024) emb_scan_kernel(const int32_t* __restric
   }
   int run = sh[threadIdx.x] - s;
   for (int i = lo; i < hi; ++i) {
+    const int c = cnt[i];
     start[i] = run;
-    run += cnt[i];
+    run += c;
   }
   if (threadIdx.x == 1023) start[V] = sh[1023];
 }
-// rank[i] = number of earlier positions with the same id; perm[start[id] + rank] = i
-__global__ void __launch_bounds__(kThreads) emb_rank_kernel(const int32_t* a, int na, const int32_t* b, int nb, int vocab,
-                                                            const int32_t* __restrict__ start, int32_t* __restrict__ rank,
-                                                            int32_t* __restrict__ perm) {
-  __shared__ int tile[kThreads];
-  const int n = na + nb;
-  const int i = blockIdx.x * kThreads + threadIdx.x;
-  const int my = i < n ? id_at(a, na, b, i, vocab) : -1;
-  int r = 0;
-  const int last_tile = blockIdx.x;  // positions >= (blockIdx.x+1)*kThreads are never earlier than i
-  for (int t = 0; t <= last_tile; ++t) {
-    const int j = t * kThreads + threadIdx.x;
-    __syncthreads();
-    tile[threadIdx.x] = j < n ? id_at(a, na, b, j, vocab) : -2;
-    __syncthreads();
-    const int lim = t == last_tile ? (int)threadIdx.x : kThreads;
-    for (int k = 0; k < lim; ++k) r += tile[k] == my;
+
+// One radix pass over (key, value) pairs; pass 0 takes key = id of position i, value = i.
+// Histogram: hist[digit * nblk + block] = number of the block's entries with that digit, so that an
+// exclusive scan of the whole array gives each (digit, block) its first output slot.
+__global__ void __launch_bounds__(kThreads) radix_hist_kernel(const int32_t* a, int na, const int32_t* b, int vocab,
+                                                              const int32_t* __restrict__ keys, int n, int shift, int nblk,
+                                                              int32_t* __restrict__ hist) {
+  __shared__ int h[256];
+  h[threadIdx.x] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kSortPerBlock;
+  for (int r = 0; r < kSortPerBlock / kThreads; ++r) {
+    const int i = base + r * kThreads + threadIdx.x;
+    if (i < n) atomicAdd(&h[((keys ? keys[i] : id_at(a, na, b, i, vocab)) >> shift) & 255], 1);
   }
-  if (i < n) {
-    rank[i] = r;
-    perm[start[my] + r] = i;
+  __syncthreads();
+  hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+// Stable scatter: entries keep their order within a digit.  The block's four wavefronts take turns;
+// within a wavefront the lanes holding the same digit are found with eight ballots.
+__global__ void __launch_bounds__(kThreads) radix_scatter_kernel(const int32_t* a, int na, const int32_t* b, int vocab,
+                                                                 const int32_t* __restrict__ keys, const int32_t* __restrict__ vals,
+                                                                 int n, int shift, int nblk, const int32_t* __restrict__ offs,
+                                                                 int32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out) {
+  __shared__ int next[256];
+  next[threadIdx.x] = offs[threadIdx.x * nblk + blockIdx.x];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int base = blockIdx.x * kSortPerBlock;
+  for (int r = 0; r < kSortPerBlock / kThreads; ++r) {
+    const int i = base + r * kThreads + threadIdx.x;
+    const bool valid = i < n;
+    const int key = valid ? (keys ? keys[i] : id_at(a, na, b, i, vocab)) : 0;
+    const int val = valid ? (vals ? vals[i] : i) : 0;
+    const int digit = (key >> shift) & 255;
+    for (int w = 0; w < kThreads / kWave; ++w) {
+      if (wave == w) {
+        unsigned long long peers = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+          const unsigned long long set = __ballot((digit >> bit) & 1);
+          peers &= ((digit >> bit) & 1) ? set : ~set;
+        }
+        if (valid) {
+          const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+          const int slot = next[digit] + rank;
+          keys_out[slot] = key;
+          vals_out[slot] = val;
+          if (rank == 0) next[digit] += __popcll(peers);   // every peer has read next[digit] (lock-step) before this write
+        }
+      }
+      __syncthreads();
+    }
   }
 }
 
-constexpr int kEmbThreads = 512;
-__global__ void __launch_bounds__(kEmbThreads) emb_reduce_kernel(const int32_t* a, const half_t* __restrict__ dxa, int na, DropDev da,
-                                                                 const int32_t* b, const half_t* __restrict__ dxb, int nb, DropDev db,
-                                                                 half_t* __restrict__ gE, int d, int vocab,
-                                                                 const int32_t* __restrict__ start, const int32_t* __restrict__ rank,
-                                                                 const int32_t* __restrict__ perm) {
-  extern __shared__ float part[];  // [groups][d]
-  const int i = blockIdx.x;
-  if (rank[i] != 0) return;  // only the first occurrence of an id reduces its row (block-uniform)
-  const int v = id_at(a, na, b, i, vocab);
-  const int s0 = start[v], n = start[v + 1] - s0;
-  const int chunks = d >> 3;
-  const int groups = kEmbThreads / chunks;
-  const int g = threadIdx.x / chunks, c = threadIdx.x % chunks;
-  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (g < groups) {
-    for (int k = g; k < n; k += groups) {
-      const int pos = perm[s0 + k];
-      const bool in_a = pos < na;
-      const int row = in_a ? pos : pos - na;
-      const half_t* src = (in_a ? dxa : dxb) + (size_t)row * d + c * 8;
-      const DropDev& dd = in_a ? da : db;
-      float x[8];
-      unpack8(ld_half8(src), x);
-      uint32_t bits = 0xFFu;
-      float sc = 1.f;
-      if (dd.thr) {
-        bits = drop_keep8(dd, (uint32_t)row, (uint32_t)c);
-        sc = dd.scale;
-      }
+// dropout-masked, unscaled gradient chunk (8 columns) of sorted entry `pos`
+__device__ __forceinline__ void emb_row_chunk(int pos, int c, int d, const half_t* __restrict__ dxa, int na, const DropDev& da,
+                                              const half_t* __restrict__ dxb, const DropDev& db, float (&acc)[8]) {
+  const bool in_a = pos < na;
+  const int row = in_a ? pos : pos - na;
+  const DropDev& dd = in_a ? da : db;
+  float x[8];
+  unpack8(ld_half8((in_a ? dxa : dxb) + (size_t)row * d + c * 8), x);
+  uint32_t bits = 0xFFu;
+  float sc = 1.f;
+  if (dd.thr) {
+    bits = drop_keep8(dd, (uint32_t)row, (uint32_t)c);
+    sc = dd.scale;
+  }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] += ((bits >> e) & 1u) ? x[e] * sc : 0.f;
-    }
+  for (int e = 0; e < 8; ++e) acc[e] += ((bits >> e) & 1u) ? x[e] * sc : 0.f;
+}
+__device__ __forceinline__ void emb_add_to_row(half_t* __restrict__ gE, int v, int c, int d, const float (&tot)[8]) {
+  half_t* dst = gE + (size_t)v * d + c * 8;
+  float cur[8];
+  unpack8(ld_half8(dst), cur);
+  const float sq = sqrtf((float)d);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) part[g * d + c * 8 + e] = acc[e];
+  for (int e = 0; e < 8; ++e) cur[e] += sq * tot[e];
+  st_half8(dst, pack8(cur));
+}
+
+// One block per segment of kEmbSeg sorted entries, one thread per 8 columns.
+// part[(2 * seg + 0) * d ..]: sum of the segment's first run if that run began in an earlier segment;
+// part[(2 * seg + 1) * d ..]: sum of its last run if that run began here and goes on in the next one.
+__global__ void __launch_bounds__(kThreads) emb_segment_kernel(const int32_t* a, const half_t* __restrict__ dxa, int na, DropDev da,
+                                                               const int32_t* b, const half_t* __restrict__ dxb, int nb, DropDev db,
+                                                               half_t* __restrict__ gE, int d, int vocab,
+                                                               const int32_t* __restrict__ start, const int32_t* __restrict__ perm,
+                                                               float* __restrict__ part) {
+  __shared__ int s_pos[kEmbSeg], s_id[kEmbSeg];
+  const int n = na + nb, e0 = blockIdx.x * kEmbSeg, cnt = min(kEmbSeg, n - e0);
+  if ((int)threadIdx.x < cnt) {
+    const int pos = perm[e0 + threadIdx.x];
+    s_pos[threadIdx.x] = pos;
+    s_id[threadIdx.x] = id_at(a, na, b, pos, vocab);
   }
   __syncthreads();
-  if (g == 0) {
-    float tot[8], cur[8];
+  const int c = threadIdx.x;
+  if (c >= (d >> 3)) return;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  int run_begin = 0;
+  for (int k = 0; k < cnt; ++k) {
+    emb_row_chunk(s_pos[k], c, d, dxa, na, da, dxb, db, acc);
+    const int v = s_id[k];
+    if (k + 1 < cnt && s_id[k + 1] == v) continue;
+    const int g_begin = start[v], g_end = start[v + 1];  // where id v's positions lie in the sorted list
+    if (g_begin == e0 + run_begin && g_end == e0 + k + 1) {
+      emb_add_to_row(gE, v, c, d, acc);
+    } else {
+      float* dst = part + ((size_t)2 * blockIdx.x + (g_begin < e0 ? 0 : 1)) * d + c * 8;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) tot[e] = acc[e];
-    for (int gg = 1; gg < groups; ++gg) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) tot[e] += part[gg * d + c * 8 + e];
+      for (int e = 0; e < 8; ++e) dst[e] = acc[e];
     }
-    half_t* dst = gE + (size_t)v * d + c * 8;
-    unpack8(ld_half8(dst), cur);
-    const float sq = sqrtf((float)d);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) cur[e] += sq * tot[e];
-    st_half8(dst, pack8(cur));
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    run_begin = k + 1;
   }
+}
+// Block s finishes the id whose run began in an earlier segment and ends in segment s.
+__global__ void __launch_bounds__(kThreads) emb_finish_kernel(const int32_t* a, int na, const int32_t* b, int nb, half_t* __restrict__ gE,
+                                                              int d, int vocab, const int32_t* __restrict__ start,
+                                                              const int32_t* __restrict__ perm, const float* __restrict__ part) {
+  const int e0 = blockIdx.x * kEmbSeg;
+  const int v = id_at(a, na, b, perm[e0], vocab);
+  const int g_begin = start[v], g_end = start[v + 1];
+  if (g_begin >= e0 || g_end > e0 + kEmbSeg) return;  // no run carried in, or it goes on: a later block finishes it
+  const int c = threadIdx.x;
+  if (c >= (d >> 3)) return;
+  const int first = g_begin / kEmbSeg;
+  float tot[8];
+  const float* p = part + ((size_t)2 * first + 1) * d + c * 8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) tot[e] = p[e];
+  for (int sg = first + 1; sg <= (int)blockIdx.x; ++sg) {
+    p = part + (size_t)2 * sg * d + c * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tot[e] += p[e];
+  }
+  emb_add_to_row(gE, v, c, d, tot);
 }
 
 __global__ void __launch_bounds__(kThreads) dropout_mask_kernel(uint8_t* keep, int rows, int n_cols, DropDev drop) {
@@ -668,34 +741,77 @@ int launch_softmax_xent(half_t* logits, const int32_t* targets, float* row_loss,
   return NMT_OK;
 }
 
-int64_t embed_bwd_scratch_ints(int vocab, int rows_total) { return (int64_t)2 * vocab + 8 + 2 * (int64_t)rows_total; }
+namespace {
+struct EmbScratch {
+  int64_t cnt, start, k1, v1, k2, perm, hist, part, total;  // offsets in int32 units
+  int nblk, nseg;
+};
+EmbScratch emb_scratch(int vocab, int n, int d) {
+  EmbScratch e;
+  e.nblk = ceil_div(n, kSortPerBlock);
+  e.nseg = ceil_div(n, kEmbSeg);
+  int64_t cur = 0;
+  auto take = [&](int64_t ints) {
+    const int64_t off = cur;
+    cur += round_up(ints, 4);
+    return off;
+  };
+  e.cnt = take(vocab);
+  e.start = take(vocab + 1);
+  e.k1 = take(n);
+  e.v1 = take(n);
+  e.k2 = take(n);
+  e.perm = take(n);
+  e.hist = take((int64_t)256 * e.nblk + 1);
+  e.part = take((int64_t)2 * e.nseg * d);
+  e.total = cur;
+  return e;
+}
+}  // namespace
+
+int64_t embed_bwd_scratch_ints(int vocab, int rows_total, int d) { return emb_scratch(vocab, rows_total, d).total; }
 
 int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const DropDev& drop_a, const int32_t* ids_b,
                      const half_t* dx_b, int rows_b, const DropDev& drop_b, half_t* gE, int d, int vocab, int32_t* scratch,
                      hipStream_t stream) {
   NMT_REQUIRE(rows_a >= 0 && rows_b >= 0 && rows_a + rows_b > 0, "embed_bwd: no rows");
-  NMT_REQUIRE(d >= 8 && d % 8 == 0 && d / 8 <= kEmbThreads && vocab > 0, "embed_bwd: bad d=%d", d);
+  NMT_REQUIRE(d >= 8 && d % 8 == 0 && d / 8 <= kThreads && vocab > 0 && vocab <= 65536, "embed_bwd: bad d=%d or vocab=%d", d, vocab);
   NMT_REQUIRE((rows_a == 0 || (ids_a && dx_a && aligned16(dx_a))) && (rows_b == 0 || (ids_b && dx_b && aligned16(dx_b))) && gE &&
-                  aligned16(gE) && scratch,
+                  aligned16(gE) && scratch && aligned16(scratch),
               "embed_bwd: null or misaligned pointer");
   NMT_REQUIRE((!drop_a.thr || drop_a.n_pos > 0) && (!drop_b.thr || drop_b.n_pos > 0), "embed_bwd: positions per sentence must be positive");
   const int n = rows_a + rows_b;
-  int32_t* cnt = scratch;
-  int32_t* start = cnt + vocab;
-  int32_t* rank = start + vocab + 8;
-  int32_t* perm = rank + n;
+  const EmbScratch e = emb_scratch(vocab, n, d);
+  int32_t *cnt = scratch + e.cnt, *start = scratch + e.start, *k1 = scratch + e.k1, *v1 = scratch + e.v1, *k2 = scratch + e.k2;
+  int32_t *perm = scratch + e.perm, *hist = scratch + e.hist;
+  float* part = reinterpret_cast<float*>(scratch + e.part);
   hipLaunchKernelGGL(fill_int_kernel, dim3(ceil_div(vocab, kThreads)), dim3(kThreads), 0, stream, cnt, vocab, 0);
   NMT_LAUNCH_CHECK();
   hipLaunchKernelGGL(emb_hist_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, vocab, cnt);
   NMT_LAUNCH_CHECK();
   hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, stream, cnt, start, vocab);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(emb_rank_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, vocab, start,
-                     rank, perm);
+  // stable sort of the positions by id: low byte, then high byte
+  const int nh = 256 * e.nblk;
+  hipLaunchKernelGGL(radix_hist_kernel, dim3(e.nblk), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, vocab, (const int32_t*)nullptr, n, 0,
+                     e.nblk, hist);
   NMT_LAUNCH_CHECK();
-  const int groups = kEmbThreads / (d / 8);
-  hipLaunchKernelGGL(emb_reduce_kernel, dim3(n), dim3(kEmbThreads), (size_t)groups * d * sizeof(float), stream, ids_a, dx_a, rows_a,
-                     drop_a, ids_b, dx_b, rows_b, drop_b, gE, d, vocab, start, rank, perm);
+  hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, hist, nh);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(radix_scatter_kernel, dim3(e.nblk), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, vocab, (const int32_t*)nullptr,
+                     (const int32_t*)nullptr, n, 0, e.nblk, hist, k1, v1);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(radix_hist_kernel, dim3(e.nblk), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, vocab, k1, n, 8, e.nblk, hist);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, hist, nh);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(radix_scatter_kernel, dim3(e.nblk), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, vocab, k1, v1, n, 8, e.nblk, hist,
+                     k2, perm);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(emb_segment_kernel, dim3(e.nseg), dim3(kThreads), 0, stream, ids_a, dx_a, rows_a, drop_a, ids_b, dx_b, rows_b, drop_b, gE,
+                     d, vocab, start, perm, part);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(emb_finish_kernel, dim3(e.nseg), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, gE, d, vocab, start, perm, part);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

@@ -212,15 +212,21 @@ def test_embedding_forward_matches_oracle(B, n_pos, d, V, p):
     assert_close16(host(x), want, "embedding forward")
 
 
-@pytest.mark.parametrize("d,V,p", [(64, 1000, 0.1), (1024, 4096, 0.3)])
-def test_embedding_backward_matches_oracle_and_is_deterministic(d, V, p):
+@pytest.mark.parametrize("d,V,p,Ba,Sa,Bb,Sb", [(64, 1000, 0.1, 6, 11, 6, 9), (1024, 4096, 0.3, 6, 11, 6, 9), (128, 40000, 0.1, 40, 33, 37, 29),
+                                               (64, 65536, 0.0, 3, 400, 5, 300)])
+def test_embedding_backward_matches_oracle_and_is_deterministic(d, V, p, Ba, Sa, Bb, Sb):
+    """The larger cases have ids whose positions fill several 64-entry blocks of the sorted list (sums
+    carried over block borders), ids above 255 * 256 and more than one 1024-entry block per sort pass."""
     rng = np.random.default_rng(d)
-    Ba, Sa, Bb, Sb = 6, 11, 6, 9
     ids_a = rng.integers(4, V, size=(Ba, Sa))
     ids_b = rng.integers(4, V, size=(Bb, Sb))
     ids_a[:, :4] = 7            # a heavily repeated id, shared by both streams
     ids_b[:3, :] = 7
     ids_b[3:, -2:] = 1
+    if Ba * Sa > 1000:
+        ids_a[:, 5:12] = V - 1  # > 64 and > 192 occurrences: first, middle and last blocks of a carried sum
+        ids_b[:, 3:6] = V - 3
+        ids_a[1::2, 20:] = 300
     dxa, dxb = f16(rng.normal(size=(Ba * Sa, d))), f16(rng.normal(size=(Bb * Sb, d)))
     g0 = f16(rng.normal(size=(V, d)))
     da, db_ = _drop(p, 0, 5, 1, 77, Sa), _drop(p, 1, 5, 1, 77, Sb)
@@ -230,7 +236,7 @@ def test_embedding_backward_matches_oracle_and_is_deterministic(d, V, p):
     sc = math.sqrt(d) / (1 - float(np.float32(p)))
     np.add.at(want, ids_a.reshape(-1), dxa * ka * sc)
     np.add.at(want, ids_b.reshape(-1), dxb * kb * sc)
-    scratch = torch.zeros(A.nmt_op_embed_bwd_scratch(V, Ba * Sa + Bb * Sb), dtype=torch.int32, device=DEV)
+    scratch = torch.zeros(A.nmt_op_embed_bwd_scratch(V, Ba * Sa + Bb * Sb, d), dtype=torch.int32, device=DEV)
     outs = []
     for _ in range(2):
         gE = dev16(g0)
