@@ -73,8 +73,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="big_accum", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pipes", type=int, default=3, help="sub-batches kept in flight on separate streams")
-    ap.add_argument("--group", type=int, default=1, help="sub-batches stacked into one forward/backward pass")
+    ap.add_argument("--pipes", type=int, default=1, help="forward/backward passes kept in flight on separate streams")
+    ap.add_argument("--group", type=int, default=16, help="sub-batches stacked into one forward/backward pass")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -34,7 +34,7 @@
 
 namespace {
 
-constexpr int kThreads = 256;  // 4 wavefronts, arranged 2 x 2 over the block tile
+constexpr int kThreads = 256;  // threads of the split-k reduction kernel
 constexpr uint32_t kOob = 0x80000000u;  // byte offset no operand reaches: such loads return 0
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
@@ -70,14 +70,14 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned char
 // Either way a wavefront's ds_read_b128 of 32 rows x 2 chunks touches every bank equally often.
 // All offsets are relative to the first element of the block's current k-tile, so operands of any
 // size work with 32-bit offsets.
-template <int R, int BK>
+template <int R, int BK, int NW>
 struct DirectOp {
   static constexpr int ROWB = BK * 2;             // bytes per tile row
   static constexpr int CPR = BK / 8;              // 16-byte chunks per row
   static constexpr int RPI = 64 / CPR;            // rows per wave instruction (1 KB)
   static constexpr int BYTES = R * ROWB;
-  static constexpr int NV = BYTES / 4096;         // wave instructions per wave and k-tile
-  static_assert(NV >= 1 && BYTES % 4096 == 0, "tile too small for four waves");
+  static constexpr int NV = BYTES / (1024 * NW);  // wave instructions per wave and k-tile
+  static_assert(NV >= 1 && BYTES % (1024 * NW) == 0, "tile too small for the work-group's waves");
   uint32_t voff[NV];
   int c8, wave;
   __device__ __forceinline__ static int swz(int row) { return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3); }
@@ -90,18 +90,18 @@ struct DirectOp {
   __device__ __forceinline__ void init(int ld, int rows_in, int tid) {
     wave = tid >> 6;
     const int L = tid & 63, rowl = L / CPR, p = L % CPR;
-    // RPI * (wave + 4 it) adds nothing to the swizzle bits except, for BK = 64, bit 3 of the row (= wave & 1)
+    // RPI * (wave + NW it) adds nothing to the swizzle bits except, for BK = 64, bit 3 of the row (= wave & 1)
     c8 = (p ^ swz(RPI * wave + rowl)) << 3;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
-      const int row = RPI * (wave + 4 * it) + rowl;
+      const int row = RPI * (wave + NW * it) + rowl;
       voff[it] = row < rows_in ? ((uint32_t)row * (uint32_t)ld + (uint32_t)c8) * 2u : kOob;
     }
   }
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int kleft) const {
     const bool kv = c8 < kleft;  // only the last k-tile can fail this
 #pragma unroll
-    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, kv ? voff[it] : kOob);
+    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + NW * it) * 1024, kv ? voff[it] : kOob);
   }
   // per-lane fragment addresses, one per k-step (the swizzle is an XOR in the k-step bits)
   struct Frag { uint32_t a[BK / 16]; };
@@ -121,14 +121,14 @@ struct DirectOp {
 // ---- transposed operand: memory [K][rows] (rows contiguous), LDS tile [BK k][R] -------------------
 // Within k row k, slot q (16 bytes) holds chunk q ^ (y(k) << 1): the four k rows a 16-lane group of
 // the transposing read touches then lie in four different 32-byte bank segments.
-template <int R, int BK>
+template <int R, int BK, int NW>
 struct TransOp {
   static constexpr int ROWB = R * 2;        // bytes per k row
   static constexpr int BYTES = BK * ROWB;
-  static constexpr int NV = BYTES / 4096;
+  static constexpr int NV = BYTES / (1024 * NW);
   static constexpr int CPR = R / 8;         // 16-byte chunks per k row
   static constexpr int KPI = 64 / CPR;      // k rows per wave instruction
-  static_assert(NV >= 1 && BYTES % 4096 == 0, "tile too small for four waves");
+  static_assert(NV >= 1 && BYTES % (1024 * NW) == 0, "tile too small for the work-group's waves");
   uint32_t voff[NV];
   int wave;
   __device__ __forceinline__ static int ysw(int k2) { return R == 64 ? (k2 & 3) : ((k2 & 1) | ((k2 & 2) << 1)); }
@@ -140,15 +140,15 @@ struct TransOp {
   __device__ __forceinline__ void init(int ld, int rows_in, int tid) {
     wave = tid >> 6;
     const int L = tid & 63, kl = L / CPR, slot = L % CPR;
-    const int cc = slot ^ (ysw((KPI * wave + kl) & 3) << 1);  // k row of instruction `it` is KPI * (wave + 4 it) + kl
+    const int cc = slot ^ (ysw((KPI * wave + kl) & 3) << 1);  // k row of instruction `it` is KPI * (wave + NW it) + kl
     const bool ok = cc * 8 < rows_in;
 #pragma unroll
     for (int it = 0; it < NV; ++it)
-      voff[it] = ok ? ((uint32_t)(KPI * (wave + 4 * it) + kl) * (uint32_t)ld + (uint32_t)(cc * 8)) * 2u : kOob;
+      voff[it] = ok ? ((uint32_t)(KPI * (wave + NW * it) + kl) * (uint32_t)ld + (uint32_t)(cc * 8)) * 2u : kOob;
   }
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char* tile, int /*kleft*/) const {
 #pragma unroll
-    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + 4 * it) * 1024, voff[it]);
+    for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + NW * it) * 1024, voff[it]);
   }
   static constexpr int READS = 2;
   struct Frag { uint32_t a[2]; };
@@ -194,10 +194,10 @@ struct Interleave<MF, MF, NR> {
   __device__ __forceinline__ static void run() {}
 };
 
-template <int BM, int BN, bool AT, bool BT, int BK>
+template <int BM, int BN, bool AT, bool BT, int BK, int NW>
 struct Tile {
-  using OpA = typename std::conditional<AT, TransOp<BM, BK>, DirectOp<BM, BK>>::type;
-  using OpB = typename std::conditional<BT, TransOp<BN, BK>, DirectOp<BN, BK>>::type;
+  using OpA = typename std::conditional<AT, TransOp<BM, BK, NW>, DirectOp<BM, BK, NW>>::type;
+  using OpB = typename std::conditional<BT, TransOp<BN, BK, NW>, DirectOp<BN, BK, NW>>::type;
   static constexpr int STAGE = OpA::BYTES + OpB::BYTES;   // (BM + BN) * BK * 2 bytes
 };
 
@@ -208,9 +208,9 @@ constexpr int wait_vm_lds(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; 
 
 // NS stages of BK k each form a ring: while k-tile t is multiplied, tiles t+1 .. t+NS-1 are in LDS
 // or on their way.
-template <int BM, int BN, bool AT, bool BT, int BK, int NS>
-__global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
-  using T = Tile<BM, BN, AT, BT, BK>;
+template <int BM, int BN, bool AT, bool BT, int BK, int NS, int NW>
+__global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
+  using T = Tile<BM, BN, AT, BT, BK, NW>;
   using OpA = typename T::OpA;
   using OpB = typename T::OpB;
   static_assert(NS == 2 || NS == 4, "two or four stages");
@@ -220,9 +220,10 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
   __shared__ __align__(1024) unsigned char stage1[T::STAGE];
   __shared__ __align__(1024) unsigned char stage2[NS > 2 ? T::STAGE : 16];
   __shared__ __align__(1024) unsigned char stage3[NS > 2 ? T::STAGE : 16];
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KS = BK / 16;
+  constexpr int WGN = NW / 2;  // the waves form a 2 x WGN grid over the block tile
+  constexpr int WM = BM / 2, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // Work-group -> tile.  Consecutive work-group ids go round-robin over the 8 XCDs; undo that so
   // each XCD (own L2) gets a contiguous run of tiles.
@@ -333,8 +334,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g) {
 
   // ---- epilogue: accumulators -> per-wave LDS staging (fp32) -> row-wise 16-byte stores -------
   // staging width per pass: the wave's whole width if 4 waves x 32 rows of it fit one stage, else 32
-  constexpr int SW = (4 * 32 * WN * 4 <= T::STAGE) ? WN : (4 * 32 * 64 * 4 <= T::STAGE && WN % 64 == 0) ? 64 : 32;
-  static_assert(4 * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
+  constexpr int SW = (NW * 32 * WN * 4 <= T::STAGE) ? WN : (NW * 32 * 64 * 4 <= T::STAGE && WN % 64 == 0) ? 64 : 32;
+  static_assert(NW * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
   float* stg = reinterpret_cast<float*>(stage1) + wave * (32 * SW);
   constexpr int CH = SW / 8;  // 8-column chunks per staged row
   const GemmEpilogue& ep = g.ep;
@@ -428,14 +429,14 @@ __global__ void __launch_bounds__(kThreads) splitk_reduce_kernel(const float* __
   st_half8(C + (size_t)row * ldc + c8 * 8, o);
 }
 
-template <int BM, int BN, bool AT, bool BT, int BK, int NS>
+template <int BM, int BN, bool AT, bool BT, int BK, int NS, int NW>
 int launch_variant(const GemmArgs& g, int splits, hipStream_t stream) {
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT, BK, NS>), dim3(g.tiles_m * g.tiles_n, splits), dim3(kThreads), 0, stream, g);
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, AT, BT, BK, NS, NW>), dim3(g.tiles_m * g.tiles_n, splits), dim3(64 * NW), 0, stream, g);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 
-template <int BM, int BN, int BK, int NS>
+template <int BM, int BN, int BK, int NS, int NW = 4>
 int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t stream) {
   GemmArgs g = a;
   g.tiles_m = ceil_div(g.M, BM);
@@ -450,10 +451,10 @@ int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t s
     splits = 1;
   }
   int rc;
-  if (!a_t && !b_t) rc = launch_variant<BM, BN, false, false, BK, NS>(g, splits, stream);
-  else if (!a_t && b_t) rc = launch_variant<BM, BN, false, true, BK, NS>(g, splits, stream);
-  else if (a_t && b_t) rc = launch_variant<BM, BN, true, true, BK, NS>(g, splits, stream);
-  else rc = launch_variant<BM, BN, true, false, BK, NS>(g, splits, stream);
+  if (!a_t && !b_t) rc = launch_variant<BM, BN, false, false, BK, NS, NW>(g, splits, stream);
+  else if (!a_t && b_t) rc = launch_variant<BM, BN, false, true, BK, NS, NW>(g, splits, stream);
+  else if (a_t && b_t) rc = launch_variant<BM, BN, true, true, BK, NS, NW>(g, splits, stream);
+  else rc = launch_variant<BM, BN, true, false, BK, NS, NW>(g, splits, stream);
   if (rc != NMT_OK || splits == 1) return rc;
   const int64_t n = (int64_t)g.M * (g.N / 8);
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, g.partial, splits, g.M, g.N, g.C, g.ldc);
@@ -492,21 +493,23 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   NMT_REQUIRE(!partial || (reinterpret_cast<uintptr_t>(partial) & 15u) == 0, "gemm: partial-sum buffer must be 16-byte aligned");
   GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, ep, partial, 0};
   const int64_t plane = (int64_t)M * N;
+  // Work-groups of 256 x 256 tiles run one per compute unit; they pay off once there are enough of them.
+  const int64_t t256 = (int64_t)ceil_div(M, 256) * ceil_div(N, 256);
   if (splits == 0) {  // choose: a short, wide problem (a weight gradient over many positions) is cut along k
     splits = 1;
-    if (partial && plain) {
-      const int64_t tiles = (int64_t)ceil_div(M, 128) * ceil_div(N, 128);
-      int want = (int)((768 + tiles - 1) / tiles);   // about three work-groups per compute unit
-      want = want < K / 2048 ? want : K / 2048;      // and at least 2048 k per split
+    if (partial && plain && t256 < 192) {
+      int64_t want = (256 + t256 / 2) / t256;                   // one work-group per compute unit
+      want = want < K / 2048 ? want : K / 2048;                 // at least 2048 k per split
+      want = want < partial_floats / plane ? want : partial_floats / plane;
       want = want < 64 ? want : 64;
-      if (want >= 2 && plane * want <= partial_floats) splits = want;
-      else if (want >= 2 && partial_floats / plane >= 2) splits = (int)(partial_floats / plane);
+      if (want >= 2) splits = (int)want;
     }
   }
   NMT_REQUIRE(splits == 1 || plane * splits <= partial_floats, "gemm: partial-sum buffer of %lld floats too small for %d splits",
               (long long)partial_floats, splits);
   if (const char* force = getenv("NMT_GEMM_TILE")) {  // tuning aid: force one tile shape
     if (!strcmp(force, "256x256")) return launch_tile<256, 256, 32, 4>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "256x256w8")) return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
@@ -514,6 +517,7 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
     if (!strcmp(force, "64x128")) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, splits, stream);
   }
+  if (t256 * splits >= 192) return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
   if (splits > 1) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
   const double s128 = tile_score(M, N, 128, 128, 2, 1.0);
   const double s12864 = tile_score(M, N, 128, 64, 2, 0.85);

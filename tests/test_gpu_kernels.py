@@ -33,7 +33,8 @@ def test_dropout_mask_bit_exact(p, n_pos, n_cols, B):
 
 # ---- GEMM -------------------------------------------------------------------------------------
 GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (37, 1000, 64), (515, 264, 200), (3003, 1024, 1024), (256, 3072, 1024),
-               (1, 8, 8), (130, 64, 4096), (136, 264, 3003)]
+               (1, 8, 8), (130, 64, 4096), (136, 264, 3003),
+               (4088, 3080, 200)]   # enough 256 x 256 tiles for the large-tile kernel, ragged on every side
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
@@ -54,7 +55,8 @@ def test_gemm_matches_oracle(M, N, K, mode):
     assert_close16(host(dC), Am @ Bm.T, f"gemm {mode} {M}x{N}x{K}")
 
 
-@pytest.mark.parametrize("M,N,K,splits", [(136, 264, 3003, 3), (256, 128, 8192, 0), (64, 64, 4500, 64), (1024, 512, 6000, 5)])
+@pytest.mark.parametrize("M,N,K,splits", [(136, 264, 3003, 3), (256, 128, 8192, 0), (64, 64, 4500, 64), (1024, 512, 6000, 5),
+                                            (2048, 2040, 1500, 3), (1024, 1024, 16384, 0)])  # the last two: large-tile kernel
 def test_gemm_split_along_k_matches_oracle(M, N, K, splits):
     """Weight-gradient form (both operands stored [K, rows]) with the contraction cut into pieces."""
     rng = np.random.default_rng(M + N + K)
