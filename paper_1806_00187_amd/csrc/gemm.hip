@@ -47,7 +47,7 @@ struct GemmArgs {
   const half_t* B;
   half_t* C;
   int lda, ldb, ldc, M, N, K;
-  int tiles_m, tiles_n, tm_fast;
+  int tiles_m, tiles_n, group_m;
   GemmEpilogue ep;
   // split-K: work-group (tile, z) contracts k in [z * k_chunk, min(K, (z + 1) * k_chunk)) and writes its
   // fp32 tile to partial[z][M][N]; partial == nullptr: one work-group per tile, epilogue, fp16 result
@@ -237,10 +237,9 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   // time form a patch of tiles and each A / B panel they stream is shared by several of them in L2.
   int tm, tn;
   {
-    constexpr int GROUP = 8;
-    const int per_group = GROUP * g.tiles_n;
-    const int first = (pid / per_group) * GROUP;
-    const int rows = min(g.tiles_m - first, GROUP);
+    const int per_group = g.group_m * g.tiles_n;
+    const int first = (pid / per_group) * g.group_m;
+    const int rows = min(g.tiles_m - first, g.group_m);
     tm = first + (pid % per_group) % rows;
     tn = (pid % per_group) / rows;
   }
@@ -441,7 +440,8 @@ int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t s
   GemmArgs g = a;
   g.tiles_m = ceil_div(g.M, BM);
   g.tiles_n = ceil_div(g.N, BN);
-  g.tm_fast = g.M <= g.N;
+  g.group_m = 8;
+  if (const char* e = getenv("NMT_GEMM_GROUP")) g.group_m = atoi(e) > 0 ? atoi(e) : 8;
   if (splits > 1) {
     g.k_chunk = (int)round_up(ceil_div(g.K, splits), BK);
     splits = ceil_div(g.K, g.k_chunk);  // no empty split
@@ -510,6 +510,8 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   if (const char* force = getenv("NMT_GEMM_TILE")) {  // tuning aid: force one tile shape
     if (!strcmp(force, "256x256")) return launch_tile<256, 256, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "256x256w8")) return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "256x256k64")) return launch_tile<256, 256, 64, 2, 8>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "256x128w8")) return launch_tile<256, 128, 64, 2, 8>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
@@ -517,7 +519,12 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
     if (!strcmp(force, "64x128")) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, splits, stream);
   }
-  if (t256 * splits >= 192) return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
+  if (t256 * splits >= 192) {
+    // k-contiguous operands are fetched in whole 128-byte lines by 64-deep stages; transposed ones
+    // gain more from the longer look-ahead of four 32-deep stages
+    if (!a_t && !b_t) return launch_tile<256, 256, 64, 2, 8>(g, a_t, b_t, splits, stream);
+    return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
+  }
   if (splits > 1) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
   const double s128 = tile_score(M, N, 128, 128, 2, 1.0);
   const double s12864 = tile_score(M, N, 128, 64, 2, 0.85);

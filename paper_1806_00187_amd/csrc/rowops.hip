@@ -280,7 +280,7 @@ __global__ void __launch_bounds__(kFinThreads) finalize_partials_kernel(const fl
 // ------------------------------------------------------------------------------------------------
 // Column sums of an fp16 matrix (bias gradients): grid (column blocks of 512, row splits).
 // ------------------------------------------------------------------------------------------------
-constexpr int kColsumMaxSplits = 64;
+constexpr int kColsumMaxSplits = 512;
 
 __global__ void __launch_bounds__(kThreads) colsum_kernel(const half_t* __restrict__ src, int ld, float* __restrict__ partial,
                                                           int rows, int cols) {
@@ -292,7 +292,20 @@ __global__ void __launch_bounds__(kThreads) colsum_kernel(const half_t* __restri
   const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
   float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (col < cols) {
-    for (int r = r0 + wave; r < r1; r += kWavesPerBlock) {
+    int r = r0 + wave;
+    for (; r + 3 * kWavesPerBlock < r1; r += 4 * kWavesPerBlock) {  // four independent loads in flight
+      half8_t h[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) h[u] = ld_half8(src + (size_t)(r + u * kWavesPerBlock) * ld + col);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float v[8];
+        unpack8(h[u], v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += v[e];
+      }
+    }
+    for (; r < r1; r += kWavesPerBlock) {
       float v[8];
       unpack8(ld_half8(src + (size_t)r * ld + col), v);
 #pragma unroll
@@ -711,9 +724,10 @@ int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int ro
   NMT_REQUIRE(rows > 0 && cols > 0 && cols % 8 == 0 && ld % 8 == 0 && ld >= cols, "colsum: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
   NMT_REQUIRE(src && dst && partial && aligned16(src), "colsum: null or misaligned pointer");
   const int cb = ceil_div(cols, 512);
-  int splits = 512 / cb;
-  splits = splits < 1 ? 1 : (splits > kColsumMaxSplits ? kColsumMaxSplits : splits);
-  if (splits > rows) splits = rows;
+  int splits = 2048 / cb;  // enough blocks to keep every compute unit streaming
+  splits = splits > kColsumMaxSplits ? kColsumMaxSplits : splits;
+  splits = splits > rows / 16 ? rows / 16 : splits;
+  splits = splits < 1 ? 1 : splits;
   hipLaunchKernelGGL(colsum_kernel, dim3(cb, splits), dim3(kThreads), 0, stream, src, ld, partial, rows, cols);
   NMT_LAUNCH_CHECK();
   hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, 32)), dim3(kFinThreads), 0, stream, partial, splits, 1, cols,
