@@ -222,6 +222,7 @@ def gemm_leg(model, pass_rows, A, torch, log):
     worst, best = None, None
     per_kind = {}
     cache = {}
+    partial = torch.empty(16 << 20, dtype=torch.float32, device="cuda")   # the step's partial-sum scratch size
     for (M, N, K, a_t, b_t), count in agg.items():
         rows_a, cols_a = (K, M) if a_t else (M, K)
         rows_b, cols_b = (K, N) if b_t else (N, K)
@@ -232,7 +233,10 @@ def gemm_leg(model, pass_rows, A, torch, log):
                     torch.empty(M, N, device="cuda", dtype=torch.float16))
             cache = {(rows_a, cols_a, rows_b, cols_b, M, N): bufs}
         a, b, c = bufs
-        ms = _timed(torch, lambda: A.nmt_op_gemm(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K), 10)
+        if a_t and b_t:   # weight gradient: as in the step, the library may cut the contraction into pieces (fp32 partial sums)
+            ms = _timed(torch, lambda: A.nmt_op_gemm_splitk(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K, partial, 0), 10)
+        else:
+            ms = _timed(torch, lambda: A.nmt_op_gemm(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K), 10)
         fl = 2.0 * M * N * K
         tot_flops += fl * count
         tot_ms += ms * count
