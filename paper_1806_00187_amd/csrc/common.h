@@ -132,6 +132,7 @@ struct GemmEpilogue {
   const half_t* add = nullptr;
   const half_t* relu_src = nullptr;
   float mask_scale = 1.f;
+  int row0 = 0;  // row of the whole activation that row 0 of this product is (dropout counters)
 };
 // partial: optional fp32 scratch of partial_floats floats for cutting the contraction into `splits`
 // pieces summed by a second kernel (splits == 0: the launcher decides; needs an empty epilogue).

@@ -201,6 +201,14 @@ struct Tile {
   static constexpr int STAGE = OpA::BYTES + OpB::BYTES;   // (BM + BN) * BK * 2 bytes
 };
 
+// Orders one wavefront's LDS accesses: what its other lanes wrote before is visible after (LDS
+// instructions of a wavefront execute in order; this keeps the compiler from reordering them).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // s_waitcnt immediates (gfx9 encoding): at most n vector-memory operations outstanding, with or
 // without also waiting for every LDS operation
 constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
@@ -342,7 +350,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int jg = 0; jg < WN / SW; ++jg) {
-      if (i || jg) __syncthreads();
+      if (i || jg) wave_sync();  // the staging area is the wave's own: no work-group barrier needed
 #pragma unroll
       for (int jj = 0; jj < SW / 32; ++jj)
 #pragma unroll
@@ -350,7 +358,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
           const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);  // MFMA 32x32 result layout
           stg[row * SW + jj * 32 + (lane & 31)] = acc[i][jg * (SW / 32) + jj][r];
         }
-      __syncthreads();
+      wave_sync();
 #pragma unroll
       for (int it = 0; it < CH / 2; ++it) {
         const int q = it * 64 + lane;
@@ -381,7 +389,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
             for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
           }
           if (ep.drop.thr) {
-            const uint32_t bits = drop_keep8(ep.drop, (uint32_t)gr, (uint32_t)gc >> 3);
+            const uint32_t bits = drop_keep8(ep.drop, (uint32_t)(gr + ep.row0), (uint32_t)gc >> 3);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = ((bits >> e) & 1u) ? v[e] * ep.drop.scale : 0.f;
           }
@@ -520,6 +528,25 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
     if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, splits, stream);
   }
   if (t256 * splits >= 192) {
+    // A last, partly filled round of 256 x 256 tiles leaves compute units idle for a whole tile's
+    // time.  If that round is small, the rows it would cover are given to a second launch with small
+    // tiles (two work-groups per compute unit), which costs about a third of a round.
+    const int tiles_n = ceil_div(N, 256), rounds = (int)(t256 / 256);
+    if (splits == 1 && rounds >= 1 && t256 % 256 != 0) {
+      const int main_tm = 256 * rounds / tiles_n, m_main = main_tm * 256, m_tail = M - m_main;
+      const int64_t tail128 = (int64_t)ceil_div(m_tail, 128) * ceil_div(N, 128);
+      const double cost_split = ceil_div((int64_t)main_tm * tiles_n, 256) + 0.3 * ceil_div(tail128, 512);
+      if (main_tm >= 1 && cost_split + 0.25 <= rounds + 1) {
+        int rc = launch_gemm(A, a_t, lda, B, b_t, ldb, C, ldc, m_main, N, K, ep, stream, nullptr, 0, 1);
+        if (rc != NMT_OK) return rc;
+        GemmEpilogue tail = ep;
+        tail.row0 = ep.row0 + m_main;
+        if (tail.add) tail.add += (size_t)m_main * ldc;
+        if (tail.relu_src) tail.relu_src += (size_t)m_main * ldc;
+        return launch_gemm(a_t ? A + m_main : A + (size_t)m_main * lda, a_t, lda, B, b_t, ldb, C + (size_t)m_main * ldc, ldc, m_tail, N,
+                           K, tail, stream, nullptr, 0, 1);
+      }
+    }
     // k-contiguous operands are fetched in whole 128-byte lines by 64-deep stages; transposed ones
     // gain more from the longer look-ahead of four 32-deep stages
     if (!a_t && !b_t) return launch_tile<256, 256, 64, 2, 8>(g, a_t, b_t, splits, stream);

@@ -69,6 +69,33 @@ def test_gemm_split_along_k_matches_oracle(M, N, K, splits):
         A.nmt_op_gemm_splitk(dev16(Am.T), 1, M, dev16(Bm.T), 1, N, dC, N + 8, M, N, K, part[: M * N], 2)
 
 
+def test_gemm_large_problem_with_a_small_tile_tail_keeps_epilogue_rows():
+    """Enough rows for one full round of large tiles plus a remainder, which goes to a second launch
+    with small tiles: bias, ReLU and the dropout counters of the remainder must be those of its rows."""
+    rng = np.random.default_rng(17)
+    n_pos, B = 50, 100
+    M, N, K = B * n_pos, 3080, 64
+    x, W, b = f16(rng.normal(size=(M, K))), f16(rng.normal(size=(N, K)) / 8), f16(rng.normal(size=N))
+    add = f16(rng.normal(size=(M, N)))
+    dC = dev16(add)
+    drop = _drop(0.25, 50, 9, 1, 99, n_pos)
+    A.nmt_op_gemm(dev16(x), 0, K, dev16(W), 0, K, dC, N, M, N, K, bias=dev16(b), relu=True, drop=drop, add=dC)
+    keep = O.dropout_keep(99, 50, 9, 1, np.arange(B), n_pos, N, 0.25)
+    want = np.maximum(O.linear_fwd(x, W, b), 0) * keep / (1 - float(np.float32(0.25))) + add
+    assert_close16(host(dC), want, "bias+relu+dropout+add, 5000 rows")
+    # input-gradient and weight-gradient forms of the same size
+    dy = f16(rng.normal(size=(M, 256)))
+    Wt = f16(rng.normal(size=(256, N)) / 16)           # stored [out=256, in=N]: dx = dy W
+    dx = torch.zeros(M, N, dtype=torch.float16, device=DEV)
+    A.nmt_op_gemm(dev16(dy), 0, 256, dev16(Wt), 1, N, dx, N, M, N, 256)
+    assert_close16(host(dx), dy @ Wt, "dgrad, 5000 rows")
+    xt = f16(rng.normal(size=(64, M)))                 # A stored [K, M]
+    yt = f16(rng.normal(size=(64, N)) / 8)
+    out = torch.zeros(M, N, dtype=torch.float16, device=DEV)
+    A.nmt_op_gemm(dev16(xt), 1, M, dev16(yt), 1, N, out, N, M, N, 64)
+    assert_close16(host(out), xt.T @ yt, "both operands transposed, 5000 rows")
+
+
 def test_gemm_epilogues_match_oracle():
     rng = np.random.default_rng(5)
     M, N, K, n_pos = 3 * 50, 256, 64, 50
