@@ -42,6 +42,15 @@ def model_flops(model, B, S, T):
     return 3 * (enc + dec + 2 * Nt * d * V)
 
 
+def model_flops_packed(model, src_lens, tgt_lens):
+    """The same count over the real (non-pad) positions of every sentence."""
+    d, F, V, Le, Ld = model["d_model"], model["d_ff"], model["vocab"], model["enc_layers"], model["dec_layers"]
+    ls, lt = src_lens.astype(float), tgt_lens.astype(float)
+    enc = Le * (ls * (8 * d * d + 4 * d * F) + 4 * ls * ls * d)
+    dec = Ld * (lt * (12 * d * d + 4 * d * F) + ls * 4 * d * d + 2 * lt * lt * d + 4 * lt * ls * d)
+    return float((3 * (enc + dec + 2 * lt * d * V)).sum())
+
+
 def gemm_shapes(model, Ns, Nt):
     """(M, N, K, a_t, b_t, count) of every GEMM launch of one forward + backward pass over Ns source
     and Nt target positions."""
@@ -75,6 +84,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pipes", type=int, default=1, help="forward/backward passes kept in flight on separate streams")
     ap.add_argument("--group", type=int, default=16, help="sub-batches stacked into one forward/backward pass")
+    ap.add_argument("--padded", action="store_true", help="keep the sub-batches' padding rows (default: sentences packed back to back)")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -104,7 +114,14 @@ def main():
     n_pass = -(-k_micro // group)
     sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256, n_pipes=max(1, min(args.pipes, n_pass)))
     dbatches = [sess.to_device(b) for b in batches]
-    if group > 1:
+    packed = not args.padded
+    src_lens = np.concatenate([(b["src"] != I.PAD).sum(1) for b in batches])
+    tgt_lens = np.concatenate([(b["tgt_out"] != I.PAD).sum(1) for b in batches])
+    if packed:
+        dbatches = sess.pack(batches, size=group)      # the same sentences without the padding rows, still resident in HBM
+        for g in dbatches:
+            sess._reserve_bytes(A.nmt_workspace_bytes_packed(sess.ctx, g["packed"].shape[0], g["n_src"], g["n_tgt"]))
+    elif group > 1:
         dbatches = Session.group(dbatches, group)      # ids of a group's sub-batches back to back, still resident in HBM
         for g in dbatches:
             sess.reserve(g["segs"])
@@ -112,6 +129,8 @@ def main():
         for b, s, t in shapes:
             sess.reserve(b, s, t)
     pass_rows = [(sum(b * s for b, s, _ in shapes[i:i + group]), sum(b * t for b, _, t in shapes[i:i + group])) for i in range(0, k_micro, group)]
+    if packed:
+        pass_rows = [(g["n_src"], g["n_tgt"]) for g in dbatches]
     tr = Trainer(sess, peak_lr=1e-3, warmup=4000, init_scale=128.0)
 
     # warm-up: also lets the dynamic loss scale settle (an overflowing update is skipped and halves it)
@@ -141,7 +160,7 @@ def main():
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
     tokens_per_step = sum(ntoks)
     value = tokens_per_step / (ms_per_step * 1e-3)
-    flops_step = sum(model_flops(model, *s) for s in shapes)
+    flops_step = model_flops_packed(model, src_lens, tgt_lens) if packed else sum(model_flops(model, *s) for s in shapes)
     achieved_tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     log(f"[bench] {ms_per_step:.2f} ms/update, {value:,.0f} target tok/s, {achieved_tflops:.1f} TFLOP/s, loss/token {loss / ntok:.3f}")
 
@@ -152,7 +171,9 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "micro_batches_per_update": k_micro,
                    "target_tokens_per_update": tokens_per_step, "padded_shapes_BST": shapes, "loss_scale": tr.scale,
-                   "overflow_updates_in_timed_region": int(sum(flags)), "sub_batches_per_pass": group, "passes_in_flight": sess.n_pipes, "wall_ms_per_step": wall * 1e3 / args.steps},
+                   "overflow_updates_in_timed_region": int(sum(flags)), "sub_batches_per_pass": group, "passes_in_flight": sess.n_pipes,
+                   "rows": "packed (no padding rows)" if packed else "padded", "source_positions_per_update": int(sum(r[0] for r in pass_rows)),
+                   "target_positions_per_update": int(sum(r[1] for r in pass_rows)), "wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": None,
         "whole_update": {"bound": "mfma", "kernel": "every launch of the timed region", "achieved": achieved_tflops,
                          "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_FP16_TFLOPS,

@@ -109,7 +109,27 @@ int nmt_forward_loss_group(nmt_ctx* ctx, int32_t n_seg, const nmt_segment* segs 
                            const uint32_t* d_sent_uid, int32_t training, float* d_loss_sum, int32_t* d_ntok,
                            void* stream);
 
-/* Backward pass in fp16 of the last nmt_forward_loss / nmt_forward_loss_group; writes every element of g16 with the
+/* The same for sentences PACKED back to back, without padding: d_sentences (device, n_sent entries,
+ * read by the kernels of this call) gives every sentence's source and target length, its uid and
+ * the micro index of the sub-batch it belongs to; d_src holds n_src_tokens ids (the source sentences
+ * one after another), d_tgt_in / d_tgt_out n_tgt_tokens ids.  n_src_tokens, n_tgt_tokens (host) must
+ * be the sums of the lengths and max_src_len, max_tgt_len (host) at least the longest ones: the
+ * library sizes its launches from them and clamps what it reads from d_sentences to them, so
+ * inconsistent values give undefined results but no access outside the caller's buffers.  Padding
+ * positions carry no loss and no gradient, so loss, token count and gradients equal those of the
+ * padded sub-batches; only the rows that do nothing are gone. */
+typedef struct {
+  int32_t src_len, tgt_len; /* >= 1 */
+  uint32_t uid;             /* names the sentence's dropout streams */
+  uint32_t micro_idx;       /* < 256 */
+} nmt_sentence;
+int64_t nmt_workspace_bytes_packed(const nmt_ctx* ctx, int32_t n_sent, int64_t n_src_tokens, int64_t n_tgt_tokens);
+int nmt_forward_loss_packed(nmt_ctx* ctx, int32_t n_sent, const nmt_sentence* d_sentences, int64_t n_src_tokens,
+                            int64_t n_tgt_tokens, int32_t max_src_len, int32_t max_tgt_len, const int32_t* d_src,
+                            const int32_t* d_tgt_in, const int32_t* d_tgt_out, float loss_scale, uint32_t step,
+                            int32_t training, float* d_loss_sum, int32_t* d_ntok, void* stream);
+
+/* Backward pass in fp16 of the last nmt_forward_loss / nmt_forward_loss_group / nmt_forward_loss_packed; writes every element of g16 with the
  * gradient of loss_scale * loss_sum ("perform the backward pass as usual"). */
 int nmt_backward(nmt_ctx* ctx, void* stream);
 

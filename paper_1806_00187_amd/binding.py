@@ -51,6 +51,8 @@ _SIGNATURES = {
     "nmt_bind": (C.c_int, [_P, _P, _P, _P, _P, _P, _P, _P, _I64]),
     "nmt_forward_loss": (C.c_int, [_P, _P, _P, _P, _I32, _I32, _I32, _F, _U32, _U32, _P, _I32, _P, _P, _P]),
     "nmt_forward_loss_group": (C.c_int, [_P, _I32, _SP, _P, _P, _P, _F, _U32, _P, _I32, _P, _P, _P]),
+    "nmt_workspace_bytes_packed": (_I64, [_P, _I32, _I64, _I64]),
+    "nmt_forward_loss_packed": (C.c_int, [_P, _I32, _P, _I64, _I64, _I32, _I32, _P, _P, _P, _F, _U32, _I32, _P, _P, _P]),
     "nmt_backward": (C.c_int, [_P, _P]),
     "nmt_accumulate": (C.c_int, [_P, _I32, _P]),
     "nmt_check_overflow": (C.c_int, [_P, _F, _P, _P]),
@@ -192,6 +194,22 @@ def nmt_forward_loss_group(ctx, segs, src, tgt_in, tgt_out, loss_scale, step, lo
     another; sent_uid: one uint32 per sentence in the same order, or None."""
     _check(load().nmt_forward_loss_group(ctx, len(segs), _segments(segs), _p(src), _p(tgt_in), _p(tgt_out), loss_scale, step,
                                          _p(sent_uid), 1 if training else 0, _p(loss_sum), _p(ntok), _stream(stream)))
+
+
+def nmt_workspace_bytes_packed(ctx, n_sent, n_src_tokens, n_tgt_tokens):
+    n = load().nmt_workspace_bytes_packed(ctx, n_sent, n_src_tokens, n_tgt_tokens)
+    if n < 0:
+        _check(int(n))
+    return n
+
+
+def nmt_forward_loss_packed(ctx, sentences, n_src_tokens, n_tgt_tokens, max_src_len, max_tgt_len, src, tgt_in, tgt_out, loss_scale,
+                            step, loss_sum, ntok, training=True, stream=None):
+    """sentences: int32 device tensor [n_sent, 4] = (src_len, tgt_len, uid, micro_idx) per sentence; src / tgt_in / tgt_out: flat
+    int32 device tensors of n_src_tokens / n_tgt_tokens ids, sentences back to back."""
+    _check(load().nmt_forward_loss_packed(ctx, sentences.shape[0], _p(sentences), n_src_tokens, n_tgt_tokens, max_src_len, max_tgt_len,
+                                          _p(src), _p(tgt_in), _p(tgt_out), loss_scale, step, 1 if training else 0, _p(loss_sum),
+                                          _p(ntok), _stream(stream)))
 
 
 def nmt_backward(ctx, stream=None):

@@ -182,4 +182,10 @@ struct SegmentList {
 // encoder-decoder attention.  uid == nullptr: a sentence's id is its index within its sub-batch.
 int launch_build_tables(const SegmentList& segs, int n_sent, const uint32_t* uid, uint2* rk_src, uint2* rk_tgt, int4* tab_ss,
                         int4* tab_tt, int4* tab_ts, hipStream_t stream);
+// The same for sentences packed back to back (no padding): first rows come from a prefix sum of the
+// lengths in `sentences`; lengths are clamped to [1, max] and to the row totals, so no table entry
+// ever points outside [0, n_src) / [0, n_tgt).  sent_rows: scratch of 2 * n_sent ints.
+int launch_build_tables_packed(const nmt_sentence* sentences, int n_sent, int n_src, int n_tgt, int max_src, int max_tgt,
+                               int32_t* sent_rows, uint2* rk_src, uint2* rk_tgt, int4* tab_ss, int4* tab_tt, int4* tab_ts,
+                               hipStream_t stream);
 int launch_dropout_mask(uint8_t* keep, int rows, int n_cols, const DropDev& drop, hipStream_t stream);

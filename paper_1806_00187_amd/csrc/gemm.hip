@@ -221,13 +221,13 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   using T = Tile<BM, BN, AT, BT, BK, NW>;
   using OpA = typename T::OpA;
   using OpB = typename T::OpB;
-  static_assert(NS == 2 || NS == 4, "two or four stages");
+  static_assert(NS >= 2 && NS <= 4, "two to four stages");
   // separate arrays, so that the compiler can tell that fragment reads of one stage do not depend
   // on the loads in flight into the others
   __shared__ __align__(1024) unsigned char stage0[T::STAGE];
   __shared__ __align__(1024) unsigned char stage1[T::STAGE];
   __shared__ __align__(1024) unsigned char stage2[NS > 2 ? T::STAGE : 16];
-  __shared__ __align__(1024) unsigned char stage3[NS > 2 ? T::STAGE : 16];
+  __shared__ __align__(1024) unsigned char stage3[NS > 3 ? T::STAGE : 16];
   constexpr int WGN = NW / 2;  // the waves form a 2 x WGN grid over the block tile
   constexpr int WM = BM / 2, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -316,10 +316,8 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   const int nk = (k_end - k_base + BK - 1) / BK;
   request(stage0, k_base);
   request(stage1, k_base + BK);
-  if constexpr (NS == 4) {
-    request(stage2, k_base + 2 * BK);
-    request(stage3, k_base + 3 * BK);
-  }
+  if constexpr (NS >= 3) request(stage2, k_base + 2 * BK);
+  if constexpr (NS == 4) request(stage3, k_base + 3 * BK);
   __builtin_amdgcn_s_waitcnt(wait_vm((NS - 1) * kPerTile));
   __builtin_amdgcn_s_barrier();
   fetch(stage0, 0, 0);
@@ -327,6 +325,12 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
     for (int kt = 0; kt < nk; kt += 2) {
       k_tile(stage0, stage1, k_base + (kt + 2) * BK);
       k_tile(stage1, stage0, k_base + (kt + 3) * BK);
+    }
+  } else if constexpr (NS == 3) {
+    for (int kt = 0; kt < nk; kt += 3) {
+      k_tile(stage0, stage1, k_base + (kt + 3) * BK);
+      k_tile(stage1, stage2, k_base + (kt + 4) * BK);
+      k_tile(stage2, stage0, k_base + (kt + 5) * BK);
     }
   } else {
     for (int kt = 0; kt < nk; kt += 4) {
@@ -520,6 +524,8 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
     if (!strcmp(force, "256x256w8")) return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "256x256k64")) return launch_tile<256, 256, 64, 2, 8>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "256x128w8")) return launch_tile<256, 128, 64, 2, 8>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "256x128s3")) return launch_tile<256, 128, 32, 3, 4>(g, a_t, b_t, splits, stream);
+    if (!strcmp(force, "128x256s3")) return launch_tile<128, 256, 32, 3, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, splits, stream);
     if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);

@@ -72,6 +72,7 @@ struct EncW { int64_t qkv, o, s1, x1, h, s2, x2, lse, st1, st2; };
 struct DecW { int64_t qkv, o1, s1, x1, lse1, q, kv, o2, s2, x2, lse2, h, s3, x3, st1, st2, st3; };
 struct Plan {
   int64_t rk_src, rk_tgt, tab_ss, tab_tt, tab_ts;  // row keys (dropout, positions) and per-sentence attention tables
+  int64_t sent_rows;                                // first source / target row of every sentence (packed batches)
   int64_t x0, y0, logits, rowloss;
   std::vector<EncW> enc;
   std::vector<DecW> dec;
@@ -162,6 +163,7 @@ int64_t plan_workspace(const nmt_ctx* c, const GroupDims& gd, Plan& p) {
   p.tab_ss = take(B * (int64_t)sizeof(int4));
   p.tab_tt = take(B * (int64_t)sizeof(int4));
   p.tab_ts = take(B * (int64_t)sizeof(int4));
+  p.sent_rows = take(2 * B * (int64_t)sizeof(int32_t));
   p.x0 = take(Ns * d * h2);
   p.y0 = take(Nt * d * h2);
   p.enc.resize(k.enc_layers);
@@ -397,13 +399,81 @@ extern "C" int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_
                                 stream);
 }
 
+namespace {
+// How the row keys and sentence tables of a pass are built: from a short list of rectangular
+// sub-batches (host), or from a device array of sentences packed back to back.
+struct TableSource {
+  int n_seg = 0;
+  const nmt_segment* segs = nullptr;
+  const uint32_t* uid = nullptr;
+  const nmt_sentence* sentences = nullptr;
+};
+int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& src, const int32_t* d_src, const int32_t* d_tgt_in,
+                 const int32_t* d_tgt_out, float loss_scale, uint32_t step, int32_t training, float* d_loss_sum, int32_t* d_ntok,
+                 void* stream);
+}  // namespace
+
 extern "C" int nmt_forward_loss_group(nmt_ctx* ctx, int32_t n_seg, const nmt_segment* segs, const int32_t* d_src,
                                       const int32_t* d_tgt_in, const int32_t* d_tgt_out, float loss_scale, uint32_t step,
                                       const uint32_t* d_sent_uid, int32_t training, float* d_loss_sum, int32_t* d_ntok,
                                       void* stream) {
   GroupDims gd;
   NMT_TRY(check_group(ctx, n_seg, segs, gd));
-  nmt_ctx* c = ctx;
+  TableSource src;
+  src.n_seg = n_seg;
+  src.segs = segs;
+  src.uid = d_sent_uid;
+  return forward_pass(ctx, gd, src, d_src, d_tgt_in, d_tgt_out, loss_scale, step, training, d_loss_sum, d_ntok, stream);
+}
+
+namespace {
+int check_packed(const nmt_ctx* c, int n_sent, const nmt_sentence* d_sent, int64_t n_src, int64_t n_tgt, int max_src, int max_tgt,
+                 GroupDims& gd) {
+  NMT_REQUIRE(c, "null context");
+  NMT_REQUIRE(d_sent && n_sent >= 1 && n_sent <= (1 << 20), "packed batch: %d sentences outside [1, 2^20]", n_sent);
+  NMT_REQUIRE(max_src >= 1 && max_src <= c->cfg.max_len && max_tgt >= 1 && max_tgt <= c->cfg.max_len,
+              "packed batch: longest source / target %d / %d outside [1, max_len=%d]", max_src, max_tgt, c->cfg.max_len);
+  NMT_REQUIRE(n_src >= n_sent && n_src <= (int64_t)n_sent * max_src && n_tgt >= n_sent && n_tgt <= (int64_t)n_sent * max_tgt,
+              "packed batch: token totals inconsistent with the sentence count and the longest lengths");
+  NMT_REQUIRE(n_src <= (1 << 20) && n_tgt <= (1 << 20), "more than 2^20 positions in one pass");
+  gd = GroupDims{};
+  gd.Bt = n_sent;
+  gd.Ns = n_src;
+  gd.Nt = n_tgt;
+  gd.maxS = max_src;
+  gd.maxT = max_tgt;
+  return NMT_OK;
+}
+}  // namespace
+
+extern "C" int64_t nmt_workspace_bytes_packed(const nmt_ctx* ctx, int32_t n_sent, int64_t n_src_tokens, int64_t n_tgt_tokens) {
+  if (!ctx || n_sent < 1 || n_src_tokens < n_sent || n_tgt_tokens < n_sent || n_src_tokens > (1 << 20) || n_tgt_tokens > (1 << 20)) {
+    nmt_set_error("nmt_workspace_bytes_packed: bad sizes");
+    return NMT_EINVAL;
+  }
+  GroupDims gd;
+  gd.Bt = n_sent;
+  gd.Ns = n_src_tokens;
+  gd.Nt = n_tgt_tokens;
+  Plan p;
+  return plan_workspace(ctx, gd, p);
+}
+
+extern "C" int nmt_forward_loss_packed(nmt_ctx* ctx, int32_t n_sent, const nmt_sentence* d_sentences, int64_t n_src_tokens,
+                                       int64_t n_tgt_tokens, int32_t max_src_len, int32_t max_tgt_len, const int32_t* d_src,
+                                       const int32_t* d_tgt_in, const int32_t* d_tgt_out, float loss_scale, uint32_t step,
+                                       int32_t training, float* d_loss_sum, int32_t* d_ntok, void* stream) {
+  GroupDims gd;
+  NMT_TRY(check_packed(ctx, n_sent, d_sentences, n_src_tokens, n_tgt_tokens, max_src_len, max_tgt_len, gd));
+  TableSource src;
+  src.sentences = d_sentences;
+  return forward_pass(ctx, gd, src, d_src, d_tgt_in, d_tgt_out, loss_scale, step, training, d_loss_sum, d_ntok, stream);
+}
+
+namespace {
+int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const int32_t* d_src, const int32_t* d_tgt_in,
+                 const int32_t* d_tgt_out, float loss_scale, uint32_t step, int32_t training, float* d_loss_sum, int32_t* d_ntok,
+                 void* stream) {
   c->have_fwd = false;
   NMT_REQUIRE(d_src && d_tgt_in && d_tgt_out && d_loss_sum && d_ntok, "nmt_forward_loss: null pointer");
   NMT_REQUIRE(c->w16 && c->g16, "nmt_forward_loss: nmt_bind has not been called");
@@ -424,13 +494,16 @@ extern "C" int nmt_forward_loss_group(nmt_ctx* ctx, int32_t n_seg, const nmt_seg
   const Run r{c, static_cast<hipStream_t>(stream)};
   hipStream_t st = r.st;
   const int4 *tab_ss = r.ws<int4>(p.tab_ss), *tab_tt = r.ws<int4>(p.tab_tt), *tab_ts = r.ws<int4>(p.tab_ts);
-  {
+  if (tsrc.sentences) {
+    NMT_TRY(launch_build_tables_packed(tsrc.sentences, Bt, Ns, Nt, maxS, maxT, r.ws<int32_t>(p.sent_rows), r.ws<uint2>(p.rk_src),
+                                       r.ws<uint2>(p.rk_tgt), r.ws<int4>(p.tab_ss), r.ws<int4>(p.tab_tt), r.ws<int4>(p.tab_ts), st));
+  } else {
     SegmentList sl = {};
-    sl.n = n_seg;
-    for (int i = 0; i < n_seg; ++i) {
-      sl.B[i] = segs[i].B; sl.S[i] = segs[i].S; sl.T[i] = segs[i].T; sl.micro[i] = segs[i].micro_idx;
+    sl.n = tsrc.n_seg;
+    for (int i = 0; i < tsrc.n_seg; ++i) {
+      sl.B[i] = tsrc.segs[i].B; sl.S[i] = tsrc.segs[i].S; sl.T[i] = tsrc.segs[i].T; sl.micro[i] = tsrc.segs[i].micro_idx;
     }
-    NMT_TRY(launch_build_tables(sl, Bt, d_sent_uid, r.ws<uint2>(p.rk_src), r.ws<uint2>(p.rk_tgt), r.ws<int4>(p.tab_ss),
+    NMT_TRY(launch_build_tables(sl, Bt, tsrc.uid, r.ws<uint2>(p.rk_src), r.ws<uint2>(p.rk_tgt), r.ws<int4>(p.tab_ss),
                                 r.ws<int4>(p.tab_tt), r.ws<int4>(p.tab_ts), st));
   }
 
@@ -498,6 +571,7 @@ extern "C" int nmt_forward_loss_group(nmt_ctx* ctx, int32_t n_seg, const nmt_seg
   c->have_fwd = true;
   return NMT_OK;
 }
+}  // namespace
 
 // ================================================================================================
 // backward

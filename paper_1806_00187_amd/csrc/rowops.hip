@@ -660,6 +660,55 @@ __global__ void __launch_bounds__(kThreads) build_tables_kernel(const SegmentLis
   for (int t = 0; t < T; ++t) rk_tgt[trow + t] = make_uint2(id, hi | (uint32_t)t);
 }
 
+// Packed sentences: exclusive prefix sums of the clamped lengths (one block of 1024 threads) ...
+__global__ void __launch_bounds__(1024) packed_rows_kernel(const nmt_sentence* __restrict__ sent, int n_sent, int max_src, int max_tgt,
+                                                           int32_t* __restrict__ rows) {
+  __shared__ int sh_s[1024], sh_t[1024];
+  const int per = (n_sent + 1023) / 1024;
+  const int lo = min(n_sent, (int)threadIdx.x * per), hi = min(n_sent, lo + per);
+  int ss = 0, tt = 0;
+  for (int i = lo; i < hi; ++i) {
+    ss += min(max(sent[i].src_len, 1), max_src);
+    tt += min(max(sent[i].tgt_len, 1), max_tgt);
+  }
+  sh_s[threadIdx.x] = ss;
+  sh_t[threadIdx.x] = tt;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int vs = (int)threadIdx.x >= o ? sh_s[threadIdx.x - o] : 0, vt = (int)threadIdx.x >= o ? sh_t[threadIdx.x - o] : 0;
+    __syncthreads();
+    sh_s[threadIdx.x] += vs;
+    sh_t[threadIdx.x] += vt;
+    __syncthreads();
+  }
+  int rs = sh_s[threadIdx.x] - ss, rt = sh_t[threadIdx.x] - tt;
+  for (int i = lo; i < hi; ++i) {
+    rows[2 * i] = rs;
+    rows[2 * i + 1] = rt;
+    rs += min(max(sent[i].src_len, 1), max_src);
+    rt += min(max(sent[i].tgt_len, 1), max_tgt);
+  }
+}
+// ... then one thread per sentence writes its table entries and row keys.
+__global__ void __launch_bounds__(kThreads) packed_tables_kernel(const nmt_sentence* __restrict__ sent, int n_sent, int n_src, int n_tgt,
+                                                                int max_src, int max_tgt, const int32_t* __restrict__ rows,
+                                                                uint2* __restrict__ rk_src, uint2* __restrict__ rk_tgt,
+                                                                int4* __restrict__ tab_ss, int4* __restrict__ tab_tt,
+                                                                int4* __restrict__ tab_ts) {
+  const int sb = blockIdx.x * kThreads + threadIdx.x;
+  if (sb >= n_sent) return;
+  const nmt_sentence se = sent[sb];
+  // rows past the totals the host sized everything for do not exist: a sentence is cut there
+  const int srow = min(rows[2 * sb], n_src - 1), trow = min(rows[2 * sb + 1], n_tgt - 1);
+  const int S = min(min(max(se.src_len, 1), max_src), n_src - srow), T = min(min(max(se.tgt_len, 1), max_tgt), n_tgt - trow);
+  const uint32_t hi = (se.micro_idx & 0xFFu) << 16;
+  tab_ss[sb] = make_int4(srow, srow, S, S);
+  tab_tt[sb] = make_int4(trow, trow, T, T);
+  tab_ts[sb] = make_int4(trow, srow, T, S);
+  for (int t = 0; t < S; ++t) rk_src[srow + t] = make_uint2(se.uid, hi | (uint32_t)t);
+  for (int t = 0; t < T; ++t) rk_tgt[trow + t] = make_uint2(se.uid, hi | (uint32_t)t);
+}
+
 // ================================================================================================
 // launchers
 // ================================================================================================
@@ -845,6 +894,19 @@ int launch_build_tables(const SegmentList& segs, int n_sent, const uint32_t* uid
   NMT_REQUIRE(rk_src && rk_tgt && tab_ss && tab_tt && tab_ts, "build_tables: null pointer");
   hipLaunchKernelGGL(build_tables_kernel, dim3(ceil_div(n_sent, kThreads)), dim3(kThreads), 0, stream, segs, n_sent, uid, rk_src, rk_tgt,
                      tab_ss, tab_tt, tab_ts);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int launch_build_tables_packed(const nmt_sentence* sentences, int n_sent, int n_src, int n_tgt, int max_src, int max_tgt,
+                               int32_t* sent_rows, uint2* rk_src, uint2* rk_tgt, int4* tab_ss, int4* tab_tt, int4* tab_ts,
+                               hipStream_t stream) {
+  NMT_REQUIRE(sentences && n_sent > 0 && n_src >= n_sent && n_tgt >= n_sent && max_src > 0 && max_tgt > 0, "build_tables: bad packed batch");
+  NMT_REQUIRE(sent_rows && rk_src && rk_tgt && tab_ss && tab_tt && tab_ts, "build_tables: null pointer");
+  hipLaunchKernelGGL(packed_rows_kernel, dim3(1), dim3(1024), 0, stream, sentences, n_sent, max_src, max_tgt, sent_rows);
+  NMT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(packed_tables_kernel, dim3(ceil_div(n_sent, kThreads)), dim3(kThreads), 0, stream, sentences, n_sent, n_src, n_tgt,
+                     max_src, max_tgt, sent_rows, rk_src, rk_tgt, tab_ss, tab_tt, tab_ts);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

@@ -78,7 +78,9 @@ class Session:
 
     def reserve(self, B, S=None, T=None):
         """Workspace for one (B, S, T) batch, or for a group given as a list of (B, S, T, micro)."""
-        need = nmt.nmt_workspace_bytes_group(self.ctx, B) if S is None else nmt.nmt_workspace_bytes(self.ctx, B, S, T)
+        self._reserve_bytes(nmt.nmt_workspace_bytes_group(self.ctx, B) if S is None else nmt.nmt_workspace_bytes(self.ctx, B, S, T))
+
+    def _reserve_bytes(self, need):
         for p in range(self.n_pipes):
             if self.workspaces[p] is None or self.workspaces[p].numel() < need:
                 torch.cuda.synchronize(self.device)
@@ -109,9 +111,42 @@ class Session:
             out.append(grp)
         return out
 
+    def pack(self, batches, size=None, pad_id=1):
+        """Host sub-batches (numpy, right-padded) -> packed passes: the sentences of `size` consecutive sub-batches (all if
+        None) back to back without padding, plus the per-sentence table (src_len, tgt_len, uid, micro).  Sub-batch j keeps micro
+        index j; a sentence's uid is its `sent_uid` entry or its index within its sub-batch."""
+        size = len(batches) if size is None else size
+        out = []
+        for g0 in range(0, len(batches), size):
+            sent, src, tin, tout = [], [], [], []
+            for j in range(g0, min(len(batches), g0 + size)):
+                b = batches[j]
+                uid = b.get("sent_uid")
+                for i in range(b["src"].shape[0]):
+                    ls, lt = int((b["src"][i] != pad_id).sum()), int((b["tgt_out"][i] != pad_id).sum())
+                    assert ls >= 1 and lt >= 1 and (b["src"][i, ls:] == pad_id).all() and (b["tgt_out"][i, lt:] == pad_id).all()
+                    sent.append((ls, lt, int(uid[i]) if uid is not None else i, j))
+                    src.append(b["src"][i, :ls])
+                    tin.append(b["tgt_in"][i, :lt])
+                    tout.append(b["tgt_out"][i, :lt])
+            tab = np.asarray(sent, dtype=np.int64)
+            dev = lambda parts: torch.from_numpy(np.ascontiguousarray(np.concatenate(parts), dtype=np.int32)).to(self.device)
+            out.append({"packed": torch.from_numpy(tab.astype(np.uint32).view(np.int32).reshape(-1, 4).copy()).to(self.device),
+                        "n_src": int(tab[:, 0].sum()), "n_tgt": int(tab[:, 1].sum()), "max_src": int(tab[:, 0].max()),
+                        "max_tgt": int(tab[:, 1].max()), "src": dev(src), "tgt_in": dev(tin), "tgt_out": dev(tout)})
+        return out
+
     # ---- the five calls ----
     def forward_loss(self, dbatch, loss_scale, step, micro=0, training=True, pipe=0):
-        """dbatch: one device sub-batch (2-D id tensors), or a group made by Session.group (then `micro` is unused)."""
+        """dbatch: one device sub-batch (2-D id tensors), a group made by Session.group or a packed pass made by Session.pack
+        (for the last two `micro` is unused)."""
+        if "packed" in dbatch:
+            need = nmt.nmt_workspace_bytes_packed(self.ctx, dbatch["packed"].shape[0], dbatch["n_src"], dbatch["n_tgt"])
+            self._reserve_bytes(need)
+            nmt.nmt_forward_loss_packed(self.ctxs[pipe], dbatch["packed"], dbatch["n_src"], dbatch["n_tgt"], dbatch["max_src"],
+                                        dbatch["max_tgt"], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step,
+                                        self.loss_sums[pipe], self.ntoks[pipe], training=training)
+            return
         if "segs" in dbatch:
             self.reserve(dbatch["segs"])
             nmt.nmt_forward_loss_group(self.ctxs[pipe], dbatch["segs"], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale,

@@ -324,3 +324,75 @@ def test_group_entry_point_rejects_bad_segment_lists():
             assert e.value.code == A.NMT_EINVAL
     finally:
         sess.close()
+
+
+def test_packed_sentences_without_padding_match_the_oracle_and_the_padded_pass():
+    """The same three sub-batches as sentences packed back to back: loss, token count and gradient
+    against the oracle's accumulated gradient, and against the padded group pass (pad rows carry
+    nothing, so the two differ by rounding only)."""
+    model = dict(I.MODELS["tiny"], dropout=0.1)
+    weights = I.init_weights(seed=21, perturb=0.05, **model)
+    shapes = [(5, 9, 7), (3, 14, 12), (8, 4, 6)]
+    batches = [I.tiny_batch(seed=300 + i, B=B, S=S, T=T, vocab=model["vocab"], short_by=2) for i, (B, S, T) in enumerate(shapes)]
+    uids = [np.arange(100 * i, 100 * i + b["src"].shape[0], dtype=np.uint32) for i, b in enumerate(batches)]
+    batches = [dict(b, sent_uid=uids[i]) for i, b in enumerate(batches)]
+    cfg = _oracle_cfg(model, act_dropout=0.1, seed=5)
+    P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    loss_scale, step = 64.0, 3
+    acc, loss_ref, ntok_ref, allow = None, 0.0, 0, []
+    for j, mb in enumerate(batches):
+        l, n, cache = O.forward_loss(P16, cfg, mb["src"], mb["tgt_in"], mb["tgt_out"], training=True, step=step, micro=j, sent_uid=uids[j])
+        g = O.backward(P16, cfg, cache, loss_scale)
+        allow.append(_gate_allowance(P16, cfg, cache, loss_scale, g))
+        acc = O.accumulate(acc, g, j == 0)
+        loss_ref += l
+        ntok_ref += n
+    want = O.to_fp16_storage(acc)
+    allow_acc = {k: float(np.sqrt(sum(a[k] ** 2 for a in allow))) for k in allow[0]}
+    sess = Session(model, weights, act_dropout=0.1, seed=5, max_sentences=8)
+    try:
+        (pk,) = sess.pack(batches)
+        assert pk["n_tgt"] == ntok_ref and pk["n_src"] < sum(B * S for B, S, _ in shapes)
+        sess.forward_loss(pk, loss_scale, step)
+        sess.backward()
+        assert int(sess.ntok.item()) == ntok_ref
+        assert abs(float(sess.loss_sum.item()) - loss_ref) / loss_ref <= LOSS_TOL
+        worst = _check_grads(sess, sess.g16, want, model["d_model"], "packed g16", allow_acc)
+        print("packed pass: worst gradient rel-L2", worst)
+        g_packed = host(sess.g16).astype(np.float64)
+        (grp,) = Session.group([sess.to_device(b) for b in batches], 3)
+        sess.forward_loss(grp, loss_scale, step)
+        sess.backward()
+        assert rel_l2(g_packed, host(sess.g16).astype(np.float64)) <= 5e-3
+        # two packed passes (2 + 1 sub-batches) accumulate to the same gradient
+        for i, part in enumerate(sess.pack(batches, size=2)):
+            sess.forward_loss(part, loss_scale, step)
+            sess.backward()
+            sess.accumulate(i == 0)
+        assert rel_l2(host(sess.acc).astype(np.float64), g_packed) <= 5e-3
+    finally:
+        sess.close()
+
+
+def test_packed_entry_point_clamps_inconsistent_lengths_and_rejects_bad_totals():
+    """Lengths on the device that exceed what the host announced are cut to the announced totals (no
+    access outside the buffers; the result is then undefined but finite buffers stay in bounds);
+    totals that cannot belong to the sentence count are refused."""
+    model = I.MODELS["tiny"]
+    sess = Session(model, I.init_weights(seed=1, **model), max_sentences=4, max_len=16)
+    try:
+        ids = torch.full((64,), 5, dtype=torch.int32, device="cuda")
+        tab = torch.tensor([[4, 4, 0, 0], [400, 400, 1, 0], [3, 3, 2, 0]], dtype=torch.int32, device="cuda")   # 2nd entry lies
+        need = A.nmt_workspace_bytes_packed(sess.ctx, 3, 11, 11)
+        sess._reserve_bytes(need)
+        guard = torch.full((1024,), 7, dtype=torch.int32, device="cuda")
+        A.nmt_forward_loss_packed(sess.ctx, tab, 11, 11, 4, 4, ids, ids, ids, 1.0, 1, sess.loss_sum, sess.ntok)
+        sess.backward()
+        torch.cuda.synchronize()
+        assert (guard == 7).all()
+        for n_src, n_tgt, ms, mt in ((2, 11, 4, 4), (11, 11, 0, 4), (11, 11, 4, 17), (13, 11, 4, 4)):
+            with pytest.raises(A.NmtError) as e:
+                A.nmt_forward_loss_packed(sess.ctx, tab, n_src, n_tgt, ms, mt, ids, ids, ids, 1.0, 1, sess.loss_sum, sess.ntok)
+            assert e.value.code == A.NMT_EINVAL
+    finally:
+        sess.close()
