@@ -10,6 +10,7 @@ import pytest
 import nmt_inputs as I
 from oracle import nmt_oracle as O
 from paper_1806_00187_amd.session import Session
+from tests.gpu_util import host, rel_l2
 from tests.test_gpu_step import GRAD_TOL, LOSS_TOL, _check_grads, _gate_allowance, _oracle_cfg
 
 pytestmark = pytest.mark.gpu
@@ -67,3 +68,48 @@ def test_transformer_base_long_sequences_match_oracle():
     batch = I.fill_batch(buckets[-1], src_len, tgt_len, model["vocab"], rng)
     assert max(batch["src"].shape[1], batch["tgt_in"].shape[1]) > 200
     _full_size_case("base", batch, loss_scale=32.0, draws=2)
+
+
+def test_bench_configuration_one_packed_pass_equals_sub_batches_one_by_one():
+    """The launch configuration bench.py times: Transformer-big, all 16 sub-batches of an update as one
+    packed pass.  The oracle cannot run 53k tokens of the big model in test time, so this checks the
+    property that holds at any size: the pass must give the loss, token count and gradient of the 16
+    sub-batches processed one by one through the path the tests above pin to the oracle, up to the
+    rounding of one fp16 store per sub-batch (the one-by-one gradients) versus one per pass."""
+    model = I.MODELS["big"]
+    weights = I.init_weights(seed=0, **model)
+    batches = I.workload_batches("big_accum", which="random", count=16, n_sentences=50_000)
+    loss_scale, step = 1.0, 5
+    sess = Session(model, weights, max_sentences=max(b["src"].shape[0] for b in batches), max_len=256)
+    try:
+        loss_1, ntok_1 = 0.0, 0
+        for j, b in enumerate(batches):
+            sess.forward_loss(sess.to_device(b), loss_scale, step, j)
+            sess.backward()
+            sess.accumulate(j == 0)
+            loss_1 += float(sess.loss_sum.item())
+            ntok_1 += int(sess.ntok.item())
+        ref = sess.named(sess.acc)
+        ref = {k: v.astype(np.float64) for k, v in ref.items()}
+        (pk,) = sess.pack(batches)
+        sess.forward_loss(pk, loss_scale, step)
+        sess.backward()
+        assert int(sess.ntok.item()) == ntok_1 == pk["n_tgt"]
+        assert abs(float(sess.loss_sum.item()) - loss_1) / loss_1 <= 1e-4
+        got = sess.named(sess.g16)
+        d = model["d_model"]
+        worst = ("", 0.0)
+        for name, w in ref.items():
+            g = got[name].astype(np.float64).reshape(w.shape)
+            assert np.isfinite(g).all(), name
+            if name.endswith(("bqkv", "bkv")):      # the key-bias part is zero in exact arithmetic: compare the rest
+                key = slice(d, 2 * d) if name.endswith("bqkv") else slice(0, d)
+                rest = np.ones(w.shape[0], dtype=bool)
+                rest[key] = False
+                g, w = g[rest], w[rest]
+            e = rel_l2(g, w)
+            worst = max(worst, (name, e), key=lambda t: t[1])
+            assert e <= 5e-3, (name, e)
+        print("packed pass of 16 sub-batches vs one by one: worst gradient rel-L2", worst, flush=True)
+    finally:
+        sess.close()
