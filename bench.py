@@ -183,7 +183,8 @@ def main():
 
     if not args.no_legs:
         result["phases_ms_per_update"] = phase_leg(sess, tr, dbatches, ntoks, torch)
-        result["roofline"] = gemm_leg(model, pass_rows, A, torch, log)     # the dominant kernel
+        result["roofline"] = gemm_leg(model, pass_rows, A, torch, log,     # the dominant kernel
+                                      MEASURED_GEMM_TRAFFIC if (args.workload == "big_accum" and packed and group == 16) else None)
         result["hbm_kernels"] = hbm_leg(sess, torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(model, weights, batches[len(batches) // 2], k_micro, tokens_per_step, tr.scale, log)
@@ -233,7 +234,13 @@ def phase_leg(sess, tr, dbatches, ntoks, torch):
     return acc
 
 
-def gemm_leg(model, pass_rows, A, torch, log):
+# HBM-side bytes per product of the default workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated against
+# kernels of known size; profiles/bench_big_accum_gemm_hbm_traffic.txt): 197.5 GB per update over 201 products,
+# for 87.4 GB of algorithmic operand + result bytes.
+MEASURED_GEMM_TRAFFIC = {"bytes_per_launch": 983e6, "algorithmic_bytes_per_launch": 435e6, "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
+
+
+def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
     """Every distinct GEMM of the update timed alone through nmt_op_gemm (HIP events, 10 launches
     each): algorithmic FLOPs / summed average durations = achieved rate of the GEMM kernel."""
     agg = {}
@@ -277,7 +284,7 @@ def gemm_leg(model, pass_rows, A, torch, log):
     achieved = tot_flops / tot_ms / 1e9
     log(f"[bench] GEMM leg: {achieved:.1f} TFLOP/s over {n_launch} launches, {tot_ms:.2f} ms per update; worst {worst}, best {best}")
     return {"bound": "mfma", "kernel": "gemm_kernel (all GEMM launches of one update, each shape timed alone)",
-            "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS, "traffic": None,
+            "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS, "traffic": traffic,
             "launches_per_update": n_launch, "avg_launch_us": tot_ms * 1e3 / n_launch, "ms_per_update": tot_ms,
             "by_kind_tflops": {k: v[0] / v[1] / 1e9 for k, v in per_kind.items()}, "worst_tflops": worst, "best_tflops": best}
 
