@@ -289,7 +289,8 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[set][i], bf[set][j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < TN; ++j)  // B first: the result tile is transposed, lane = row of C, registers = columns
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[set][j], af[set][i], acc[i][j], 0, 0, 0);
   };
   auto interleave = [&]() { Interleave<0, TM * TN, OpA::READS * TM + OpB::READS * TN>::run(); };
   // One k-tile.  On entry the fragments of k-step 0 of `cur` are in registers and the next NS-1
@@ -344,11 +345,17 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   __syncthreads();
 
   // ---- epilogue: accumulators -> per-wave LDS staging (fp32) -> row-wise 16-byte stores -------
-  // staging width per pass: the wave's whole width if 4 waves x 32 rows of it fit one stage, else 32
+  // The products were formed as (B tile) x (A tile)^T, so in the MFMA result layout lane l holds row
+  // l%32 of the C tile and, in registers 4q..4q+3, the four consecutive columns 8q + 4(l/32) .. +3:
+  // one 16-byte LDS write per register quad.  A staged row is SW floats; its 16-byte chunks are
+  // XOR-swizzled with the row so that 16 lanes (16 rows, same logical chunk) hit every bank once.
+  // staging width per pass: the wave's whole width if NW waves x 32 rows of it fit one stage, else less
   constexpr int SW = (NW * 32 * WN * 4 <= T::STAGE) ? WN : (NW * 32 * 64 * 4 <= T::STAGE && WN % 64 == 0) ? 64 : 32;
   static_assert(NW * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
   float* stg = reinterpret_cast<float*>(stage1) + wave * (32 * SW);
-  constexpr int CH = SW / 8;  // 8-column chunks per staged row
+  constexpr int CH = SW / 8;    // 8-column chunks per staged row
+  constexpr int QC = SW / 4;    // 16-byte chunks per staged row (8, 16 or 32)
+  auto swz = [](int row, int chunk) { return QC >= 16 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7)); };
   const GemmEpilogue& ep = g.ep;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -358,9 +365,11 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
 #pragma unroll
       for (int jj = 0; jj < SW / 32; ++jj)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);  // MFMA 32x32 result layout
-          stg[row * SW + jj * 32 + (lane & 31)] = acc[i][jg * (SW / 32) + jj][r];
+        for (int q = 0; q < 4; ++q) {
+          const floatx16& a = acc[i][jg * (SW / 32) + jj];
+          const floatx4 v4 = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+          const int row = lane & 31, chunk = jj * 8 + 2 * q + (lane >> 5);
+          *reinterpret_cast<floatx4*>(stg + row * SW + swz(row, chunk) * 4) = v4;
         }
       wave_sync();
 #pragma unroll
@@ -370,8 +379,8 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
         const int gr = m0 + wm * WM + i * 32 + rl, gc = n0 + wn * WN + jg * SW + c8 * 8;
         if (gr < g.M && gc < g.N) {
           float v[8];
-          const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + rl * SW + c8 * 8);
-          const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + rl * SW + c8 * 8 + 4);
+          const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + rl * SW + swz(rl, 2 * c8) * 4);
+          const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + rl * SW + swz(rl, 2 * c8 + 1) * 4);
           if (g.partial) {
             float* dst = g.partial + ((size_t)blockIdx.y * g.M + gr) * g.N + gc;
             *reinterpret_cast<floatx4*>(dst) = lo;
