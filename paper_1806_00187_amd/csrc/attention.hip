@@ -126,6 +126,35 @@ __device__ __forceinline__ uint32_t hidden_keys(const AttnArgs& a, const Sent& s
   return (uint32_t)__ballot(hid);
 }
 
+// Writes a transposed result tile (MFMA layout: lane = row l%32 of the output, registers = groups of
+// four consecutive columns) to global memory through the wavefront's LDS tile, so that every store
+// instruction covers whole 2*DH-byte rows instead of 16-byte pieces of 32 rows.
+template <int DH>
+__device__ __forceinline__ void store_rows(half_t* tile, const floatx16 (&acc)[(DH < 32 ? 32 : DH) / 32], float scale, half_t* dst, int ld,
+                                           int row0, int row_end, int lane) {
+  constexpr int PR = DH + 8, DT = (DH < 32 ? 32 : DH) / 32, CH = DH / 8;
+  const int g = lane >> 5;
+  wave_sync();  // earlier reads of the tile are done
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int dh0 = t * 32 + 8 * rq + 4 * g;
+      if (dh0 < DH) {
+        half4_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (half_t)(acc[t][4 * rq + e] * scale);
+        *reinterpret_cast<half4_t*>(tile + (lane & 31) * PR + dh0) = o;
+      }
+    }
+  wave_sync();
+#pragma unroll
+  for (int it = 0; it < (32 * CH + 63) / 64; ++it) {
+    const int idx = it * 64 + lane, r = idx / CH, c = idx % CH;
+    if (r < 32 && row0 + r < row_end) st_half8(dst + (size_t)(row0 + r) * ld + c * 8, ld_half8(tile + r * PR + c * 8));
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // forward: the wavefront owns 32 queries
 // ------------------------------------------------------------------------------------------------
@@ -196,20 +225,8 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
     }
   }
   l += __shfl_xor(l, 32, kWave);
+  store_rows<DH>(Vs, oacc, 1.f / l, a.Out + (size_t)se.q0 * a.ldo + h * DH, a.ldo, q0, se.Tq, lane);
   if (!qvalid) return;
-  const float inv = 1.f / l;
-#pragma unroll
-  for (int t = 0; t < DT; ++t)
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const int dh0 = t * 32 + 8 * rq + 4 * g;
-      if (dh0 < DH) {
-        half4_t o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (half_t)(oacc[t][4 * rq + e] * inv);
-        *reinterpret_cast<half4_t*>(a.Out + (size_t)(se.q0 + q) * a.ldo + h * DH + dh0) = o;
-      }
-    }
   if (g == 0) a.lse[(size_t)h * a.Nq + se.q0 + q] = (m + log2f(l)) * kLn2;
 }
 
@@ -304,23 +321,8 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
         dKt[t] = MFMA(tr_frag<DH>(Qs, PR, kb, t, lane), dsf[s2], dKt[t]);
       }
   }
-  if (!kvalid) return;
-#pragma unroll
-  for (int t = 0; t < DT; ++t)
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const int dh0 = t * 32 + 8 * rq + 4 * g;
-      if (dh0 < DH) {
-        half4_t ok, ov;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          ok[e] = (half_t)dKt[t][4 * rq + e];
-          ov[e] = (half_t)dVt[t][4 * rq + e];
-        }
-        *reinterpret_cast<half4_t*>(a.dK + (size_t)(se.k0 + key) * a.lddk + h * DH + dh0) = ok;
-        *reinterpret_cast<half4_t*>(a.dV + (size_t)(se.k0 + key) * a.lddv + h * DH + dh0) = ov;
-      }
-    }
+  store_rows<DH>(Qs, dKt, 1.f, a.dK + (size_t)se.k0 * a.lddk + h * DH, a.lddk, k0, se.Tk, lane);
+  store_rows<DH>(dOs, dVt, 1.f, a.dV + (size_t)se.k0 * a.lddv + h * DH, a.lddv, k0, se.Tk, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -387,19 +389,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) dQt[t] = MFMA(tr_frag<DH>(Ks, PR, 16 * s2 + 4 * g, t, lane), dsf[s2], dQt[t]);
   }
-  if (!qvalid) return;
-#pragma unroll
-  for (int t = 0; t < DT; ++t)
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const int dh0 = t * 32 + 8 * rq + 4 * g;
-      if (dh0 < DH) {
-        half4_t o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (half_t)dQt[t][4 * rq + e];
-        *reinterpret_cast<half4_t*>(a.dQ + (size_t)(se.q0 + q) * a.lddq + h * DH + dh0) = o;
-      }
-    }
+  store_rows<DH>(Ks, dQt, 1.f, a.dQ + (size_t)se.q0 * a.lddq + h * DH, a.lddq, q0, se.Tq, lane);
 }
 
 template <int DH>
