@@ -350,9 +350,12 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   // one 16-byte LDS write per register quad.  A staged row is SW floats; its 16-byte chunks are
   // XOR-swizzled with the row so that 16 lanes (16 rows, same logical chunk) hit every bank once.
   // staging width per pass: the wave's whole width if NW waves x 32 rows of it fit one stage, else less
-  constexpr int SW = (NW * 32 * WN * 4 <= T::STAGE) ? WN : (NW * 32 * 64 * 4 <= T::STAGE && WN % 64 == 0) ? 64 : 32;
-  static_assert(NW * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
-  float* stg = reinterpret_cast<float*>(stage1) + wave * (32 * SW);
+  // (half of the waves stage in stage0, the other half in stage1, so that a staged row can be 64 columns
+  //  = whole 128-byte lines of fp16 output even when a stage is small)
+  constexpr int HW = NW / 2;
+  constexpr int SW = (HW * 32 * WN * 4 <= T::STAGE) ? WN : (HW * 32 * 64 * 4 <= T::STAGE && WN % 64 == 0) ? 64 : 32;
+  static_assert(HW * 32 * SW * 4 <= T::STAGE, "epilogue staging does not fit");
+  float* stg = reinterpret_cast<float*>(wave < HW ? stage0 : stage1) + (wave % HW) * (32 * SW);
   constexpr int CH = SW / 8;    // 8-column chunks per staged row
   constexpr int QC = SW / 4;    // 16-byte chunks per staged row (8, 16 or 32)
   auto swz = [](int row, int chunk) { return QC >= 16 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7)); };
