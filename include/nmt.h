@@ -129,13 +129,21 @@ int nmt_forward_loss_packed(nmt_ctx* ctx, int32_t n_sent, const nmt_sentence* d_
                             const int32_t* d_tgt_in, const int32_t* d_tgt_out, float loss_scale, uint32_t step,
                             int32_t training, float* d_loss_sum, int32_t* d_ntok, void* stream);
 
-/* Backward pass in fp16 of the last nmt_forward_loss / nmt_forward_loss_group / nmt_forward_loss_packed; writes every element of g16 with the
- * gradient of loss_scale * loss_sum ("perform the backward pass as usual"). */
+/* Backward pass in fp16 of the last nmt_forward_loss / nmt_forward_loss_group /
+ * nmt_forward_loss_packed; writes every element of g16 with nmt_grad_scale(ctx) times the gradient
+ * of loss_scale * loss_sum ("perform the backward pass as usual"). */
 int nmt_backward(nmt_ctx* ctx, void* stream);
 
 /* Gradient accumulation over sub-batches ("Training with Larger Batches"):
- * first != 0: acc32 = float(g16); else acc32 += float(g16). */
+ * first != 0: acc32 = float(g16) / s; else acc32 += float(g16) / s, where s = nmt_grad_scale(ctx). */
 int nmt_accumulate(nmt_ctx* ctx, int32_t first, void* stream);
+
+/* The power-of-two factor s <= 1 by which the last forward call's pass scales what it writes to g16:
+ * g16 = fp16(s * gradient of loss_scale * loss_sum).  s = 1 for passes of fewer than 8192 target
+ * positions (any single sub-batch of the paper's size) and halves with every doubling beyond that, so
+ * that the sum over a group of sub-batches reaches the fp16 range at the same loss scale as a single
+ * sub-batch's gradient would.  nmt_accumulate divides it out again (exactly). */
+float nmt_grad_scale(const nmt_ctx* ctx);
 
 /* Conversion of the accumulated gradients to their original scale plus overflow detection in
  * one pass ("Half-Precision Training"): *d_flag = 1 iff any element of acc32 is inf or NaN,

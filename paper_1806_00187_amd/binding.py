@@ -45,6 +45,7 @@ _SIGNATURES = {
     "nmt_destroy": (None, [_P]),
     "nmt_param_count": (_I64, [_P]),
     "nmt_param_tensors": (_I32, [_P]),
+    "nmt_grad_scale": (C.c_float, [_P]),
     "nmt_param_info": (C.c_int, [_P, _I32, C.POINTER(C.c_char_p), C.POINTER(_I64), C.POINTER(_I32), C.POINTER(_I32)]),
     "nmt_workspace_bytes": (_I64, [_P, _I32, _I32, _I32]),
     "nmt_workspace_bytes_group": (_I64, [_P, _I32, _SP]),
@@ -140,6 +141,10 @@ def nmt_destroy(ctx):
 
 def nmt_param_count(ctx):
     return load().nmt_param_count(ctx)
+
+
+def nmt_grad_scale(ctx):
+    return load().nmt_grad_scale(ctx)
 
 
 def nmt_param_tensors(ctx):

@@ -133,6 +133,7 @@ struct GemmEpilogue {
   const half_t* relu_src = nullptr;
   float mask_scale = 1.f;
   int row0 = 0;  // row of the whole activation that row 0 of this product is (dropout counters)
+  float out_scale = 1.f;  // the accumulated product is multiplied by this first (weight gradients of a large pass)
 };
 // partial: optional fp32 scratch of partial_floats floats for cutting the contraction into `splits`
 // pieces summed by a second kernel (splits == 0: the launcher decides; needs an empty epilogue).
@@ -156,18 +157,18 @@ int64_t layernorm_bwd_scratch_floats(int d);
 int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const half_t* resid, const half_t* gamma,
                                   const float* stats, half_t* dy, half_t* dym, half_t* dgamma, half_t* dbeta,
                                   half_t* dbias, float* partial, int rows, int d, const DropDev& drop,
-                                  hipStream_t stream);
+                                  hipStream_t stream, float vec_scale = 1.f);  // vec_scale: factor on dgamma, dbeta, dbias
 int launch_embed_fwd(const int32_t* ids, const half_t* E, half_t* x, int rows, int d, int vocab, const DropDev& drop,
                      hipStream_t stream);
 int launch_softmax_xent(half_t* logits, const int32_t* targets, float* row_loss, int rows, int V, int pad_id,
                         float eps_ls, float loss_scale, float* loss_sum, int32_t* ntok, hipStream_t stream);
 int64_t colsum_scratch_floats(int cols);
-int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream);
+int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream, float scale = 1.f);
 int64_t embed_bwd_scratch_ints(int vocab, int rows_total, int d);
 int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const DropDev& drop_a,
                      const int32_t* ids_b, const half_t* dx_b, int rows_b, const DropDev& drop_b, half_t* gE, int d,
-                     int vocab, int32_t* scratch, hipStream_t stream);
-int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipStream_t stream);
+                     int vocab, int32_t* scratch, hipStream_t stream, float scale = 1.f);
+int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipStream_t stream, float mult = 1.f);
 int launch_check_overflow(float* acc, int64_t n, float inv_scale, int32_t* flag, hipStream_t stream);
 int launch_adam(float* master, float* m, float* v, const float* g, half_t* w16, int64_t n, float lr, float b1,
                 float b2, float eps, int t, const int32_t* flag, hipStream_t stream);

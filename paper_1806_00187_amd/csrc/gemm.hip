@@ -392,8 +392,8 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
           }
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            v[e] = lo[e];
-            v[4 + e] = hi[e];
+            v[e] = lo[e] * ep.out_scale;
+            v[4 + e] = hi[e] * ep.out_scale;
           }
           if (ep.bias) {
             const half8_t b = ld_half8(ep.bias + gc);
@@ -432,7 +432,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
 
 // C[m, n] = fp16(sum_z partial[z][m][n]), 8 columns per thread, splits summed in increasing order
 __global__ void __launch_bounds__(kThreads) splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N,
-                                                                half_t* __restrict__ C, int ldc) {
+                                                                half_t* __restrict__ C, int ldc, float scale) {
   const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int chunks = N >> 3;
   if (gid >= (int64_t)M * chunks) return;
@@ -446,8 +446,8 @@ __global__ void __launch_bounds__(kThreads) splitk_reduce_kernel(const float* __
   half8_t o;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    o[e] = (half_t)lo[e];
-    o[4 + e] = (half_t)hi[e];
+    o[e] = (half_t)(lo[e] * scale);
+    o[4 + e] = (half_t)(hi[e] * scale);
   }
   st_half8(C + (size_t)row * ldc + c8 * 8, o);
 }
@@ -481,7 +481,7 @@ int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t s
   else rc = launch_variant<BM, BN, true, false, BK, NS, NW>(g, splits, stream);
   if (rc != NMT_OK || splits == 1) return rc;
   const int64_t n = (int64_t)g.M * (g.N / 8);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, g.partial, splits, g.M, g.N, g.C, g.ldc);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, g.partial, splits, g.M, g.N, g.C, g.ldc, g.ep.out_scale);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -512,7 +512,7 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   NMT_REQUIRE(!ep.bias || aligned16(ep.bias), "gemm: bias must be 16-byte aligned");
   NMT_REQUIRE((!ep.add || aligned16(ep.add)) && (!ep.relu_src || aligned16(ep.relu_src)), "gemm: epilogue operand misaligned");
   NMT_REQUIRE(splits >= 0 && splits <= 64, "gemm: number of k splits %d outside [0, 64]", splits);
-  const bool plain = !ep.bias && !ep.relu && !ep.drop.thr && !ep.add && !ep.relu_src;
+  const bool plain = !ep.bias && !ep.relu && !ep.drop.thr && !ep.add && !ep.relu_src;  // (out_scale is applied by the reduction)
   NMT_REQUIRE(splits <= 1 || (partial && plain), "gemm: splitting k needs a partial-sum buffer and no epilogue");
   NMT_REQUIRE(!partial || (reinterpret_cast<uintptr_t>(partial) & 15u) == 0, "gemm: partial-sum buffer must be 16-byte aligned");
   GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, ep, partial, 0};

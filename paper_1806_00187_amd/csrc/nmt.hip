@@ -98,6 +98,7 @@ struct nmt_ctx {
   bool have_fwd = false;
   int Bt = 0, Ns = 0, Nt = 0, maxS = 0, maxT = 0, training = 0;  // sentences, source / target rows, longest sides
   float loss_scale = 1.f;
+  float gscale = 1.f;  // power-of-two factor on everything the current pass writes to g16
   uint32_t step = 0;
   const int32_t *src = nullptr, *tgt_in = nullptr, *tgt_out = nullptr;
   Plan plan;
@@ -309,6 +310,7 @@ extern "C" void nmt_destroy(nmt_ctx* ctx) {
   delete ctx;
 }
 extern "C" int64_t nmt_param_count(const nmt_ctx* ctx) { return ctx ? ctx->P : -1; }
+extern "C" float nmt_grad_scale(const nmt_ctx* ctx) { return ctx ? ctx->gscale : 0.f; }
 extern "C" int32_t nmt_param_tensors(const nmt_ctx* ctx) { return ctx ? (int32_t)ctx->tensors.size() : -1; }
 
 extern "C" int nmt_param_info(const nmt_ctx* ctx, int32_t idx, const char** name, int64_t* offset, int32_t* rows, int32_t* cols) {
@@ -383,7 +385,9 @@ struct Run {
   }
   // gW[out, in] = dy^T x
   int wgrad(const half_t* dy, int N, int out, const half_t* x, int in, int64_t gW) const {
-    return launch_gemm(dy, true, out, x, true, in, c->g16 + gW, in, out, in, N, GemmEpilogue{}, st,
+    GemmEpilogue ep;
+    ep.out_scale = c->gscale;
+    return launch_gemm(dy, true, out, x, true, in, c->g16 + gW, in, out, in, N, ep, st,
                        c->plan.wgpart_floats ? ws<float>(c->plan.wgpart) : nullptr, c->plan.wgpart_floats, 0);
   }
 };
@@ -485,6 +489,11 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
   }
   c->Bt = (int)gd.Bt; c->Ns = (int)gd.Ns; c->Nt = (int)gd.Nt; c->maxS = gd.maxS; c->maxT = gd.maxT;
   c->loss_scale = loss_scale; c->step = step; c->training = training != 0;
+  // A pass over many sub-batches sums proportionally more token gradients into each weight gradient.
+  // Scaling that sum down by a power of two before the one fp16 rounding keeps it in the range a single
+  // sub-batch's gradient has, so grouping does not lower the loss scale at which fp16 overflows.
+  c->gscale = 1.f;
+  for (int64_t n = gd.Nt; n >= 8192; n >>= 1) c->gscale *= 0.5f;
   c->src = d_src; c->tgt_in = d_tgt_in; c->tgt_out = d_tgt_out;
 
   const nmt_config& k = c->cfg;
@@ -643,7 +652,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
                      const FfnP& f, const LnP& ln, uint32_t site_res) -> int {
     NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, sub, x_in, r.w(ln.g), stats, dy, dym, r.g(ln.g), r.g(ln.b), r.g(f.b2), lnpart, N, d,
-                                          r.drop(site_res, tgt, k.dropout), st));
+                                          r.drop(site_res, tgt, k.dropout), st, c->gscale));
     NMT_TRY(fork());
     NMT_TRY(w.wgrad(dsub, N, d, hact, F, f.w2));
     GemmEpilogue relu_bwd;
@@ -651,7 +660,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     relu_bwd.mask_scale = act_scale;
     NMT_TRY(r.dgrad(dsub, N, d, f.w2, F, dhid, relu_bwd));
     NMT_TRY(fork());
-    NMT_TRY(launch_colsum(dhid, F, w.g(f.b1), cspart, N, F, sd));
+    NMT_TRY(launch_colsum(dhid, F, w.g(f.b1), cspart, N, F, sd, c->gscale));
     NMT_TRY(w.wgrad(dhid, N, F, x_in, d, f.w1));
     GemmEpilogue res;
     res.add = dy;
@@ -664,7 +673,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
                       int causal) -> int {
     NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, sub, x_in, r.w(ln.g), stats, dy, dym, r.g(ln.g), r.g(ln.b), r.g(a.bo), lnpart, N, d,
-                                          r.drop(site_res, tgt, k.dropout), st));
+                                          r.drop(site_res, tgt, k.dropout), st, c->gscale));
     NMT_TRY(fork());
     NMT_TRY(w.wgrad(dsub, N, d, o, d, a.wo));
     NMT_TRY(r.dgrad(dsub, N, d, a.wo, d, dO));
@@ -672,7 +681,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
                                  dqkv + 2 * d, 3 * d, key_ids, k.pad_id, causal, Bt, H, dh, tgt ? maxT : maxS, tgt ? maxT : maxS,
                                  tgt ? tab_tt : tab_ss, N, st));
     NMT_TRY(fork());
-    NMT_TRY(launch_colsum(dqkv, 3 * d, w.g(a.bqkv), cspart, N, 3 * d, sd));
+    NMT_TRY(launch_colsum(dqkv, 3 * d, w.g(a.bqkv), cspart, N, 3 * d, sd, c->gscale));
     NMT_TRY(w.wgrad(dqkv, N, 3 * d, x_in, d, a.wqkv));
     GemmEpilogue res;
     res.add = dy;
@@ -687,7 +696,9 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   const half_t* x_dec = r.ws<half_t>(p.dec[k.dec_layers - 1].x3);
   half_t* dx = r.ws<half_t>(p.dx_dec);
   NMT_TRY(fork());
-  NMT_TRY(launch_gemm(dlogits, true, V, x_dec, true, d, w.g(c->embed), d, V, d, Nt, GemmEpilogue{}, sd));
+  GemmEpilogue vocab_ep;
+  vocab_ep.out_scale = c->gscale;
+  NMT_TRY(launch_gemm(dlogits, true, V, x_dec, true, d, w.g(c->embed), d, V, d, Nt, vocab_ep, sd));
   NMT_TRY(launch_gemm(dlogits, false, V, r.w(c->embed), true, d, dx, d, Nt, d, V, GemmEpilogue{}, st));
 
   // ---- decoder, top to bottom ----
@@ -704,7 +715,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_TRY(begin_sublayer());
     NMT_TRY(launch_residual_layernorm_bwd(dx, r.ws<half_t>(W.s2), r.ws<half_t>(W.x1), r.w(P.ln2.g), r.ws<float>(W.st2), dy, dym,
                                           r.g(P.ln2.g), r.g(P.ln2.b), r.g(P.cross.bo), lnpart, Nt, d,
-                                          r.drop(layer_site(li, kKindCrossRes), true, k.dropout), st));
+                                          r.drop(layer_site(li, kKindCrossRes), true, k.dropout), st, c->gscale));
     NMT_TRY(fork());
     NMT_TRY(w.wgrad(dsub, Nt, d, r.ws<half_t>(W.o2), d, P.cross.wo));
     NMT_TRY(r.dgrad(dsub, Nt, d, P.cross.wo, d, dO));
@@ -712,8 +723,8 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_TRY(launch_attention_bwd(r.ws<half_t>(W.q), d, kv, 2 * d, kv + d, 2 * d, r.ws<half_t>(W.o2), d, dO, d, r.ws<float>(W.lse2), dq, d,
                                  dkv, 2 * d, dkv + d, 2 * d, c->src, k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, st));
     NMT_TRY(fork());
-    NMT_TRY(launch_colsum(dq, d, w.g(P.cross.bq), cspart, Nt, d, sd));
-    NMT_TRY(launch_colsum(dkv, 2 * d, w.g(P.cross.bkv), cspart, Ns, 2 * d, sd));
+    NMT_TRY(launch_colsum(dq, d, w.g(P.cross.bq), cspart, Nt, d, sd, c->gscale));
+    NMT_TRY(launch_colsum(dkv, 2 * d, w.g(P.cross.bkv), cspart, Ns, 2 * d, sd, c->gscale));
     NMT_TRY(w.wgrad(dq, Nt, d, r.ws<half_t>(W.x1), d, P.cross.wq));
     NMT_TRY(w.wgrad(dkv, Ns, 2 * d, enc_out, d, P.cross.wkv));
     GemmEpilogue res;
@@ -744,7 +755,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   NMT_HIP_CHECK(hipEventRecord(c->ev_join, sd));
   NMT_HIP_CHECK(hipStreamWaitEvent(st, c->ev_join, 0));
   NMT_TRY(launch_embed_bwd(c->src, denc, Ns, r.drop(kSiteEmbSrc, false, k.dropout), c->tgt_in, dx_dec0, Nt, r.drop(kSiteEmbTgt, true, k.dropout),
-                           r.g(c->embed), d, V, r.ws<int32_t>(p.embscratch), st));
+                           r.g(c->embed), d, V, r.ws<int32_t>(p.embscratch), st, c->gscale));
   return NMT_OK;
 }
 
@@ -753,7 +764,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
 // ================================================================================================
 extern "C" int nmt_accumulate(nmt_ctx* ctx, int32_t first, void* stream) {
   NMT_REQUIRE(ctx && ctx->g16 && ctx->acc, "nmt_accumulate: g16 / acc32 not bound");
-  return launch_accumulate(ctx->g16, ctx->acc, ctx->P, first, static_cast<hipStream_t>(stream));
+  return launch_accumulate(ctx->g16, ctx->acc, ctx->P, first, static_cast<hipStream_t>(stream), 1.f / ctx->gscale);
 }
 extern "C" int nmt_check_overflow(nmt_ctx* ctx, float inv_scale, int32_t* d_flag, void* stream) {
   NMT_REQUIRE(ctx && ctx->acc, "nmt_check_overflow: acc32 not bound");

@@ -8,8 +8,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxBlocks = 256 * 8;  // 8 work-groups per CU keeps enough loads in flight
 
+// acc (+)= mult * float(g16); mult undoes the power-of-two factor a pass applied before rounding to fp16
 __global__ void __launch_bounds__(kThreads) accumulate_kernel(const half_t* __restrict__ g16, float* __restrict__ acc, int64_t n,
-                                                              int first) {
+                                                              int first, float mult) {
   const int64_t nvec = n >> 3;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
@@ -25,15 +26,15 @@ __global__ void __launch_bounds__(kThreads) accumulate_kernel(const half_t* __re
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      lo[e] += (float)g[e];
-      hi[e] += (float)g[4 + e];
+      lo[e] += mult * (float)g[e];
+      hi[e] += mult * (float)g[4 + e];
     }
     a[0] = lo;
     a[1] = hi;
   }
   // tail (n not a multiple of 8)
   for (int64_t i = (nvec << 3) + (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
-    acc[i] = (first ? 0.f : acc[i]) + (float)g16[i];
+    acc[i] = (first ? 0.f : acc[i]) + mult * (float)g16[i];
 }
 
 __global__ void set_flag_kernel(int32_t* flag, int32_t v) { *flag = v; }
@@ -106,10 +107,10 @@ int grid_for(int64_t nvec) {
 
 }  // namespace
 
-int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipStream_t stream) {
+int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipStream_t stream, float mult) {
   NMT_REQUIRE(g16 && acc && n > 0, "accumulate: bad arguments");
   NMT_REQUIRE(aligned16(g16) && aligned16(acc), "accumulate: buffers must be 16-byte aligned");
-  hipLaunchKernelGGL(accumulate_kernel, dim3(grid_for(n >> 3)), dim3(kThreads), 0, stream, g16, acc, n, first);
+  hipLaunchKernelGGL(accumulate_kernel, dim3(grid_for(n >> 3)), dim3(kThreads), 0, stream, g16, acc, n, first, mult);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

@@ -252,7 +252,8 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
 // flight) and are combined in a fixed order.
 constexpr int kFinThreads = 1024;
 __global__ void __launch_bounds__(kFinThreads) finalize_partials_kernel(const float* __restrict__ partial, int nblk, int nq,
-                                                                        int cols, int pitch, half_t* d0, half_t* d1, half_t* d2) {
+                                                                        int cols, int pitch, half_t* d0, half_t* d1, half_t* d2,
+                                                                        float scale) {
   __shared__ float red[32][33];
   const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
   const int cblocks = (cols + 31) / 32;
@@ -273,7 +274,7 @@ __global__ void __launch_bounds__(kFinThreads) finalize_partials_kernel(const fl
 #pragma unroll
     for (int r = 1; r < 32; ++r) t += red[r][cx];
     half_t* dst = k == 0 ? d0 : (k == 1 ? d1 : d2);
-    if (dst) dst[col] = (half_t)t;
+    if (dst) dst[col] = (half_t)(t * scale);
   }
 }
 
@@ -547,11 +548,11 @@ __device__ __forceinline__ void emb_row_chunk(int pos, int c, int d, const half_
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] += ((bits >> e) & 1u) ? x[e] * sc : 0.f;
 }
-__device__ __forceinline__ void emb_add_to_row(half_t* __restrict__ gE, int v, int c, int d, const float (&tot)[8]) {
+__device__ __forceinline__ void emb_add_to_row(half_t* __restrict__ gE, int v, int c, int d, const float (&tot)[8], float scale) {
   half_t* dst = gE + (size_t)v * d + c * 8;
   float cur[8];
   unpack8(ld_half8(dst), cur);
-  const float sq = sqrtf((float)d);
+  const float sq = sqrtf((float)d) * scale;
 #pragma unroll
   for (int e = 0; e < 8; ++e) cur[e] += sq * tot[e];
   st_half8(dst, pack8(cur));
@@ -564,7 +565,7 @@ __global__ void __launch_bounds__(kThreads) emb_segment_kernel(const int32_t* a,
                                                                const int32_t* b, const half_t* __restrict__ dxb, int nb, DropDev db,
                                                                half_t* __restrict__ gE, int d, int vocab,
                                                                const int32_t* __restrict__ start, const int32_t* __restrict__ perm,
-                                                               float* __restrict__ part) {
+                                                               float* __restrict__ part, float scale) {
   __shared__ int s_pos[kEmbSeg], s_id[kEmbSeg];
   const int n = na + nb, e0 = blockIdx.x * kEmbSeg, cnt = min(kEmbSeg, n - e0);
   if ((int)threadIdx.x < cnt) {
@@ -583,7 +584,7 @@ __global__ void __launch_bounds__(kThreads) emb_segment_kernel(const int32_t* a,
     if (k + 1 < cnt && s_id[k + 1] == v) continue;
     const int g_begin = start[v], g_end = start[v + 1];  // where id v's positions lie in the sorted list
     if (g_begin == e0 + run_begin && g_end == e0 + k + 1) {
-      emb_add_to_row(gE, v, c, d, acc);
+      emb_add_to_row(gE, v, c, d, acc, scale);
     } else {
       float* dst = part + ((size_t)2 * blockIdx.x + (g_begin < e0 ? 0 : 1)) * d + c * 8;
 #pragma unroll
@@ -597,7 +598,8 @@ __global__ void __launch_bounds__(kThreads) emb_segment_kernel(const int32_t* a,
 // Block s finishes the id whose run began in an earlier segment and ends in segment s.
 __global__ void __launch_bounds__(kThreads) emb_finish_kernel(const int32_t* a, int na, const int32_t* b, int nb, half_t* __restrict__ gE,
                                                               int d, int vocab, const int32_t* __restrict__ start,
-                                                              const int32_t* __restrict__ perm, const float* __restrict__ part) {
+                                                              const int32_t* __restrict__ perm, const float* __restrict__ part,
+                                                              float scale) {
   const int e0 = blockIdx.x * kEmbSeg;
   const int v = id_at(a, na, b, perm[e0], vocab);
   const int g_begin = start[v], g_end = start[v + 1];
@@ -614,7 +616,7 @@ __global__ void __launch_bounds__(kThreads) emb_finish_kernel(const int32_t* a, 
 #pragma unroll
     for (int e = 0; e < 8; ++e) tot[e] += p[e];
   }
-  emb_add_to_row(gE, v, c, d, tot);
+  emb_add_to_row(gE, v, c, d, tot, scale);
 }
 
 __global__ void __launch_bounds__(kThreads) dropout_mask_kernel(uint8_t* keep, int rows, int n_cols, DropDev drop) {
@@ -745,7 +747,7 @@ int64_t layernorm_bwd_scratch_floats(int d) { return (int64_t)kLnBwdMaxBlocks * 
 int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const half_t* resid, const half_t* gamma,
                                   const float* stats, half_t* dy, half_t* dym, half_t* dgamma, half_t* dbeta,
                                   half_t* dbias, float* partial, int rows, int d, const DropDev& drop,
-                                  hipStream_t stream) {
+                                  hipStream_t stream, float vec_scale) {
   NMT_REQUIRE(rows > 0 && d >= 8 && d % 8 == 0 && d <= 2048, "layernorm_bwd: d=%d must be a multiple of 8 in [8, 2048]", d);
   NMT_REQUIRE(dout && sub && resid && gamma && stats && dy && partial, "layernorm_bwd: null pointer");
   NMT_REQUIRE(aligned16(dout) && aligned16(sub) && aligned16(resid) && aligned16(gamma) && aligned16(dy) && aligned16(dym),
@@ -762,14 +764,14 @@ int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const h
   }
   NMT_LAUNCH_CHECK();
   hipLaunchKernelGGL(finalize_partials_kernel, dim3(3 * ceil_div(d, 32)), dim3(kFinThreads), 0, stream, partial, nblk, 3, d,
-                     nch * 512, dgamma, dbeta, dbias);
+                     nch * 512, dgamma, dbeta, dbias, vec_scale);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 
 int64_t colsum_scratch_floats(int cols) { return (int64_t)kColsumMaxSplits * cols; }
 
-int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream) {
+int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream, float scale) {
   NMT_REQUIRE(rows > 0 && cols > 0 && cols % 8 == 0 && ld % 8 == 0 && ld >= cols, "colsum: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
   NMT_REQUIRE(src && dst && partial && aligned16(src), "colsum: null or misaligned pointer");
   const int cb = ceil_div(cols, 512);
@@ -780,7 +782,7 @@ int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int ro
   hipLaunchKernelGGL(colsum_kernel, dim3(cb, splits), dim3(kThreads), 0, stream, src, ld, partial, rows, cols);
   NMT_LAUNCH_CHECK();
   hipLaunchKernelGGL(finalize_partials_kernel, dim3(ceil_div(cols, 32)), dim3(kFinThreads), 0, stream, partial, splits, 1, cols,
-                     cols, dst, (half_t*)nullptr, (half_t*)nullptr);
+                     cols, dst, (half_t*)nullptr, (half_t*)nullptr, scale);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -836,7 +838,7 @@ int64_t embed_bwd_scratch_ints(int vocab, int rows_total, int d) { return emb_sc
 
 int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const DropDev& drop_a, const int32_t* ids_b,
                      const half_t* dx_b, int rows_b, const DropDev& drop_b, half_t* gE, int d, int vocab, int32_t* scratch,
-                     hipStream_t stream) {
+                     hipStream_t stream, float scale) {
   NMT_REQUIRE(rows_a >= 0 && rows_b >= 0 && rows_a + rows_b > 0, "embed_bwd: no rows");
   NMT_REQUIRE(d >= 8 && d % 8 == 0 && d / 8 <= kThreads && vocab > 0 && vocab <= 65536, "embed_bwd: bad d=%d or vocab=%d", d, vocab);
   NMT_REQUIRE((rows_a == 0 || (ids_a && dx_a && aligned16(dx_a))) && (rows_b == 0 || (ids_b && dx_b && aligned16(dx_b))) && gE &&
@@ -872,9 +874,9 @@ int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const
                      k2, perm);
   NMT_LAUNCH_CHECK();
   hipLaunchKernelGGL(emb_segment_kernel, dim3(e.nseg), dim3(kThreads), 0, stream, ids_a, dx_a, rows_a, drop_a, ids_b, dx_b, rows_b, drop_b, gE,
-                     d, vocab, start, perm, part);
+                     d, vocab, start, perm, part, scale);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(emb_finish_kernel, dim3(e.nseg), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, gE, d, vocab, start, perm, part);
+  hipLaunchKernelGGL(emb_finish_kernel, dim3(e.nseg), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, gE, d, vocab, start, perm, part, scale);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

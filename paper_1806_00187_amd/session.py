@@ -157,6 +157,10 @@ class Session:
         nmt.nmt_forward_loss(self.ctxs[pipe], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step, micro,
                              self.loss_sums[pipe], self.ntoks[pipe], sent_uid=dbatch.get("sent_uid"), training=training)
 
+    def grad_scale(self, pipe=0):
+        """Power-of-two factor the last forward call's pass applies to what it writes to g16."""
+        return nmt.nmt_grad_scale(self.ctxs[pipe])
+
     def backward(self, pipe=0):
         nmt.nmt_backward(self.ctxs[pipe])
 
