@@ -35,6 +35,7 @@ struct AttnArgs {
   int pad_id, causal, B, H, Tq, Tk;  // with a sentence table: Tq, Tk are the largest lengths in it
   const int4* tab;                   // per sentence (first query row, first key row, Tq, Tk), or nullptr
   int Nq;                            // query rows in total: lse is [H, Nq]
+  int fused_max;                     // backward: sentences with max(Tq, Tk) <= this are left to the fused kernel
 };
 
 // Rows and lengths of sentence b: from the table when several batches of different shapes are
@@ -87,10 +88,11 @@ struct Item {
   bool live;
 };
 __device__ __forceinline__ Item work_item(const AttnArgs& a) {
-  const int hg = (a.H + 3) >> 2;  // groups of four heads
+  const int wpb = blockDim.x >> 6;            // heads per work-group (one wavefront each)
+  const int hg = (a.H + wpb - 1) / wpb;
   Item it;
   it.b = blockIdx.x / hg;
-  it.h = (blockIdx.x % hg) * 4 + (threadIdx.x >> 6);
+  it.h = (blockIdx.x % hg) * wpb + (threadIdx.x >> 6);
   it.tile = blockIdx.y;
   it.live = it.h < a.H;
   return it;
@@ -242,7 +244,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
   if (!it.live) return;
   const Sent se = sentence(a, it.b);
   const int k0 = it.tile * 32;
-  if (k0 >= se.Tk) return;
+  if (k0 >= se.Tk || max(se.Tq, se.Tk) <= a.fused_max) return;
   const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
   unsigned char* mine = smem_raw + (threadIdx.x >> 6) * WAVE_LDS;
   half_t* Qs = reinterpret_cast<half_t*>(mine);
@@ -336,7 +338,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
   if (!it.live) return;
   const Sent se = sentence(a, it.b);
   const int q0 = it.tile * 32;
-  if (q0 >= se.Tq) return;
+  if (q0 >= se.Tq || max(se.Tq, se.Tk) <= a.fused_max) return;
   const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
   half_t* Ks = reinterpret_cast<half_t*>(smem_raw) + (threadIdx.x >> 6) * (32 * PR);
 
@@ -392,6 +394,146 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
   store_rows<DH>(Ks, dQt, 1.f, a.dQ + (size_t)se.q0 * a.lddq + h * DH, a.lddq, q0, se.Tq, lane);
 }
 
+// ------------------------------------------------------------------------------------------------
+// backward, fused: one wavefront owns a whole (sentence, head) whose queries and keys fit NT 32-row
+// tiles each, reads Q, K, V, O, dO once and writes dQ, dK, dV once.  Scores are formed with the key on
+// the lane (as in the dK/dV kernel); for dQ the dS tile is turned around through a small LDS tile
+// and the transposing read.
+// ------------------------------------------------------------------------------------------------
+constexpr int kDsPitch = 40;  // halfs per row of the 32 x 32 dS tile in LDS
+template <int DH, int NT>
+constexpr int fused_wave_lds() {
+  return (2 * NT + 1) * 32 * (DH + 8) * 2 + 32 * kDsPitch * 2 + 2 * 32 * NT * 4;  // Q and dO tiles, one K tile, dS, lse and D
+}
+template <int DH, int NT>
+__global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs a) {
+  constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, TILE = 32 * PR;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const Item it = work_item(a);
+  if (!it.live) return;
+  const Sent se = sentence(a, it.b);
+  const int tmax = max(se.Tq, se.Tk);
+  if (tmax > 32 * NT || tmax <= 32 * (NT - 1)) return;  // longer: other kernels; shorter: the instance with fewer tiles
+  const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
+  unsigned char* mine = smem_raw + (threadIdx.x >> 6) * fused_wave_lds<DH, NT>();
+  half_t* Qs = reinterpret_cast<half_t*>(mine);
+  half_t* dOs = Qs + NT * TILE;
+  half_t* Ks = dOs + NT * TILE;
+  half_t* dSs = Ks + TILE;
+  float* lse_s = reinterpret_cast<float*>(dSs + 32 * kDsPitch);
+  float* D_s = lse_s + 32 * NT;
+
+  const half_t* Qb = a.Q + (size_t)se.q0 * a.ldq + h * DH;
+  const half_t* dOb = a.dO + (size_t)se.q0 * a.lddo + h * DH;
+  const half_t* Ob = a.O + (size_t)se.q0 * a.ldo + h * DH;
+  const half_t* Kb = a.K + (size_t)se.k0 * a.ldk + h * DH;
+  const half_t* Vb = a.V + (size_t)se.k0 * a.ldv + h * DH;
+  const float* lse_b = a.lse + (size_t)h * a.Nq + se.q0;
+  const int nqt = (se.Tq + 31) >> 5, nkt = (se.Tk + 31) >> 5;
+
+  // queries: Q and dO tiles to LDS, D[q] = sum_dh dO[q,dh] * O[q,dh] and the log-sum-exp beside them
+#pragma unroll
+  for (int qt = 0; qt < NT; ++qt) {
+    if (qt < nqt) {
+      half8_t qf[KS], dof[KS], of[KS];
+      load_rows<DH>(Qb, a.ldq, qt * 32, se.Tq, lane, qf);
+      load_rows<DH>(dOb, a.lddo, qt * 32, se.Tq, lane, dof);
+      load_rows<DH>(Ob, a.ldo, qt * 32, se.Tq, lane, of);
+      const int ql = qt * 32 + (lane & 31);
+      const float lse_q = ql < se.Tq ? lse_b[ql] * kLog2e : 0.f;
+      float Dq = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)of[s][e];
+      Dq += __shfl_xor(Dq, 32, kWave);
+      put_rows<DH>(Qs + qt * TILE, lane, qf);
+      put_rows<DH>(dOs + qt * TILE, lane, dof);
+      if (g == 0) {
+        lse_s[ql] = lse_q;
+        D_s[ql] = Dq;
+      }
+    }
+  }
+  const float scale = rsqrtf((float)DH), sc = scale * kLog2e;
+  floatx16 dQt[NT][DT];
+#pragma unroll
+  for (int qt = 0; qt < NT; ++qt)
+#pragma unroll
+    for (int t = 0; t < DT; ++t) dQt[qt][t] = zero16();
+
+#pragma unroll
+  for (int kt = 0; kt < NT; ++kt) {
+    if (kt < nkt) {
+      const int k0 = kt * 32, key = k0 + (lane & 31);
+      const bool khid = key >= se.Tk || (a.key_ids && a.key_ids[se.k0 + key] == a.pad_id);
+      half8_t kf[KS], vf[KS];
+      load_rows<DH>(Kb, a.ldk, k0, se.Tk, lane, kf);
+      load_rows<DH>(Vb, a.ldv, k0, se.Tk, lane, vf);
+      wave_sync();  // whatever read the K tile before is done
+      put_rows<DH>(Ks, lane, kf);
+      floatx16 dKt[DT], dVt[DT];
+#pragma unroll
+      for (int t = 0; t < DT; ++t) {
+        dKt[t] = zero16();
+        dVt[t] = zero16();
+      }
+#pragma unroll
+      for (int qt = 0; qt < NT; ++qt) {
+        if (qt < nqt && !(a.causal && qt < kt)) {  // causal: earlier query tiles precede every key of this tile
+          wave_sync();  // Q, dO, K tiles and the row statistics are in LDS; the previous dS tile has been read
+          floatx16 s = zero16(), dp = zero16();
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const int off = qt * TILE + (lane & 31) * PR + ks * 16 + g * 8;
+            s = MFMA(ld_half8(Qs + off), kf[ks], s);
+            dp = MFMA(ld_half8(dOs + off), vf[ks], dp);
+          }
+          half8_t pf[2], dsf[2];
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const floatx4 l4 = *reinterpret_cast<const floatx4*>(lse_s + qt * 32 + 8 * rq + 4 * g);
+            const floatx4 d4 = *reinterpret_cast<const floatx4*>(D_s + qt * 32 + 8 * rq + 4 * g);
+            half4_t ds4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * rq + e;
+              const int qq = qt * 32 + 8 * rq + 4 * g + e;
+              const bool hid = khid || qq >= se.Tq || (a.causal && key > qq);
+              const float p = hid ? 0.f : exp2f(s[r] * sc - l4[e]);
+              pf[r >> 3][r & 7] = (half_t)p;
+              ds4[e] = (half_t)(p * (dp[r] - d4[e]) * scale);
+              dsf[r >> 3][r & 7] = ds4[e];
+            }
+            // dS[key][query]: this lane's key row, four consecutive queries
+            *reinterpret_cast<half4_t*>(dSs + (lane & 31) * kDsPitch + 8 * rq + 4 * g) = ds4;
+          }
+#pragma unroll
+          for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+              const int kb = 16 * s2 + 4 * g;
+              dVt[t] = MFMA(tr_frag<DH>(dOs + qt * TILE, PR, kb, t, lane), pf[s2], dVt[t]);
+              dKt[t] = MFMA(tr_frag<DH>(Qs + qt * TILE, PR, kb, t, lane), dsf[s2], dKt[t]);
+            }
+          wave_sync();  // the dS tile is complete
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const half8_t dst = tr_frag<32>(dSs, kDsPitch, 16 * s2 + 4 * g, 0, lane);  // lane = query, slots = keys
+#pragma unroll
+            for (int t = 0; t < DT; ++t) dQt[qt][t] = MFMA(tr_frag<DH>(Ks, PR, 16 * s2 + 4 * g, t, lane), dst, dQt[qt][t]);
+          }
+        }
+      }
+      store_rows<DH>(Ks, dKt, 1.f, a.dK + (size_t)se.k0 * a.lddk + h * DH, a.lddk, k0, se.Tk, lane);
+      store_rows<DH>(Ks, dVt, 1.f, a.dV + (size_t)se.k0 * a.lddv + h * DH, a.lddv, k0, se.Tk, lane);
+    }
+  }
+#pragma unroll
+  for (int qt = 0; qt < NT; ++qt)
+    if (qt < nqt) store_rows<DH>(Qs + qt * TILE, dQt[qt], 1.f, a.dQ + (size_t)se.q0 * a.lddq + h * DH, a.lddq, qt * 32, se.Tq, lane);
+}
+
 template <int DH>
 constexpr size_t tile_smem() { return (size_t)4 * 32 * (DH + 8) * sizeof(half_t); }   // one 32-row tile per wavefront
 template <int DH>
@@ -411,8 +553,26 @@ int fwd_launch(const AttnArgs& a, hipStream_t stream) {
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
+template <int DH, int NT>
+int fused_launch(const AttnArgs& a, hipStream_t stream) {
+  constexpr int kWaves = NT == 1 ? 4 : 2;   // wavefronts (heads) per work-group: bounded by LDS
+  const size_t smem = (size_t)kWaves * fused_wave_lds<DH, NT>();
+  if (int rc = allow_big_lds(attn_bwd_fused_kernel<DH, NT>, smem)) return rc;
+  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3(a.B * ((a.H + kWaves - 1) / kWaves)), dim3(64 * kWaves), smem, stream, a);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
 template <int DH>
-int bwd_launch(const AttnArgs& a, hipStream_t stream) {
+int bwd_launch(const AttnArgs& a0, hipStream_t stream) {
+  AttnArgs a = a0;
+  const int tmax = a.Tq > a.Tk ? a.Tq : a.Tk;
+  // sentences of up to 64 positions on both sides: everything in one kernel, one wavefront per (sentence, head)
+  a.fused_max = 64;
+  if (int rc = fused_launch<DH, 1>(a, stream)) return rc;
+  if (tmax > 32)
+    if (int rc = fused_launch<DH, 2>(a, stream)) return rc;
+  if (tmax <= a.fused_max) return NMT_OK;
+  // longer ones: a wavefront per 32 queries for dQ, a wavefront per 32 keys for dK and dV
   if (int rc = allow_big_lds(attn_bwd_dkv_kernel<DH>, dkv_smem<DH>())) return rc;
   const int groups = a.B * ((a.H + 3) / 4);
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3(groups, ceil_div(a.Tq, 32)), dim3(kThreads), tile_smem<DH>(), stream, a);
