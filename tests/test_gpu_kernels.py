@@ -34,7 +34,8 @@ def test_dropout_mask_bit_exact(p, n_pos, n_cols, B):
 # ---- GEMM -------------------------------------------------------------------------------------
 GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (37, 1000, 64), (515, 264, 200), (3003, 1024, 1024), (256, 3072, 1024),
                (1, 8, 8), (130, 64, 4096), (136, 264, 3003),
-               (4088, 3080, 200)]   # enough 256 x 256 tiles for the large-tile kernel, ragged on every side
+               (4088, 3080, 200),   # enough 256 x 256 tiles for the large-tile kernel, ragged on every side
+               (10240, 3328, 200), (25600, 2568, 72)]   # more tiles than compute units: resident work-groups walk over 2 and 4 tiles
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
