@@ -396,3 +396,33 @@ def test_packed_entry_point_clamps_inconsistent_lengths_and_rejects_bad_totals()
             assert e.value.code == A.NMT_EINVAL
     finally:
         sess.close()
+
+
+def test_forward_only_validation_loss_matches_oracle():
+    """Validation NLL (no dropout, no backward): token-level loss in nats from the library against the
+    oracle, for a padded sub-batch, the packed pass and a second call after a training call (the
+    training flag of one call must not leak into the next)."""
+    model = dict(I.MODELS["tiny"], dropout=0.3)
+    weights = I.init_weights(seed=4, perturb=0.05, **model)
+    batches = [I.tiny_batch(seed=41 + i, B=6, S=12 + i, T=11, vocab=model["vocab"], short_by=3) for i in range(2)]
+    cfg = _oracle_cfg(model, seed=0)
+    P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    ref = [O.forward_loss(P16, cfg, b["src"], b["tgt_in"], b["tgt_out"], training=False)[:2] for b in batches]
+    sess = Session(model, weights, max_sentences=8)
+    try:
+        for b, (loss_ref, ntok_ref) in zip(batches, ref):
+            sess.forward_loss(sess.to_device(b), 1.0, 1, 0, training=True)     # a training call in between
+            sess.forward_loss(sess.to_device(b), 1.0, 1, 0, training=False)
+            assert int(sess.ntok.item()) == ntok_ref
+            assert abs(float(sess.loss_sum.item()) - loss_ref) / loss_ref <= LOSS_TOL
+        (pk,) = sess.pack(batches)
+        sess.forward_loss(pk, 1.0, 1, training=False)
+        loss_ref, ntok_ref = sum(r[0] for r in ref), sum(r[1] for r in ref)
+        assert int(sess.ntok.item()) == ntok_ref
+        loss = float(sess.loss_sum.item())
+        assert abs(loss - loss_ref) / loss_ref <= LOSS_TOL
+        # perplexity as the paper reports it: 2 ** (NLL in bits per token)
+        bits = loss / ntok_ref / np.log(2.0)
+        assert abs(2.0 ** bits - np.exp(loss_ref / ntok_ref)) / np.exp(loss_ref / ntok_ref) <= 2e-3
+    finally:
+        sess.close()
