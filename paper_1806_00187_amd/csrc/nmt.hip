@@ -270,7 +270,7 @@ extern "C" int nmt_create(const nmt_config* cfg, nmt_ctx** out) {
   NMT_REQUIRE(cfg->label_smoothing >= 0.f && cfg->label_smoothing < 1.f, "nmt_create: label_smoothing outside [0, 1)");
   NMT_REQUIRE(cfg->ln_eps > 0.f, "nmt_create: ln_eps must be positive");
   NMT_REQUIRE(cfg->max_sentences >= 1 && cfg->max_len >= 1 && cfg->max_len <= 1024, "nmt_create: max_sentences >= 1 and 1 <= max_len <= 1024 required");
-  NMT_REQUIRE((int64_t)cfg->max_sentences * cfg->n_heads <= 65535, "nmt_create: max_sentences * n_heads exceeds 65535");
+  NMT_REQUIRE(cfg->max_sentences <= (1 << 20), "nmt_create: max_sentences above 2^20");
   nmt_ctx* c = new (std::nothrow) nmt_ctx();
   NMT_REQUIRE(c, "nmt_create: out of host memory");
   c->cfg = *cfg;
