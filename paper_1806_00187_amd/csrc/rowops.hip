@@ -124,11 +124,11 @@ __global__ void __launch_bounds__(kThreads) res_ln_fwd_kernel(const half_t* __re
   }
 }
 
-// Backward.  Each wavefront walks pairs of rows (two rows in flight hide the load latency), keeps
+// Backward.  Each wavefront walks groups of four rows (four rows in flight hide the load latency), keeps
 // per-lane column sums for dgamma, dbeta and the bias gradient in registers, and the block writes
 // one partial row per quantity (pitch NCH*512 floats, column-indexed).
 constexpr int kLnBwdMaxBlocks = 512;
-constexpr int kLnRows = 2;
+constexpr int kLnRows = 4;
 
 template <int NCH>
 __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __restrict__ dout, const half_t* __restrict__ sub,
