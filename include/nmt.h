@@ -11,7 +11,8 @@
  *    the message of the last failure on the calling thread.  No C++ exception crosses the ABI.
  *  - Pointers named d_* (and all buffers handed to nmt_bind) are DEVICE pointers owned by the
  *    caller; they must stay valid until the work enqueued on them has finished.  The library
- *    never allocates or frees device memory.  Host pointers are marked "host".
+ *    never allocates or frees device memory (nmt_backward creates one extra stream and four
+ *    events per context on first use).  Host pointers are marked "host".
  *  - `stream` is a hipStream_t passed as void*; all kernels are enqueued on it and no function
  *    synchronises unless it says so.
  *  - fp16 buffers are IEEE binary16 (passed as void*).  Matrices are row-major.
@@ -46,7 +47,7 @@ typedef struct {
   float label_smoothing;          /* weight of the uniform prior over the vocabulary       */
   float ln_eps;                   /* variance floor of layer normalisation                 */
   uint64_t seed;                  /* Philox key of the dropout streams                     */
-  int32_t max_sentences, max_len; /* limits for B and for S, T (max_len <= 1024)           */
+  int32_t max_sentences, max_len; /* limits for B (<= 2^20) and for S, T (<= 1024)        */
 } nmt_config;
 
 const char* nmt_last_error(void);
