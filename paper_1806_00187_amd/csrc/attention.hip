@@ -555,7 +555,7 @@ int fwd_launch(const AttnArgs& a, hipStream_t stream) {
 }
 template <int DH, int NT>
 int fused_launch(const AttnArgs& a, hipStream_t stream) {
-  constexpr int kWaves = NT == 1 ? 4 : 2;   // wavefronts (heads) per work-group: bounded by LDS
+  constexpr int kWaves = NT == 1 ? 4 : (NT == 2 ? 2 : 1);   // wavefronts (heads) per work-group: bounded by LDS
   const size_t smem = (size_t)kWaves * fused_wave_lds<DH, NT>();
   if (int rc = allow_big_lds(attn_bwd_fused_kernel<DH, NT>, smem)) return rc;
   hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3(a.B * ((a.H + kWaves - 1) / kWaves)), dim3(64 * kWaves), smem, stream, a);
@@ -566,11 +566,18 @@ template <int DH>
 int bwd_launch(const AttnArgs& a0, hipStream_t stream) {
   AttnArgs a = a0;
   const int tmax = a.Tq > a.Tk ? a.Tq : a.Tk;
-  // sentences of up to 64 positions on both sides: everything in one kernel, one wavefront per (sentence, head)
-  a.fused_max = 64;
+  // sentences of up to 128 positions on both sides (64 for the largest head size, whose accumulators would not
+  // fit the register file): everything in one kernel, one wavefront per (sentence, head)
+  a.fused_max = DH <= 64 ? 128 : 64;
   if (int rc = fused_launch<DH, 1>(a, stream)) return rc;
   if (tmax > 32)
     if (int rc = fused_launch<DH, 2>(a, stream)) return rc;
+  if constexpr (DH <= 64) {
+    if (tmax > 64)
+      if (int rc = fused_launch<DH, 3>(a, stream)) return rc;
+    if (tmax > 96)
+      if (int rc = fused_launch<DH, 4>(a, stream)) return rc;
+  }
   if (tmax <= a.fused_max) return NMT_OK;
   // longer ones: a wavefront per 32 queries for dQ, a wavefront per 32 keys for dK and dV
   if (int rc = allow_big_lds(attn_bwd_dkv_kernel<DH>, dkv_smem<DH>())) return rc;

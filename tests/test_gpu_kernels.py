@@ -139,7 +139,8 @@ def test_gemm_strided_operands_and_rejections():
 ATTN_CASES = [  # B, H, dh, Tq, Tk, causal
     (2, 4, 16, 16, 16, 1), (3, 2, 64, 33, 36, 0), (2, 2, 64, 45, 45, 1), (1, 2, 64, 256, 256, 1), (2, 1, 64, 130, 200, 0),
     (5, 3, 32, 7, 9, 0), (2, 2, 128, 40, 40, 1), (4, 2, 64, 1, 1, 1), (2, 2, 16, 100, 70, 0),
-    (3, 5, 64, 20, 50, 0), (2, 3, 32, 64, 10, 0), (2, 2, 64, 64, 64, 1)]
+    (3, 5, 64, 20, 50, 0), (2, 3, 32, 64, 10, 0), (2, 2, 64, 64, 64, 1), (2, 2, 64, 100, 120, 0), (2, 2, 64, 96, 96, 1),
+    (1, 2, 128, 70, 90, 0)]
 
 
 def _attn_inputs(B, H, dh, Tq, Tk, causal, seed):
