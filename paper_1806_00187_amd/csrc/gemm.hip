@@ -233,13 +233,17 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // Work-group -> tile.  Consecutive work-group ids go round-robin over the 8 XCDs; undo that so
-  // each XCD (own L2) gets a contiguous run of tiles.
-  int pid = blockIdx.x;
+  // Work-group -> (k-split, tile).  Consecutive work-group ids go round-robin over the 8 XCDs; undo
+  // that so each XCD (own L2) gets a contiguous run of tiles of as few k-splits as possible: the
+  // tiles of one split read the same k-range of A and B and share those panels in L2.
+  int pid, split;
   {
-    const int nt = g.tiles_m * g.tiles_n, xcd = pid & 7, idx = pid >> 3;
-    const int base = nt >> 3, rem = nt & 7;
-    pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+    const int nt = g.tiles_m * g.tiles_n, total = nt * (int)gridDim.y;
+    const int lin = (int)blockIdx.x + (int)blockIdx.y * nt, xcd = lin & 7, idx = lin >> 3;
+    const int base = total >> 3, rem = total & 7;
+    const int at = xcd * base + (xcd < rem ? xcd : rem) + idx;
+    split = at / nt;
+    pid = at - split * nt;
   }
   // Grouped order: 8 tile rows are swept column by column, so the work-groups an XCD runs at a
   // time form a patch of tiles and each A / B panel they stream is shared by several of them in L2.
@@ -269,7 +273,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   const typename OpA::Frag fa = OpA::frag_init(wm * WM, lane);
   const typename OpB::Frag fb = OpB::frag_init(wn * WN, lane);
 
-  const int k_base = g.partial ? (int)blockIdx.y * g.k_chunk : 0;
+  const int k_base = g.partial ? split * g.k_chunk : 0;
   const int k_end = g.partial ? min(g.K, k_base + g.k_chunk) : g.K;
   auto request = [&](unsigned char* stage, int k0) {  // asynchronous: tile k0 streams into `stage`
     const int kleft = k_end - k0;
@@ -385,7 +389,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
           const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + rl * SW + swz(rl, 2 * c8) * 4);
           const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + rl * SW + swz(rl, 2 * c8 + 1) * 4);
           if (g.partial) {
-            float* dst = g.partial + ((size_t)blockIdx.y * g.M + gr) * g.N + gc;
+            float* dst = g.partial + ((size_t)split * g.M + gr) * g.N + gc;
             *reinterpret_cast<floatx4*>(dst) = lo;
             *reinterpret_cast<floatx4*>(dst + 4) = hi;
             continue;
