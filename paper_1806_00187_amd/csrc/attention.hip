@@ -17,6 +17,7 @@
 // straight from registers: the contraction index may be permuted freely as long as both operands
 // use the same permutation, so slot j of k-step s2 stands for row 16*s2 + 8*(j/4) + 4*(l/32) + j%4.
 #include <math.h>
+#include <stdlib.h>
 
 #include "common.h"
 
@@ -36,6 +37,10 @@ struct AttnArgs {
   const int4* tab;                   // per sentence (first query row, first key row, Tq, Tk), or nullptr
   int Nq;                            // query rows in total: lse is [H, Nq]
   int fused_max;                     // backward: sentences with max(Tq, Tk) <= this are left to the fused kernel
+  // work lists over the table (or nullptr: every (sentence, tile) of the grid is looked at)
+  const int32_t* wl_counts;          // [0..3] sentences by tiles of the longer side, [4] longer ones, [5] query tiles
+  const int32_t* wl_sent;            // [4][B] sentence indices by class
+  const int2* wl_qtiles;             // (sentence, query tile)
 };
 
 // Rows and lengths of sentence b: from the table when several batches of different shapes are
@@ -87,7 +92,10 @@ struct Item {
   int b, h, tile;
   bool live;
 };
-__device__ __forceinline__ Item work_item(const AttnArgs& a) {
+// LIST 0: the grid enumerates (sentence, tile); 1: entry blockIdx.x / hg of the query-tile list;
+// 2: entry blockIdx.x / hg of the list of sentences of class `cls` (tile = 0).
+template <int LIST>
+__device__ __forceinline__ Item work_item(const AttnArgs& a, int cls = 0) {
   const int wpb = blockDim.x >> 6;            // heads per work-group (one wavefront each)
   const int hg = (a.H + wpb - 1) / wpb;
   Item it;
@@ -95,6 +103,16 @@ __device__ __forceinline__ Item work_item(const AttnArgs& a) {
   it.h = (blockIdx.x % hg) * wpb + (threadIdx.x >> 6);
   it.tile = blockIdx.y;
   it.live = it.h < a.H;
+  if (LIST == 1 && a.wl_qtiles) {
+    it.live = it.live && it.b < a.wl_counts[5];
+    const int2 e = it.live ? a.wl_qtiles[it.b] : make_int2(0, 0);
+    it.b = e.x;
+    it.tile = e.y;
+  }
+  if (LIST == 2 && a.wl_sent) {
+    it.live = it.live && it.b < a.wl_counts[cls];
+    it.b = it.live ? a.wl_sent[(size_t)cls * a.B + it.b] : 0;
+  }
   return it;
 }
 
@@ -164,7 +182,7 @@ template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item(a);
+  const Item it = work_item<1>(a);
   if (!it.live) return;
   const Sent se = sentence(a, it.b);
   const int q0 = it.tile * 32;
@@ -240,7 +258,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   constexpr int WAVE_LDS = 2 * 32 * PR * 2 + 2 * 32 * 4;  // Q and dO tiles, lse and D of the tile's queries
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item(a);
+  const Item it = work_item<0>(a);
   if (!it.live) return;
   const Sent se = sentence(a, it.b);
   const int k0 = it.tile * 32;
@@ -334,7 +352,7 @@ template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item(a);
+  const Item it = work_item<0>(a);
   if (!it.live) return;
   const Sent se = sentence(a, it.b);
   const int q0 = it.tile * 32;
@@ -409,7 +427,7 @@ template <int DH, int NT>
 __global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, TILE = 32 * PR;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item(a);
+  const Item it = work_item<2>(a, NT - 1);
   if (!it.live) return;
   const Sent se = sentence(a, it.b);
   const int tmax = max(se.Tq, se.Tk);
@@ -546,37 +564,59 @@ int allow_big_lds(Kern kern, size_t bytes) {
   return NMT_OK;
 }
 
+// Upper bounds of the list lengths, from what the host knows (the lists themselves are made on the device).
+// Query tiles: sum_b ceil(Tq_b / 32) <= (sum_b Tq_b) / 32 + B, and sum_b Tq_b <= Nq + B (a table made from
+// lengths that exceed the host's totals cuts sentences down to one row, which they may share).
+int64_t qtile_capacity(int n_sent, int n_q_rows) { return ((int64_t)n_q_rows + n_sent) / 32 + n_sent + 1; }
+int64_t qtile_bound(int n_sent, int n_q_rows, int max_tq) {
+  const int64_t a = (int64_t)n_sent * ceil_div(max_tq, 32), b = qtile_capacity(n_sent, n_q_rows);
+  return a < b ? a : b;
+}
+// Sentences whose longer side has more than 32 c positions: each takes that many of the Nq query rows or of
+// the Nk key rows (n_k_rows == 0: self-attention, the keys are the queries' rows).
+int64_t class_bound(int n_sent, int n_q_rows, int n_k_rows, int c) {
+  if (c == 0) return n_sent;
+  const int64_t b = n_q_rows / (32 * c + 1) + n_k_rows / (32 * c + 1);
+  return b < n_sent ? b : n_sent;
+}
+
 template <int DH>
 int fwd_launch(const AttnArgs& a, hipStream_t stream) {
-  const dim3 grid(a.B * ((a.H + 3) / 4), ceil_div(a.Tq, 32));
+  dim3 grid(a.B * ((a.H + 3) / 4), ceil_div(a.Tq, 32));
+  if (a.wl_qtiles) grid = dim3((unsigned)(qtile_bound(a.B, a.Nq, a.Tq) * ((a.H + 3) / 4)), 1);
   hipLaunchKernelGGL(attn_fwd_kernel<DH>, grid, dim3(kThreads), tile_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 template <int DH, int NT>
-int fused_launch(const AttnArgs& a, hipStream_t stream) {
+int fused_launch(const AttnArgs& a, int n_k_rows, hipStream_t stream) {
   constexpr int kWaves = NT == 1 ? 4 : (NT == 2 ? 2 : 1);   // wavefronts (heads) per work-group: bounded by LDS
   const size_t smem = (size_t)kWaves * fused_wave_lds<DH, NT>();
   if (int rc = allow_big_lds(attn_bwd_fused_kernel<DH, NT>, smem)) return rc;
-  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3(a.B * ((a.H + kWaves - 1) / kWaves)), dim3(64 * kWaves), smem, stream, a);
+  const int64_t n = a.wl_sent ? class_bound(a.B, a.Nq, n_k_rows, NT - 1) : a.B;
+  if (n == 0) return NMT_OK;
+  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3((unsigned)(n * ((a.H + kWaves - 1) / kWaves))), dim3(64 * kWaves), smem, stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
 template <int DH>
-int bwd_launch(const AttnArgs& a0, hipStream_t stream) {
+int bwd_launch(const AttnArgs& a0, int n_k_rows, hipStream_t stream) {
   AttnArgs a = a0;
-  const int tmax = a.Tq > a.Tk ? a.Tq : a.Tk;
+  const int tmax = a.Tq > a.Tk ? a.Tq : a.Tk, nt_max = ceil_div(tmax, 32);
   // sentences of up to 128 positions on both sides (64 for the largest head size, whose accumulators would not
-  // fit the register file): everything in one kernel, one wavefront per (sentence, head)
+  // fit the register file): everything in one kernel, one wavefront per (sentence, head).  One instance per
+  // number of 32-position tiles; without a table all sentences have the same lengths and need just one.
   a.fused_max = DH <= 64 ? 128 : 64;
-  if (int rc = fused_launch<DH, 1>(a, stream)) return rc;
-  if (tmax > 32)
-    if (int rc = fused_launch<DH, 2>(a, stream)) return rc;
+  auto wanted = [&](int nt) { return nt <= nt_max && (a.tab || nt == nt_max); };
+  if (wanted(1))
+    if (int rc = fused_launch<DH, 1>(a, n_k_rows, stream)) return rc;
+  if (wanted(2))
+    if (int rc = fused_launch<DH, 2>(a, n_k_rows, stream)) return rc;
   if constexpr (DH <= 64) {
-    if (tmax > 64)
-      if (int rc = fused_launch<DH, 3>(a, stream)) return rc;
-    if (tmax > 96)
-      if (int rc = fused_launch<DH, 4>(a, stream)) return rc;
+    if (wanted(3))
+      if (int rc = fused_launch<DH, 3>(a, n_k_rows, stream)) return rc;
+    if (wanted(4))
+      if (int rc = fused_launch<DH, 4>(a, n_k_rows, stream)) return rc;
   }
   if (tmax <= a.fused_max) return NMT_OK;
   // longer ones: a wavefront per 32 queries for dQ, a wavefront per 32 keys for dK and dV
@@ -604,9 +644,10 @@ int check_common(const AttnArgs& a, int dh) {
 
 int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O, int ldo,
                          float* lse, const int32_t* key_ids, int pad_id, int causal, int B, int H, int dh, int Tq, int Tk,
-                         const int4* sent_tab, int n_q_rows, hipStream_t stream) {
+                         const int4* sent_tab, int n_q_rows, const AttnWork* work, hipStream_t stream) {
   AttnArgs a = {};
   a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
+  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qtiles = work->qtiles; }
   a.Q = Q; a.K = K; a.V = V; a.Out = O; a.lse = lse; a.key_ids = key_ids;
   a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.ldo = ldo;
   a.pad_id = pad_id; a.causal = causal; a.B = B; a.H = H; a.Tq = Tq; a.Tk = Tk;
@@ -625,9 +666,11 @@ int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
 int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, const half_t* O, int ldo,
                          const half_t* dO, int lddo, const float* lse, half_t* dQ, int lddq, half_t* dK, int lddk, half_t* dV,
                          int lddv, const int32_t* key_ids, int pad_id, int causal, int B, int H, int dh, int Tq, int Tk,
-                         const int4* sent_tab, int n_q_rows, hipStream_t stream) {
+                         const int4* sent_tab, int n_q_rows, const AttnWork* work, hipStream_t stream) {
   AttnArgs a = {};
   a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
+  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qtiles = work->qtiles; }
+  const int n_k_rows = work ? work->n_k_rows : 0;
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.lse = const_cast<float*>(lse); a.key_ids = key_ids;
   a.dQ = dQ; a.dK = dK; a.dV = dV;
   a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.ldo = ldo; a.lddo = lddo; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;
@@ -639,9 +682,80 @@ int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
   NMT_REQUIRE(aligned16(O) && aligned16(dO) && aligned16(dQ) && aligned16(dK) && aligned16(dV), "attention_bwd: misaligned pointer");
   NMT_REQUIRE(!causal || Tq == Tk, "attention_bwd: the causal mask needs Tq == Tk");
   switch (dh) {
-    case 16: return bwd_launch<16>(a, stream);
-    case 32: return bwd_launch<32>(a, stream);
-    case 64: return bwd_launch<64>(a, stream);
-    default: return bwd_launch<128>(a, stream);
+    case 16: return bwd_launch<16>(a, n_k_rows, stream);
+    case 32: return bwd_launch<32>(a, n_k_rows, stream);
+    case 64: return bwd_launch<64>(a, n_k_rows, stream);
+    default: return bwd_launch<128>(a, n_k_rows, stream);
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Work lists of one attention kind over a sentence table.  One block; thread t takes a contiguous run of
+// sentences, so every list is in sentence order (and so the same from run to run).
+// storage: [0..7] counts, then [4][n_sent] sentences by class, then bound_q (sentence, tile) pairs.
+// ------------------------------------------------------------------------------------------------
+namespace {
+__global__ void __launch_bounds__(1024) attn_worklists_kernel(const int4* __restrict__ tab, int n_sent, int bound_q,
+                                                              int32_t* __restrict__ st) {
+  __shared__ int sh[6][1024];
+  const int t = threadIdx.x, per = (n_sent + 1023) / 1024;
+  const int lo = min(n_sent, t * per), hi = min(n_sent, lo + per);
+  int cnt[6] = {0, 0, 0, 0, 0, 0};
+  for (int i = lo; i < hi; ++i) {
+    const int4 e = tab[i];
+    const int nt = max(1, (max(e.z, e.w) + 31) >> 5);
+    ++cnt[nt <= 4 ? nt - 1 : 4];
+    cnt[5] += (e.z + 31) >> 5;
+  }
+#pragma unroll
+  for (int c = 0; c < 6; ++c) sh[c][t] = cnt[c];
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int v[6];
+#pragma unroll
+    for (int c = 0; c < 6; ++c) v[c] = t >= o ? sh[c][t - o] : 0;
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 6; ++c) sh[c][t] += v[c];
+    __syncthreads();
+  }
+  int at[6];
+#pragma unroll
+  for (int c = 0; c < 6; ++c) at[c] = sh[c][t] - cnt[c];
+  int32_t* by_tiles = st + 8;
+  int2* qtiles = reinterpret_cast<int2*>(st + 8 + 4 * (size_t)n_sent);
+  for (int i = lo; i < hi; ++i) {
+    const int4 e = tab[i];
+    const int nt = max(1, (max(e.z, e.w) + 31) >> 5);
+    if (nt <= 4) by_tiles[(size_t)(nt - 1) * n_sent + at[nt - 1]++] = i;
+    for (int q = 0; q < (e.z + 31) >> 5; ++q, ++at[5])
+      if (at[5] < bound_q) qtiles[at[5]] = make_int2(i, q);
+  }
+  if (t == 1023) {
+#pragma unroll
+    for (int c = 0; c < 5; ++c) st[c] = sh[c][1023];
+    st[5] = min(sh[5][1023], bound_q);
+  }
+}
+}  // namespace
+
+int64_t attention_worklist_ints(int n_sent, int n_q_rows) {
+  return 8 + 4 * (int64_t)n_sent + 2 * qtile_capacity(n_sent, n_q_rows);
+}
+
+AttnWork attention_work(const int32_t* storage, int n_sent, int n_k_rows) {
+  AttnWork w;
+  w.counts = storage;
+  w.by_tiles = storage + 8;
+  w.qtiles = reinterpret_cast<const int2*>(storage + 8 + 4 * (size_t)n_sent);
+  w.n_k_rows = n_k_rows;
+  return w;
+}
+
+int launch_attention_worklists(const int4* tab, int n_sent, int n_q_rows, int32_t* storage, hipStream_t stream) {
+  NMT_REQUIRE(tab && storage && n_sent > 0 && n_q_rows > 0, "attention work lists: null pointer or empty table");
+  NMT_REQUIRE((reinterpret_cast<uintptr_t>(storage) & 7u) == 0, "attention work lists: storage must be 8-byte aligned");
+  hipLaunchKernelGGL(attn_worklists_kernel, dim3(1), dim3(1024), 0, stream, tab, n_sent, (int)qtile_capacity(n_sent, n_q_rows), storage);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
 }

@@ -141,14 +141,29 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
                 int M, int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial = nullptr,
                 int64_t partial_floats = 0, int splits = 1);
 
+// Work lists of one attention kind over a sentence table, made on the device (launch_attention_worklists)
+// so that the attention kernels start no work-group for a (sentence, tile) that does not exist:
+// counts[c], c = 0..3: sentences whose longer side takes c + 1 tiles of 32 positions, [4]: longer ones,
+// [5]: query tiles; by_tiles [4][n_sent]: the sentences of each class; qtiles: (sentence, query tile).
+struct AttnWork {
+  const int32_t* counts = nullptr;
+  const int32_t* by_tiles = nullptr;
+  const int2* qtiles = nullptr;
+  int n_k_rows = 0;  // key rows in total; 0 for self-attention (the keys are the queries' rows)
+};
+int64_t attention_worklist_ints(int n_sent, int n_q_rows);  // int32 words of storage behind one AttnWork
+AttnWork attention_work(const int32_t* storage, int n_sent, int n_k_rows);
+int launch_attention_worklists(const int4* tab, int n_sent, int n_q_rows, int32_t* storage, hipStream_t stream);
+
 int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O,
                          int ldo, float* lse, const int32_t* key_ids, int pad_id, int causal, int B, int H,
-                         int dh, int Tq, int Tk, const int4* sent_tab, int n_q_rows, hipStream_t stream);
+                         int dh, int Tq, int Tk, const int4* sent_tab, int n_q_rows, const AttnWork* work,
+                         hipStream_t stream);
 int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv,
                          const half_t* O, int ldo, const half_t* dO, int lddo, const float* lse, half_t* dQ,
                          int lddq, half_t* dK, int lddk, half_t* dV, int lddv, const int32_t* key_ids, int pad_id,
                          int causal, int B, int H, int dh, int Tq, int Tk, const int4* sent_tab, int n_q_rows,
-                         hipStream_t stream);
+                         const AttnWork* work, hipStream_t stream);
 
 int launch_residual_layernorm_fwd(const half_t* sub, const half_t* resid, const half_t* gamma, const half_t* beta,
                                   half_t* out, float* stats, int rows, int d, float eps, const DropDev& drop,

@@ -72,6 +72,7 @@ struct EncW { int64_t qkv, o, s1, x1, h, s2, x2, lse, st1, st2; };
 struct DecW { int64_t qkv, o1, s1, x1, lse1, q, kv, o2, s2, x2, lse2, h, s3, x3, st1, st2, st3; };
 struct Plan {
   int64_t rk_src, rk_tgt, tab_ss, tab_tt, tab_ts;  // row keys (dropout, positions) and per-sentence attention tables
+  int64_t wl_ss, wl_tt, wl_ts;                     // attention work lists over those tables
   int64_t sent_rows;                                // first source / target row of every sentence (packed batches)
   int64_t x0, y0, logits, rowloss;
   std::vector<EncW> enc;
@@ -164,6 +165,9 @@ int64_t plan_workspace(const nmt_ctx* c, const GroupDims& gd, Plan& p) {
   p.tab_ss = take(B * (int64_t)sizeof(int4));
   p.tab_tt = take(B * (int64_t)sizeof(int4));
   p.tab_ts = take(B * (int64_t)sizeof(int4));
+  p.wl_ss = take(attention_worklist_ints((int)B, (int)Ns) * (int64_t)sizeof(int32_t));
+  p.wl_tt = take(attention_worklist_ints((int)B, (int)Nt) * (int64_t)sizeof(int32_t));
+  p.wl_ts = take(attention_worklist_ints((int)B, (int)Nt) * (int64_t)sizeof(int32_t));
   p.sent_rows = take(2 * B * (int64_t)sizeof(int32_t));
   p.x0 = take(Ns * d * h2);
   p.y0 = take(Nt * d * h2);
@@ -515,6 +519,11 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
     NMT_TRY(launch_build_tables(sl, Bt, tsrc.uid, r.ws<uint2>(p.rk_src), r.ws<uint2>(p.rk_tgt), r.ws<int4>(p.tab_ss),
                                 r.ws<int4>(p.tab_tt), r.ws<int4>(p.tab_ts), st));
   }
+  NMT_TRY(launch_attention_worklists(tab_ss, Bt, Ns, r.ws<int32_t>(p.wl_ss), st));
+  NMT_TRY(launch_attention_worklists(tab_tt, Bt, Nt, r.ws<int32_t>(p.wl_tt), st));
+  NMT_TRY(launch_attention_worklists(tab_ts, Bt, Nt, r.ws<int32_t>(p.wl_ts), st));
+  const AttnWork wl_ss = attention_work(r.ws<int32_t>(p.wl_ss), Bt, 0), wl_tt = attention_work(r.ws<int32_t>(p.wl_tt), Bt, 0),
+                 wl_ts = attention_work(r.ws<int32_t>(p.wl_ts), Bt, Ns);
 
   // ---- encoder ----
   half_t* x = r.ws<half_t>(p.x0);
@@ -525,7 +534,7 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
     half_t* qkv = r.ws<half_t>(W.qkv);
     NMT_TRY(r.linear(x, Ns, d, P.attn.wqkv, P.attn.bqkv, 3 * d, qkv));
     NMT_TRY(launch_attention_fwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, r.ws<half_t>(W.o), d, r.ws<float>(W.lse), d_src,
-                                 k.pad_id, 0, Bt, H, dh, maxS, maxS, tab_ss, Ns, st));
+                                 k.pad_id, 0, Bt, H, dh, maxS, maxS, tab_ss, Ns, &wl_ss, st));
     NMT_TRY(r.linear(r.ws<half_t>(W.o), Ns, d, P.attn.wo, P.attn.bo, d, r.ws<half_t>(W.s1)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s1), x, r.w(P.ln1.g), r.w(P.ln1.b), r.ws<half_t>(W.x1), r.ws<float>(W.st1),
                                           Ns, d, k.ln_eps, r.drop(layer_site(l, kKindSelfRes), false, k.dropout), st));
@@ -550,7 +559,7 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
     half_t* qkv = r.ws<half_t>(W.qkv);
     NMT_TRY(r.linear(y, Nt, d, P.self.wqkv, P.self.bqkv, 3 * d, qkv));
     NMT_TRY(launch_attention_fwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, r.ws<half_t>(W.o1), d, r.ws<float>(W.lse1), d_tgt_in,
-                                 k.pad_id, 1, Bt, H, dh, maxT, maxT, tab_tt, Nt, st));
+                                 k.pad_id, 1, Bt, H, dh, maxT, maxT, tab_tt, Nt, &wl_tt, st));
     NMT_TRY(r.linear(r.ws<half_t>(W.o1), Nt, d, P.self.wo, P.self.bo, d, r.ws<half_t>(W.s1)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s1), y, r.w(P.ln1.g), r.w(P.ln1.b), r.ws<half_t>(W.x1), r.ws<float>(W.st1),
                                           Nt, d, k.ln_eps, r.drop(layer_site(li, kKindSelfRes), true, k.dropout), st));
@@ -558,7 +567,7 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
     NMT_TRY(r.linear(r.ws<half_t>(W.x1), Nt, d, P.cross.wq, P.cross.bq, d, r.ws<half_t>(W.q)));
     NMT_TRY(r.linear(enc_out, Ns, d, P.cross.wkv, P.cross.bkv, 2 * d, kv));
     NMT_TRY(launch_attention_fwd(r.ws<half_t>(W.q), d, kv, 2 * d, kv + d, 2 * d, r.ws<half_t>(W.o2), d, r.ws<float>(W.lse2), d_src,
-                                 k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, st));
+                                 k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, &wl_ts, st));
     NMT_TRY(r.linear(r.ws<half_t>(W.o2), Nt, d, P.cross.wo, P.cross.bo, d, r.ws<half_t>(W.s2)));
     NMT_TRY(launch_residual_layernorm_fwd(r.ws<half_t>(W.s2), r.ws<half_t>(W.x1), r.w(P.ln2.g), r.w(P.ln2.b), r.ws<half_t>(W.x2),
                                           r.ws<float>(W.st2), Nt, d, k.ln_eps, r.drop(layer_site(li, kKindCrossRes), true, k.dropout), st));
@@ -617,6 +626,8 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   const float act_scale = (c->training && k.act_dropout > 0.f) ? 1.f / (1.f - k.act_dropout) : 1.f;
   half_t* dO = r.ws<half_t>(p.dO);
   const int4 *tab_ss = r.ws<int4>(p.tab_ss), *tab_tt = r.ws<int4>(p.tab_tt), *tab_ts = r.ws<int4>(p.tab_ts);
+  const AttnWork wl_ss = attention_work(r.ws<int32_t>(p.wl_ss), Bt, 0), wl_tt = attention_work(r.ws<int32_t>(p.wl_tt), Bt, 0),
+                 wl_ts = attention_work(r.ws<int32_t>(p.wl_ts), Bt, Ns);
   float* lnpart = r.ws<float>(p.lnpart);
   float* cspart = r.ws<float>(p.cspart);  // used on the second stream only
 
@@ -679,7 +690,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_TRY(r.dgrad(dsub, N, d, a.wo, d, dO));
     NMT_TRY(launch_attention_bwd(qkv, 3 * d, qkv + d, 3 * d, qkv + 2 * d, 3 * d, o, d, dO, d, lse, dqkv, 3 * d, dqkv + d, 3 * d,
                                  dqkv + 2 * d, 3 * d, key_ids, k.pad_id, causal, Bt, H, dh, tgt ? maxT : maxS, tgt ? maxT : maxS,
-                                 tgt ? tab_tt : tab_ss, N, st));
+                                 tgt ? tab_tt : tab_ss, N, tgt ? &wl_tt : &wl_ss, st));
     NMT_TRY(fork());
     NMT_TRY(launch_colsum(dqkv, 3 * d, w.g(a.bqkv), cspart, N, 3 * d, sd, c->gscale));
     NMT_TRY(w.wgrad(dqkv, N, 3 * d, x_in, d, a.wqkv));
@@ -721,7 +732,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     NMT_TRY(r.dgrad(dsub, Nt, d, P.cross.wo, d, dO));
     const half_t* kv = r.ws<half_t>(W.kv);
     NMT_TRY(launch_attention_bwd(r.ws<half_t>(W.q), d, kv, 2 * d, kv + d, 2 * d, r.ws<half_t>(W.o2), d, dO, d, r.ws<float>(W.lse2), dq, d,
-                                 dkv, 2 * d, dkv + d, 2 * d, c->src, k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, st));
+                                 dkv, 2 * d, dkv + d, 2 * d, c->src, k.pad_id, 0, Bt, H, dh, maxT, maxS, tab_ts, Nt, &wl_ts, st));
     NMT_TRY(fork());
     NMT_TRY(launch_colsum(dq, d, w.g(P.cross.bq), cspart, Nt, d, sd, c->gscale));
     NMT_TRY(launch_colsum(dkv, 2 * d, w.g(P.cross.bkv), cspart, Ns, 2 * d, sd, c->gscale));
@@ -827,7 +838,7 @@ extern "C" int nmt_op_attention_fwd(const void* d_Q, int32_t ldq, const void* d_
                                     void* d_O, int32_t ldo, float* d_lse, const int32_t* d_key_ids, int32_t pad_id, int32_t causal,
                                     int32_t B, int32_t H, int32_t dh, int32_t Tq, int32_t Tk, void* stream) {
   return launch_attention_fwd(static_cast<const half_t*>(d_Q), ldq, static_cast<const half_t*>(d_K), ldk, static_cast<const half_t*>(d_V),
-                              ldv, static_cast<half_t*>(d_O), ldo, d_lse, d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, nullptr, 0,
+                              ldv, static_cast<half_t*>(d_O), ldo, d_lse, d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, nullptr, 0, nullptr,
                               static_cast<hipStream_t>(stream));
 }
 extern "C" int nmt_op_attention_bwd(const void* d_Q, int32_t ldq, const void* d_K, int32_t ldk, const void* d_V, int32_t ldv,
@@ -838,7 +849,7 @@ extern "C" int nmt_op_attention_bwd(const void* d_Q, int32_t ldq, const void* d_
   return launch_attention_bwd(static_cast<const half_t*>(d_Q), ldq, static_cast<const half_t*>(d_K), ldk, static_cast<const half_t*>(d_V),
                               ldv, static_cast<const half_t*>(d_O), ldo, static_cast<const half_t*>(d_dO), lddo, d_lse,
                               static_cast<half_t*>(d_dQ), lddq, static_cast<half_t*>(d_dK), lddk, static_cast<half_t*>(d_dV), lddv,
-                              d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, nullptr, 0, static_cast<hipStream_t>(stream));
+                              d_key_ids, pad_id, causal, B, H, dh, Tq, Tk, nullptr, 0, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int nmt_op_residual_layernorm_fwd(const void* d_sub, const void* d_resid, const void* d_gamma, const void* d_beta,

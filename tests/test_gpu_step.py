@@ -374,6 +374,42 @@ def test_packed_sentences_without_padding_match_the_oracle_and_the_padded_pass()
         sess.close()
 
 
+def test_packed_pass_with_every_sentence_length_class_matches_the_oracle():
+    """Sentences of 3 to 150 positions in one packed pass: the attention kernels take them from per-class
+    work lists (one to four 32-position tiles on the longer side, and longer ones), all of which occur here."""
+    model = dict(I.MODELS["tiny"], dropout=0.1)
+    weights = I.init_weights(seed=23, perturb=0.05, **model)
+    shapes = [(2, 150, 131), (2, 97, 128), (3, 60, 90), (4, 33, 40), (7, 9, 12), (2, 3, 33)]
+    batches = [I.tiny_batch(seed=500 + i, B=B, S=S, T=T, vocab=model["vocab"], short_rows=1, short_by=2)
+               for i, (B, S, T) in enumerate(shapes)]
+    uids = [np.arange(50 * i, 50 * i + b["src"].shape[0], dtype=np.uint32) for i, b in enumerate(batches)]
+    batches = [dict(b, sent_uid=uids[i]) for i, b in enumerate(batches)]
+    cfg = _oracle_cfg(model, act_dropout=0.1, seed=9)
+    P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    loss_scale, step = 32.0, 2
+    acc, loss_ref, ntok_ref, allow = None, 0.0, 0, []
+    for j, mb in enumerate(batches):
+        l, n, cache = O.forward_loss(P16, cfg, mb["src"], mb["tgt_in"], mb["tgt_out"], training=True, step=step, micro=j, sent_uid=uids[j])
+        g = O.backward(P16, cfg, cache, loss_scale)
+        allow.append(_gate_allowance(P16, cfg, cache, loss_scale, g))
+        acc = O.accumulate(acc, g, j == 0)
+        loss_ref += l
+        ntok_ref += n
+    want = O.to_fp16_storage(acc)
+    allow_acc = {k: float(np.sqrt(sum(a[k] ** 2 for a in allow))) for k in allow[0]}
+    sess = Session(model, weights, act_dropout=0.1, seed=9, max_sentences=32, max_len=160)
+    try:
+        (pk,) = sess.pack(batches)
+        sess.forward_loss(pk, loss_scale, step)
+        sess.backward()
+        assert int(sess.ntok.item()) == ntok_ref
+        assert abs(float(sess.loss_sum.item()) - loss_ref) / loss_ref <= LOSS_TOL
+        worst = _check_grads(sess, sess.g16, want, model["d_model"], "packed g16, all length classes", allow_acc)
+        print("packed pass, all length classes: worst gradient rel-L2", worst)
+    finally:
+        sess.close()
+
+
 def test_packed_entry_point_clamps_inconsistent_lengths_and_rejects_bad_totals():
     """Lengths on the device that exceed what the host announced are cut to the announced totals (no
     access outside the buffers; the result is then undefined but finite buffers stay in bounds);
