@@ -353,48 +353,62 @@ __global__ void __launch_bounds__(kThreads) softmax_xent_kernel(half_t* __restri
     if (threadIdx.x == 0) row_loss[row] = 0.f;
     return;
   }
+  // The row stays in registers as fp16.  Pass 1 (maximum, plain sum) runs on pairs of halfs; the two
+  // exponential passes fold the shift and the scale into one fused multiply-add in front of the base-2
+  // exponential: exp(z - m) = 2^(z log2e - m log2e), loss_scale * exp(z - lse) = 2^(z log2e - lse log2e + log2 loss_scale).
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  struct Pairs { half2_t p[4]; };
+  constexpr float kLog2e = 1.4426950408889634f;
   half8_t reg[NCH];
-  float mx = -INFINITY, sz = 0.f;
+  half2_t mx2 = {(_Float16)-INFINITY, (_Float16)-INFINITY};
+  const half2_t ones = {(_Float16)1.f, (_Float16)1.f};
+  float sz = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int c = threadIdx.x + kThreads * i;
     if (c < chunks) {
       reg[i] = ld_half8(z + c * 8);
+      const Pairs h = __builtin_bit_cast(Pairs, reg[i]);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float f = (float)reg[i][e];
-        mx = fmaxf(mx, f);
-        sz += f;
+      for (int e = 0; e < 4; ++e) {
+        mx2 = __builtin_elementwise_max(mx2, h.p[e]);
+        sz = __builtin_amdgcn_fdot2(h.p[e], ones, sz, false);
       }
     }
   }
   const int yc = min(max(y, 0), V - 1);
   const float zy = (float)z[yc];
-  mx = block_reduce(mx, true, sh);
+  const float mx = block_reduce(fmaxf((float)mx2[0], (float)mx2[1]), true, sh);
+  const float shift = -mx * kLog2e;
   float se = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     if (threadIdx.x + kThreads * i < chunks) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) se += __expf((float)reg[i][e] - mx);
+      for (int e = 0; e < 8; ++e) se += __builtin_amdgcn_exp2f(fmaf((float)reg[i][e], kLog2e, shift));
     }
   }
   se = block_reduce(se, false, sh);
   sz = block_reduce(sz, false, sh);
   const float lse = mx + logf(se);
   if (threadIdx.x == 0) row_loss[row] = lse - (1.f - eps_ls) * zy - (eps_ls / (float)V) * sz;
-  const float q_uniform = eps_ls / (float)V;
+  const float q_scaled = loss_scale * eps_ls / (float)V, hit = loss_scale * (1.f - eps_ls);
+  const float shift2 = -lse * kLog2e + log2f(loss_scale);
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int c = threadIdx.x + kThreads * i;
     if (c < chunks) {
+      float g[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[e] = __builtin_amdgcn_exp2f(fmaf((float)reg[i][e], kLog2e, shift2)) - q_scaled;
+      if (c == (yc >> 3)) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (e == (yc & 7)) g[e] -= hit;
+      }
       half8_t o;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float g = __expf((float)reg[i][e] - lse) - q_uniform;
-        if (c * 8 + e == yc) g -= 1.f - eps_ls;
-        o[e] = (half_t)(loss_scale * g);
-      }
+      for (int e = 0; e < 8; ++e) o[e] = (half_t)g[e];
       st_half8(z + c * 8, o);
     }
   }
