@@ -119,8 +119,11 @@ struct DirectOp {
 };
 
 // ---- transposed operand: memory [K][rows] (rows contiguous), LDS tile [BK k][R] -------------------
-// Within k row k, slot q (16 bytes) holds chunk q ^ (y(k) << 1): the four k rows a 16-lane group of
-// the transposing read touches then lie in four different 32-byte bank segments.
+// Within k row k, slot q (16 bytes) holds chunk q ^ sw(k & 3).  A transposing read serves 32 lanes at a
+// time: two 16-lane groups (MFMA rows 0..15 and 16..31), each touching four k rows x two chunks.  With
+// sw(k) = k << 2 (chunk bits 2 and 3; bit 0 counts the two chunks of a group, bit 1 the group) those
+// sixteen chunks are all different, i.e. the 32 lanes cover every bank of a 256-byte row segment once.
+// (A 64-wide tile has only 8 chunks per k row: there sw(k) = k << 1 and the two groups share banks.)
 template <int R, int BK, int NW>
 struct TransOp {
   static constexpr int ROWB = R * 2;        // bytes per k row
@@ -131,7 +134,7 @@ struct TransOp {
   static_assert(NV >= 1 && BYTES % (1024 * NW) == 0, "tile too small for the work-group's waves");
   uint32_t voff[NV];
   int wave;
-  __device__ __forceinline__ static int ysw(int k2) { return R == 64 ? (k2 & 3) : ((k2 & 1) | ((k2 & 2) << 1)); }
+  __device__ __forceinline__ static int sw(int k) { return (k & 3) << (R == 64 ? 1 : 2); }
   __device__ __forceinline__ static const half_t* origin(const half_t* p, int ld, int r0, int k0) { return p + (size_t)k0 * ld + r0; }
   // k rows >= K lie beyond the extent and arrive as zeros
   __device__ __forceinline__ static uint32_t extent(int rows_in, int ld, int kleft) {
@@ -140,7 +143,7 @@ struct TransOp {
   __device__ __forceinline__ void init(int ld, int rows_in, int tid) {
     wave = tid >> 6;
     const int L = tid & 63, kl = L / CPR, slot = L % CPR;
-    const int cc = slot ^ (ysw((KPI * wave + kl) & 3) << 1);  // k row of instruction `it` is KPI * (wave + NW it) + kl
+    const int cc = slot ^ sw(KPI * wave + kl);  // k row of instruction `it` is KPI * (wave + NW it) + kl: same k & 3 for every it
     const bool ok = cc * 8 < rows_in;
 #pragma unroll
     for (int it = 0; it < NV; ++it)
@@ -151,24 +154,23 @@ struct TransOp {
     for (int it = 0; it < NV; ++it) dma16(rsrc, tile + (wave + NW * it) * 1024, voff[it]);
   }
   static constexpr int READS = 2;
-  struct Frag { uint32_t a[2]; };
+  struct Frag { uint32_t a[4]; };  // one address per MFMA tile of the wave (the swizzle reaches the bits a tile step changes)
   // 16-lane group q = lane/16 serves rows 16*(q&1).. of the MFMA tile and k-half q/2; lane i of the group
-  // addresses k row i/4, row offset 4*(i%4) of its 4(k) x 16(row) block.  The swizzle touches chunk bits
-  // 1 and 3, so MFMA tiles 2 and 3 of a wave (row offset 64, chunk bit 3) get an address of their own.
+  // addresses k row i/4, row offset 4*(i%4) of its 4(k) x 16(row) block.
   __device__ __forceinline__ static Frag frag_init(int row0, int lane) {
     const int q = lane >> 4, i = lane & 15;
     const int kk = 8 * (q >> 1) + (i >> 2);
     Frag f;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int r = row0 + 64 * h + 16 * (q & 1) + 4 * (i & 3);
-      const int cc = (r >> 3) ^ (ysw((i >> 2) & 3) << 1);
-      f.a[h] = (uint32_t)(kk * ROWB + cc * 16 + (r & 7) * 2);
+    for (int t = 0; t < 4; ++t) {
+      const int r = row0 + 32 * t + 16 * (q & 1) + 4 * (i & 3);
+      const int cc = ((r >> 3) ^ sw(i >> 2)) & (CPR - 1);   // (tiles past the wave's share are never read)
+      f.a[t] = (uint32_t)(kk * ROWB + cc * 16 + (r & 7) * 2);
     }
     return f;
   }
   __device__ __forceinline__ static half8_t frag(const unsigned char* tile, const Frag& f, int i, int s) {
-    const unsigned char* p = tile + f.a[i >> 1] + s * 16 * ROWB + (i & 1) * 64;
+    const unsigned char* p = tile + f.a[i] + s * 16 * ROWB;
     const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
     const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 4 * ROWB));
     const short8_t r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
