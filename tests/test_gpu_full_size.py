@@ -61,6 +61,13 @@ def test_transformer_big_sub_batch_matches_oracle():
     _full_size_case("big", batch, loss_scale=32.0, draws=2)
 
 
+def test_transformer_big_40k_vocabulary_5k_token_sub_batch_matches_oracle():
+    # the larger sub-batch (5120 tokens) and a vocabulary that is not a multiple of the GEMM tile (40000)
+    batch = I.workload_batches("big40k", which="median", count=1, n_sentences=50_000)[0]
+    assert batch["src"].shape[0] * max(batch["src"].shape[1], batch["tgt_in"].shape[1]) > 4000
+    _full_size_case("big40k", batch, loss_scale=32.0, draws=2)
+
+
 def test_transformer_base_long_sequences_match_oracle():
     # the longest bucket of the length distribution (sequences of ~250 tokens, few sentences)
     buckets, src_len, tgt_len, rng = I.make_buckets("base", 50_000)
