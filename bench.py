@@ -7,7 +7,7 @@ accumulate), then overflow check + Adam.  Inputs are synthetic (seeded length / 
 distributions standing in for the paper's WMT sub-batches) and resident in HBM before the timed
 region starts.  Prints ONE JSON line; see the design doc for the field definitions.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big_accum|big|big40k|base|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big_accum|big|big40k|base]
 """
 from __future__ import annotations
 
