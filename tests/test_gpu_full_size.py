@@ -123,5 +123,20 @@ def test_bench_configuration_one_packed_pass_equals_sub_batches_one_by_one():
         sess.accumulate(True)               # divides the factor out again
         acc = sess.named(sess.acc)
         assert all(rel_l2(acc[k].astype(np.float64), got[k]) <= 1e-6 for k in ref)
+        # the attention work lists (query tiles, sentences by length class) only choose which work-groups
+        # start: the same pass with the kernels enumerating every (sentence, tile) gives the same bits
+        import os
+        import torch
+        g_lists = sess.g16.clone()
+        loss_lists = float(sess.loss_sum.item())
+        os.environ["NMT_NO_WORKLISTS"] = "1"
+        try:
+            sess.forward_loss(pk, loss_scale, step)
+            sess.backward()
+            torch.cuda.synchronize()
+        finally:
+            del os.environ["NMT_NO_WORKLISTS"]
+        assert float(sess.loss_sum.item()) == loss_lists
+        assert torch.equal(sess.g16.view(torch.int16), g_lists.view(torch.int16))
     finally:
         sess.close()
