@@ -39,8 +39,9 @@ struct AttnArgs {
   int fused_max;                     // backward: sentences with max(Tq, Tk) <= this are left to the fused kernel
   // work lists over the table (or nullptr: every (sentence, tile) of the grid is looked at)
   const int32_t* wl_counts;          // [0..3] sentences by tiles of the longer side, [4] longer ones, [5] query tiles
-  const int32_t* wl_sent;            // [4][B] sentence indices by class
-  const int2* wl_qtiles;             // (sentence, query tile)
+  const int4* wl_sent;               // [4][B] table entries of the sentences of each class
+  const int4* wl_qsent;              // per query tile: its sentence's table entry ...
+  const int32_t* wl_qtile;           // ... and its tile number
 };
 
 // Rows and lengths of sentence b: from the table when several batches of different shapes are
@@ -87,31 +88,35 @@ __device__ __forceinline__ half8_t tr_frag(const half_t* x, int pitch, int kbase
   return __builtin_bit_cast(half8_t, r);
 }
 
-// The wavefront's own work item: sentence b, head h, 32-row tile `tile`.
+// The wavefront's own work item: a sentence, head h, 32-row tile `tile`.
 struct Item {
-  int b, h, tile;
+  Sent se;
+  int h, tile;
   bool live;
 };
 // LIST 0: the grid enumerates (sentence, tile); 1: entry blockIdx.x / hg of the query-tile list;
-// 2: entry blockIdx.x / hg of the list of sentences of class `cls` (tile = 0).
+// 2: entry blockIdx.x / hg of the list of sentences of class `cls` (tile = 0).  List entries carry
+// the sentence's table entry, so a work item costs one dependent load, not two.
 template <int LIST>
 __device__ __forceinline__ Item work_item(const AttnArgs& a, int cls = 0) {
   const int wpb = blockDim.x >> 6;            // heads per work-group (one wavefront each)
   const int hg = (a.H + wpb - 1) / wpb;
+  const int idx = blockIdx.x / hg;
   Item it;
-  it.b = blockIdx.x / hg;
   it.h = (blockIdx.x % hg) * wpb + (threadIdx.x >> 6);
   it.tile = blockIdx.y;
   it.live = it.h < a.H;
-  if (LIST == 1 && a.wl_qtiles) {
-    it.live = it.live && it.b < a.wl_counts[5];
-    const int2 e = it.live ? a.wl_qtiles[it.b] : make_int2(0, 0);
-    it.b = e.x;
-    it.tile = e.y;
-  }
-  if (LIST == 2 && a.wl_sent) {
-    it.live = it.live && it.b < a.wl_counts[cls];
-    it.b = it.live ? a.wl_sent[(size_t)cls * a.B + it.b] : 0;
+  if (LIST == 1 && a.wl_qsent) {
+    it.live = it.live && idx < a.wl_counts[5];
+    const int4 t = it.live ? a.wl_qsent[idx] : make_int4(0, 0, 0, 0);
+    it.tile = it.live ? a.wl_qtile[idx] : 0;
+    it.se = Sent{t.x, t.y, t.z, t.w};
+  } else if (LIST == 2 && a.wl_sent) {
+    it.live = it.live && idx < a.wl_counts[cls];
+    const int4 t = it.live ? a.wl_sent[(size_t)cls * a.B + idx] : make_int4(0, 0, 0, 0);
+    it.se = Sent{t.x, t.y, t.z, t.w};
+  } else {
+    it.se = it.live ? sentence(a, idx) : Sent{0, 0, 0, 0};
   }
   return it;
 }
@@ -184,7 +189,7 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Item it = work_item<1>(a);
   if (!it.live) return;
-  const Sent se = sentence(a, it.b);
+  const Sent se = it.se;
   const int q0 = it.tile * 32;
   if (q0 >= se.Tq) return;
   const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
@@ -260,7 +265,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Item it = work_item<0>(a);
   if (!it.live) return;
-  const Sent se = sentence(a, it.b);
+  const Sent se = it.se;
   const int k0 = it.tile * 32;
   if (k0 >= se.Tk || max(se.Tq, se.Tk) <= a.fused_max) return;
   const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
@@ -354,7 +359,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a)
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Item it = work_item<0>(a);
   if (!it.live) return;
-  const Sent se = sentence(a, it.b);
+  const Sent se = it.se;
   const int q0 = it.tile * 32;
   if (q0 >= se.Tq || max(se.Tq, se.Tk) <= a.fused_max) return;
   const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
@@ -429,7 +434,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Item it = work_item<2>(a, NT - 1);
   if (!it.live) return;
-  const Sent se = sentence(a, it.b);
+  const Sent se = it.se;
   const int tmax = max(se.Tq, se.Tk);
   if (tmax > 32 * NT || tmax <= 32 * (NT - 1)) return;  // longer: other kernels; shorter: the instance with fewer tiles
   const int lane = threadIdx.x & 63, g = lane >> 5, h = it.h;
@@ -583,7 +588,7 @@ int64_t class_bound(int n_sent, int n_q_rows, int n_k_rows, int c) {
 template <int DH>
 int fwd_launch(const AttnArgs& a, hipStream_t stream) {
   dim3 grid(a.B * ((a.H + 3) / 4), ceil_div(a.Tq, 32));
-  if (a.wl_qtiles) grid = dim3((unsigned)(qtile_bound(a.B, a.Nq, a.Tq) * ((a.H + 3) / 4)), 1);
+  if (a.wl_qsent) grid = dim3((unsigned)(qtile_bound(a.B, a.Nq, a.Tq) * ((a.H + 3) / 4)), 1);
   hipLaunchKernelGGL(attn_fwd_kernel<DH>, grid, dim3(kThreads), tile_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
@@ -647,7 +652,7 @@ int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
                          const int4* sent_tab, int n_q_rows, const AttnWork* work, hipStream_t stream) {
   AttnArgs a = {};
   a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
-  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qtiles = work->qtiles; }
+  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qsent = work->qsent; a.wl_qtile = work->qtile; }
   a.Q = Q; a.K = K; a.V = V; a.Out = O; a.lse = lse; a.key_ids = key_ids;
   a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.ldo = ldo;
   a.pad_id = pad_id; a.causal = causal; a.B = B; a.H = H; a.Tq = Tq; a.Tk = Tk;
@@ -669,7 +674,7 @@ int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
                          const int4* sent_tab, int n_q_rows, const AttnWork* work, hipStream_t stream) {
   AttnArgs a = {};
   a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
-  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qtiles = work->qtiles; }
+  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qsent = work->qsent; a.wl_qtile = work->qtile; }
   const int n_k_rows = work ? work->n_k_rows : 0;
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.lse = const_cast<float*>(lse); a.key_ids = key_ids;
   a.dQ = dQ; a.dK = dK; a.dV = dV;
@@ -692,7 +697,8 @@ int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
 // ------------------------------------------------------------------------------------------------
 // Work lists of one attention kind over a sentence table.  One block; thread t takes a contiguous run of
 // sentences, so every list is in sentence order (and so the same from run to run).
-// storage: [0..7] counts, then [4][n_sent] sentences by class, then bound_q (sentence, tile) pairs.
+// storage (int32 words): [0..7] counts, then [4][n_sent] int4 table entries by class, then bound_q int4
+// table entries and bound_q tile numbers of the query tiles.
 // ------------------------------------------------------------------------------------------------
 namespace {
 __global__ void __launch_bounds__(1024) attn_worklists_kernel(const int4* __restrict__ tab, int n_sent, int bound_q,
@@ -722,14 +728,18 @@ __global__ void __launch_bounds__(1024) attn_worklists_kernel(const int4* __rest
   int at[6];
 #pragma unroll
   for (int c = 0; c < 6; ++c) at[c] = sh[c][t] - cnt[c];
-  int32_t* by_tiles = st + 8;
-  int2* qtiles = reinterpret_cast<int2*>(st + 8 + 4 * (size_t)n_sent);
+  int4* by_tiles = reinterpret_cast<int4*>(st + 8);
+  int4* qsent = by_tiles + 4 * (size_t)n_sent;
+  int32_t* qtile = reinterpret_cast<int32_t*>(qsent + bound_q);
   for (int i = lo; i < hi; ++i) {
     const int4 e = tab[i];
     const int nt = max(1, (max(e.z, e.w) + 31) >> 5);
-    if (nt <= 4) by_tiles[(size_t)(nt - 1) * n_sent + at[nt - 1]++] = i;
+    if (nt <= 4) by_tiles[(size_t)(nt - 1) * n_sent + at[nt - 1]++] = e;
     for (int q = 0; q < (e.z + 31) >> 5; ++q, ++at[5])
-      if (at[5] < bound_q) qtiles[at[5]] = make_int2(i, q);
+      if (at[5] < bound_q) {
+        qsent[at[5]] = e;
+        qtile[at[5]] = q;
+      }
   }
   if (t == 1023) {
 #pragma unroll
@@ -740,21 +750,22 @@ __global__ void __launch_bounds__(1024) attn_worklists_kernel(const int4* __rest
 }  // namespace
 
 int64_t attention_worklist_ints(int n_sent, int n_q_rows) {
-  return 8 + 4 * (int64_t)n_sent + 2 * qtile_capacity(n_sent, n_q_rows);
+  return 8 + 16 * (int64_t)n_sent + 5 * qtile_capacity(n_sent, n_q_rows);
 }
 
-AttnWork attention_work(const int32_t* storage, int n_sent, int n_k_rows) {
+AttnWork attention_work(const int32_t* storage, int n_sent, int n_q_rows, int n_k_rows) {
   AttnWork w;
   w.counts = storage;
-  w.by_tiles = storage + 8;
-  w.qtiles = reinterpret_cast<const int2*>(storage + 8 + 4 * (size_t)n_sent);
+  w.by_tiles = reinterpret_cast<const int4*>(storage + 8);
+  w.qsent = w.by_tiles + 4 * (size_t)n_sent;
+  w.qtile = reinterpret_cast<const int32_t*>(w.qsent + qtile_capacity(n_sent, n_q_rows));
   w.n_k_rows = n_k_rows;
   return w;
 }
 
 int launch_attention_worklists(const int4* tab, int n_sent, int n_q_rows, int32_t* storage, hipStream_t stream) {
   NMT_REQUIRE(tab && storage && n_sent > 0 && n_q_rows > 0, "attention work lists: null pointer or empty table");
-  NMT_REQUIRE((reinterpret_cast<uintptr_t>(storage) & 7u) == 0, "attention work lists: storage must be 8-byte aligned");
+  NMT_REQUIRE((reinterpret_cast<uintptr_t>(storage) & 15u) == 0, "attention work lists: storage must be 16-byte aligned");
   hipLaunchKernelGGL(attn_worklists_kernel, dim3(1), dim3(1024), 0, stream, tab, n_sent, (int)qtile_capacity(n_sent, n_q_rows), storage);
   NMT_LAUNCH_CHECK();
   return NMT_OK;

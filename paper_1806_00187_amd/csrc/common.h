@@ -144,15 +144,18 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
 // Work lists of one attention kind over a sentence table, made on the device (launch_attention_worklists)
 // so that the attention kernels start no work-group for a (sentence, tile) that does not exist:
 // counts[c], c = 0..3: sentences whose longer side takes c + 1 tiles of 32 positions, [4]: longer ones,
-// [5]: query tiles; by_tiles [4][n_sent]: the sentences of each class; qtiles: (sentence, query tile).
+// [5]: query tiles; by_tiles [4][n_sent]: the table entries of the sentences of each class; qsent / qtile:
+// per query tile its sentence's table entry and its tile number (entries are copies, so that a work
+// item needs one dependent load).
 struct AttnWork {
   const int32_t* counts = nullptr;
-  const int32_t* by_tiles = nullptr;
-  const int2* qtiles = nullptr;
+  const int4* by_tiles = nullptr;
+  const int4* qsent = nullptr;
+  const int32_t* qtile = nullptr;
   int n_k_rows = 0;  // key rows in total; 0 for self-attention (the keys are the queries' rows)
 };
-int64_t attention_worklist_ints(int n_sent, int n_q_rows);  // int32 words of storage behind one AttnWork
-AttnWork attention_work(const int32_t* storage, int n_sent, int n_k_rows);
+int64_t attention_worklist_ints(int n_sent, int n_q_rows);  // int32 words of storage behind one AttnWork (16-byte aligned)
+AttnWork attention_work(const int32_t* storage, int n_sent, int n_q_rows, int n_k_rows);
 int launch_attention_worklists(const int4* tab, int n_sent, int n_q_rows, int32_t* storage, hipStream_t stream);
 
 int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, const half_t* V, int ldv, half_t* O,

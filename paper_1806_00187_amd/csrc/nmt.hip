@@ -522,8 +522,8 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
   NMT_TRY(launch_attention_worklists(tab_ss, Bt, Ns, r.ws<int32_t>(p.wl_ss), st));
   NMT_TRY(launch_attention_worklists(tab_tt, Bt, Nt, r.ws<int32_t>(p.wl_tt), st));
   NMT_TRY(launch_attention_worklists(tab_ts, Bt, Nt, r.ws<int32_t>(p.wl_ts), st));
-  const AttnWork wl_ss = attention_work(r.ws<int32_t>(p.wl_ss), Bt, 0), wl_tt = attention_work(r.ws<int32_t>(p.wl_tt), Bt, 0),
-                 wl_ts = attention_work(r.ws<int32_t>(p.wl_ts), Bt, Ns);
+  const AttnWork wl_ss = attention_work(r.ws<int32_t>(p.wl_ss), Bt, Ns, 0), wl_tt = attention_work(r.ws<int32_t>(p.wl_tt), Bt, Nt, 0),
+                 wl_ts = attention_work(r.ws<int32_t>(p.wl_ts), Bt, Nt, Ns);
 
   // ---- encoder ----
   half_t* x = r.ws<half_t>(p.x0);
@@ -626,8 +626,8 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   const float act_scale = (c->training && k.act_dropout > 0.f) ? 1.f / (1.f - k.act_dropout) : 1.f;
   half_t* dO = r.ws<half_t>(p.dO);
   const int4 *tab_ss = r.ws<int4>(p.tab_ss), *tab_tt = r.ws<int4>(p.tab_tt), *tab_ts = r.ws<int4>(p.tab_ts);
-  const AttnWork wl_ss = attention_work(r.ws<int32_t>(p.wl_ss), Bt, 0), wl_tt = attention_work(r.ws<int32_t>(p.wl_tt), Bt, 0),
-                 wl_ts = attention_work(r.ws<int32_t>(p.wl_ts), Bt, Ns);
+  const AttnWork wl_ss = attention_work(r.ws<int32_t>(p.wl_ss), Bt, Ns, 0), wl_tt = attention_work(r.ws<int32_t>(p.wl_tt), Bt, Nt, 0),
+                 wl_ts = attention_work(r.ws<int32_t>(p.wl_ts), Bt, Nt, Ns);
   float* lnpart = r.ws<float>(p.lnpart);
   float* cspart = r.ws<float>(p.cspart);  // used on the second stream only
 
