@@ -436,6 +436,228 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Persistent form of the 256 x 256, 8-wave kernel for products whose epilogue loads nothing per
+// element (bias, ReLU and the output scale only): one work-group per compute unit walks its tiles
+// (the same tile -> XCD assignment as above) and asks for the first k-tiles of its next tile BEFORE
+// it stores the current one, so that their latency passes behind the epilogue instead of in front of
+// the next main loop.  Vector-memory operations retire in issue order on one counter: the wait for
+// those early k-tiles is "at most as many operations outstanding as were issued after them" (the
+// epilogue's stores and the remaining requests), which does not wait for the stores.  LDS: the stages
+// not being prefetched into serve as the epilogue's staging area.
+// ------------------------------------------------------------------------------------------------
+// LDS accesses of the persistent kernel's staging rows, written as instructions: while requests into
+// other stages are in flight the compiler would otherwise put a wait for ALL of them in front of any
+// LDS access it cannot tell apart from their targets.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
+__device__ __forceinline__ void stage_write16(uint32_t addr, floatx4 v) {
+  asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+// two 16-byte reads, returned once both have arrived (and every earlier LDS operation of the wave)
+__device__ __forceinline__ void stage_read32(uint32_t a0, uint32_t a1, floatx4& lo, floatx4& hi) {
+  asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)" : "=&v"(lo), "=&v"(hi) : "v"(a0), "v"(a1) : "memory");
+}
+
+template <bool AT, bool BT, int BK, int NS>
+__global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) {
+  constexpr int BM = 256, BN = 256, NW = 8;
+  using T = Tile<BM, BN, AT, BT, BK, NW>;
+  using OpA = typename T::OpA;
+  using OpB = typename T::OpB;
+  static_assert(NS == 2 || NS == 4, "two or four stages");
+  __shared__ __align__(1024) unsigned char stage0[T::STAGE];
+  __shared__ __align__(1024) unsigned char stage1[T::STAGE];
+  __shared__ __align__(1024) unsigned char stage2[NS > 2 ? T::STAGE : 16];
+  __shared__ __align__(1024) unsigned char stage3[NS > 3 ? T::STAGE : 16];
+  constexpr int WGN = 4, WM = 128, WN = 64, TM = 4, TN = 2, KS = BK / 16;
+  static_assert((NS == 2 ? 1 : 2) * T::STAGE >= NW * 32 * WN * 4, "the spare stages must hold the staging area");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int nt = g.tiles_m * g.tiles_n;
+
+  auto decode = [&](int lin, int& m0, int& n0) {
+    const int xcd = lin & 7, idx = lin >> 3, base = nt >> 3, rem = nt & 7;
+    const int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+    const int per_group = g.group_m * g.tiles_n;
+    const int first = (pid / per_group) * g.group_m;
+    const int rows = min(g.tiles_m - first, g.group_m);
+    m0 = (first + (pid % per_group) % rows) * BM;
+    n0 = ((pid % per_group) / rows) * BN;
+  };
+
+  OpA opa;
+  OpB opb;
+  int m0, n0, rows_a, rows_b;  // the tile the operand descriptors are set up for
+  // Per-lane offsets are recomputed where they are needed rather than kept in registers across the
+  // epilogue (the register file is full there); the empty asm keeps the compiler from merging the copies.
+  auto setup = [&]() {
+    int t = tid;
+    asm volatile("" : "+v"(t));
+    rows_a = min(g.M - m0, BM);
+    rows_b = min(g.N - n0, BN);
+    opa.init(g.lda, rows_a, t);
+    opb.init(g.ldb, rows_b, t);
+  };
+  typename OpA::Frag fa;
+  typename OpB::Frag fb;
+  auto frag_setup = [&]() {
+    int l = lane;
+    asm volatile("" : "+v"(l));
+    fa = OpA::frag_init(wm * WM, l);
+    fb = OpB::frag_init(wn * WN, l);
+  };
+  auto request = [&](unsigned char* stage, int k0) {
+    const int kleft = g.K - k0;
+    opa.load(make_rsrc(OpA::origin(g.A, g.lda, m0, k0), OpA::extent(rows_a, g.lda, kleft)), stage, kleft);
+    opb.load(make_rsrc(OpB::origin(g.B, g.ldb, n0, k0), OpB::extent(rows_b, g.ldb, kleft)), stage + OpA::BYTES, kleft);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  constexpr int kPerTile = OpA::NV + OpB::NV;
+  floatx16 acc[TM][TN];
+  half8_t af[2][TM], bf[2][TN];
+  auto fetch = [&](const unsigned char* stage, int s, int set) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[set][i] = OpA::frag(stage, fa, i, s);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bf[set][j] = OpB::frag(stage + OpA::BYTES, fb, j, s);
+  };
+  auto multiply = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[set][j], af[set][i], acc[i][j], 0, 0, 0);
+  };
+  auto interleave = [&]() { Interleave<0, TM * TN, OpA::READS * TM + OpB::READS * TN>::run(); };
+  auto k_tile = [&](unsigned char* cur, const unsigned char* nxt, int k_refill) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      if (s == KS - 1) {
+        __builtin_amdgcn_s_waitcnt(wait_vm_lds((NS - 2) * kPerTile));
+        __builtin_amdgcn_s_barrier();
+        request(cur, k_refill);
+      }
+      fetch(s == KS - 1 ? nxt : cur, (s + 1) % KS, (s + 1) & 1);
+      multiply(s & 1);
+      interleave();
+    }
+  };
+  const int nk = (g.K + BK - 1) / BK;
+  const GemmEpilogue& ep = g.ep;
+  // staging: 32 rows x 64 floats per wave, in the stages the early requests do not touch
+  constexpr int SW = 64, CH = SW / 8;
+  const uint32_t stg = NS == 2 ? lds_addr(stage1) + wave * (32 * SW * 4) : lds_addr(wave < 4 ? stage2 : stage3) + (wave & 3) * (32 * SW * 4);
+  auto swz = [](int row, int chunk) { return chunk ^ (row & 15); };
+  constexpr int kStores = TM * (CH / 2);  // global stores of one wave's epilogue on a tile that lies wholly inside C
+
+  int lin = blockIdx.x;
+  decode(lin, m0, n0);
+  setup();
+  request(stage0, 0);
+  request(stage1, BK);
+  if constexpr (NS == 4) {
+    request(stage2, 2 * BK);
+    request(stage3, 3 * BK);
+  }
+  __builtin_amdgcn_s_waitcnt(wait_vm((NS - 1) * kPerTile));
+  __builtin_amdgcn_s_barrier();
+  frag_setup();
+  fetch(stage0, 0, 0);
+  for (;;) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    if constexpr (NS == 2) {
+      for (int kt = 0; kt < nk; kt += 2) {
+        k_tile(stage0, stage1, (kt + 2) * BK);
+        k_tile(stage1, stage0, (kt + 3) * BK);
+      }
+    } else {
+      for (int kt = 0; kt < nk; kt += 4) {
+        k_tile(stage0, stage1, (kt + 4) * BK);
+        k_tile(stage1, stage2, (kt + 5) * BK);
+        k_tile(stage2, stage3, (kt + 6) * BK);
+        k_tile(stage3, stage0, (kt + 7) * BK);
+      }
+    }
+    // what the epilogue needs of the current tile; its bias is fetched here, ahead of the requests
+    // below, and waited for together with the last refills (zeros past k), so that no wait of the
+    // epilogue has to pass those requests
+    const int m0c = m0, n0c = n0;
+    const int gc = n0c + wn * WN + (lane & (CH - 1)) * 8;
+    half8_t bias8 = zero_half8();
+    if (ep.bias && gc < g.N) bias8 = ld_half8(ep.bias + gc);
+    __builtin_amdgcn_s_waitcnt(wait_vm_lds(0));
+    __syncthreads();
+    const int next = lin + (int)gridDim.x;
+    const bool more = next < nt;
+    if (more) {
+      decode(next, m0, n0);
+      setup();
+      request(stage0, 0);
+      if constexpr (NS == 4) request(stage1, BK);
+    }
+    // ---- epilogue of (m0c, n0c): accumulators -> the wave's staging rows -> 16-byte row stores ----
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if (i) wave_sync();
+#pragma unroll
+      for (int jj = 0; jj < SW / 32; ++jj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const floatx16& a = acc[i][jj];
+          const floatx4 v4 = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+          const int row = lane & 31, chunk = jj * 8 + 2 * q + (lane >> 5);
+          stage_write16(stg + (row * SW + swz(row, chunk) * 4) * 4, v4);
+        }
+      wave_sync();
+#pragma unroll
+      for (int it = 0; it < CH / 2; ++it) {
+        const int q = it * 64 + lane;
+        const int rl = q / CH, c8 = q % CH;
+        const int gr = m0c + wm * WM + i * 32 + rl;
+        if (gr < g.M && gc < g.N) {
+          floatx4 lo, hi;
+          stage_read32(stg + (rl * SW + swz(rl, 2 * c8) * 4) * 4, stg + (rl * SW + swz(rl, 2 * c8 + 1) * 4) * 4, lo, hi);
+          half8_t o;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float v = (e < 4 ? lo[e] : hi[e - 4]) * ep.out_scale + (float)bias8[e];
+            if (ep.relu) v = fmaxf(v, 0.f);
+            o[e] = (half_t)v;
+          }
+          st_half8(g.C + (size_t)gr * g.ldc + gc, o);
+        }
+      }
+    }
+    if (!more) break;
+    // every wave is done with the staging rows (its reads have returned: stage_read32 waits for them).  A bare
+    // barrier: __syncthreads() carries a fence, which would wait for the stores and the early requests.
+    __builtin_amdgcn_s_barrier();
+    setup();
+    if constexpr (NS == 2) {
+      request(stage1, BK);
+    } else {
+      request(stage2, 2 * BK);
+      request(stage3, 3 * BK);
+    }
+    // wait for the first k-tile of the new tile: everything issued after it may stay outstanding (the
+    // second early request, the stores of a full tile, the requests just made); a tile at the edge of C
+    // stores fewer rows or columns, so there the wait is for everything
+    const bool whole = m0c + BM <= g.M && n0c + BN <= g.N;
+    constexpr int kLater = (NS == 4 ? 3 : 1) * kPerTile + kStores;
+    static_assert(kLater < 64, "s_waitcnt vmcnt holds six bits");
+    if (whole) __builtin_amdgcn_s_waitcnt(wait_vm(kLater));
+    else __builtin_amdgcn_s_waitcnt(wait_vm(0));
+    __builtin_amdgcn_s_barrier();
+    frag_setup();
+    fetch(stage0, 0, 0);
+    lin = next;
+  }
+}
+
 // C[m, n] = fp16(sum_z partial[z][m][n]), 8 columns per thread, splits summed in increasing order
 __global__ void __launch_bounds__(kThreads) splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N,
                                                                 half_t* __restrict__ C, int ldc, float scale) {
@@ -572,6 +794,20 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
         return launch_gemm(a_t ? A + m_main : A + (size_t)m_main * lda, a_t, lda, B, b_t, ldb, C + (size_t)m_main * ldc, ldc, m_tail, N,
                            K, tail, stream, nullptr, 0, 1);
       }
+    }
+    // products with nothing to load per element in the epilogue and at least two tiles per compute unit:
+    // the persistent form (tuning aid NMT_GEMM_PERSIST=0 turns it off)
+    const char* pe = getenv("NMT_GEMM_PERSIST");
+    if (splits == 1 && !ep.add && !ep.relu_src && !ep.drop.thr && t256 >= 512 && !a_t && !(pe && !atoi(pe))) {
+      GemmArgs pg = g;
+      pg.tiles_m = ceil_div(M, 256);
+      pg.tiles_n = ceil_div(N, 256);
+      pg.group_m = (pg.tiles_n >= 12 && pg.tiles_n <= 16) ? 16 : 8;
+      pg.partial = nullptr;
+      if (!b_t) hipLaunchKernelGGL((gemm_persistent_kernel<false, false, 64, 2>), dim3(256), dim3(512), 0, stream, pg);
+      else hipLaunchKernelGGL((gemm_persistent_kernel<false, true, 32, 4>), dim3(256), dim3(512), 0, stream, pg);
+      NMT_LAUNCH_CHECK();
+      return NMT_OK;
     }
     // k-contiguous operands are fetched in whole 128-byte lines by 64-deep stages; transposed ones
     // gain more from the longer look-ahead of four 32-deep stages
