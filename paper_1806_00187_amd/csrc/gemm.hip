@@ -621,14 +621,33 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
         if (gr < g.M && gc < g.N) {
           floatx4 lo, hi;
           stage_read32(stg + (rl * SW + swz(rl, 2 * c8) * 4) * 4, stg + (rl * SW + swz(rl, 2 * c8 + 1) * 4) * 4, lo, hi);
-          half8_t o;
+          float v[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            float v = (e < 4 ? lo[e] : hi[e - 4]) * ep.out_scale + (float)bias8[e];
-            if (ep.relu) v = fmaxf(v, 0.f);
-            o[e] = (half_t)v;
+            v[e] = (e < 4 ? lo[e] : hi[e - 4]) * ep.out_scale + (float)bias8[e];
+            if (ep.relu) v[e] = fmaxf(v[e], 0.f);
           }
-          st_half8(g.C + (size_t)gr * g.ldc + gc, o);
+          // (loads from here on queue behind the early requests: they cost part of what those save)
+          if (ep.drop.thr) {
+            const uint32_t bits = drop_keep8(ep.drop, (uint32_t)(gr + ep.row0), (uint32_t)gc >> 3);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = ((bits >> e) & 1u) ? v[e] * ep.drop.scale : 0.f;
+          }
+          const size_t off = (size_t)gr * g.ldc + gc;
+          if (ep.add) {
+            const half8_t ad = ld_half8(ep.add + off);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += (float)ad[e];
+          }
+          if (ep.relu_src) {
+            const half8_t h = ld_half8(ep.relu_src + off);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = ((float)h[e] > 0.f) ? v[e] * ep.mask_scale : 0.f;
+          }
+          half8_t o;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (half_t)v[e];
+          st_half8(g.C + off, o);
         }
       }
     }
@@ -795,10 +814,17 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
                            K, tail, stream, nullptr, 0, 1);
       }
     }
-    // products with nothing to load per element in the epilogue and at least two tiles per compute unit:
-    // the persistent form (tuning aid NMT_GEMM_PERSIST=0 turns it off)
+    // At least two tiles per compute unit, no split along k, row-major A: the persistent form, by default
+    // for epilogues that load nothing per element.  With such loads it still wins 1-11 % on a product
+    // running alone, but in the backward pass, where the weight-gradient kernels of the second stream
+    // share the chip, work-groups that never leave their compute unit cost more than they gain
+    // (measured on the whole update).  Tuning aid: NMT_GEMM_PERSIST=0 never, =2 for every epilogue.
+    // (Not for a k-major A: the one such product without a split, the vocabulary weight gradient, has so
+    //  long a contraction that the tile change hardly counts, and measured 6 % slower in this form.)
     const char* pe = getenv("NMT_GEMM_PERSIST");
-    if (splits == 1 && !ep.add && !ep.relu_src && !ep.drop.thr && t256 >= 512 && !a_t && !(pe && !atoi(pe))) {
+    const int pmode = pe ? atoi(pe) : 1;
+    const bool loads_in_epilogue = ep.add || ep.relu_src || ep.drop.thr;
+    if (splits == 1 && t256 >= 512 && !a_t && pmode != 0 && (pmode == 2 || !loads_in_epilogue)) {
       GemmArgs pg = g;
       pg.tiles_m = ceil_div(M, 256);
       pg.tiles_n = ceil_div(N, 256);
