@@ -262,9 +262,9 @@ def phase_leg(sess, tr, dbatches, ntoks, torch):
 
 
 # HBM-side bytes per product of the default workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated against
-# kernels of known size; profiles/bench_big_accum_gemm_hbm_traffic.txt): 160.6 GB per update over 201 products,
+# kernels of known size; profiles/bench_big_accum_gemm_hbm_traffic.txt): 160.8 GB per update over 201 products,
 # for 87.4 GB of algorithmic operand + result bytes.
-MEASURED_GEMM_TRAFFIC = {"bytes_per_launch": 799e6, "algorithmic_bytes_per_launch": 435e6, "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
+MEASURED_GEMM_TRAFFIC = {"bytes_per_launch": 800e6, "algorithmic_bytes_per_launch": 435e6, "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
 
 
 def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
@@ -310,7 +310,7 @@ def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
             best = (rate, [M, N, K, kind])
     achieved = tot_flops / tot_ms / 1e9
     log(f"[bench] GEMM leg: {achieved:.1f} TFLOP/s over {n_launch} launches, {tot_ms:.2f} ms per update; worst {worst}, best {best}")
-    return {"bound": "mfma", "kernel": "gemm_kernel (all GEMM launches of one update, each shape timed alone)",
+    return {"bound": "mfma", "kernel": "gemm_kernel / gemm_persistent_kernel (all GEMM launches of one update, each shape timed alone)",
             "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS, "traffic": traffic,
             "launches_per_update": n_launch, "avg_launch_us": tot_ms * 1e3 / n_launch, "ms_per_update": tot_ms,
             "by_kind_tflops": {k: v[0] / v[1] / 1e9 for k, v in per_kind.items()}, "worst_tflops": worst, "best_tflops": best}
