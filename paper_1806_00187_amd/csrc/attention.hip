@@ -42,6 +42,7 @@ struct AttnArgs {
   const int4* wl_sent;               // [4][B] table entries of the sentences of each class
   const int4* wl_qsent;              // per query tile: its sentence's table entry ...
   const int32_t* wl_qtile;           // ... and its tile number
+  int vgx, vgy;                      // persistent kernels: the grid of work items their work-groups walk through
 };
 
 // Rows and lengths of sentence b: from the table when several batches of different shapes are
@@ -94,17 +95,19 @@ struct Item {
   int h, tile;
   bool live;
 };
-// LIST 0: the grid enumerates (sentence, tile); 1: entry blockIdx.x / hg of the query-tile list;
-// 2: entry blockIdx.x / hg of the list of sentences of class `cls` (tile = 0).  List entries carry
+// LIST 0: the grid enumerates (sentence, tile); 1: entry bx / hg of the query-tile list;
+// 2: entry bx / hg of the list of sentences of class `cls` (tile = 0).  List entries carry
 // the sentence's table entry, so a work item costs one dependent load, not two.
+// (bx, by): the work-group's place in the grid of work items -- blockIdx for a kernel that takes one item
+// per work-group, the loop position for a persistent one.
 template <int LIST>
-__device__ __forceinline__ Item work_item(const AttnArgs& a, int cls = 0) {
+__device__ __forceinline__ Item work_item(const AttnArgs& a, int bx, int by, int cls = 0) {
   const int wpb = blockDim.x >> 6;            // heads per work-group (one wavefront each)
   const int hg = (a.H + wpb - 1) / wpb;
-  const int idx = blockIdx.x / hg;
+  const int idx = bx / hg;
   Item it;
-  it.h = (blockIdx.x % hg) * wpb + (threadIdx.x >> 6);
-  it.tile = blockIdx.y;
+  it.h = (bx % hg) * wpb + (threadIdx.x >> 6);
+  it.tile = by;
   it.live = it.h < a.H;
   if (LIST == 1 && a.wl_qsent) {
     it.live = it.live && idx < a.wl_counts[5];
@@ -184,10 +187,9 @@ __device__ __forceinline__ void store_rows(half_t* tile, const floatx16 (&acc)[(
 // forward: the wavefront owns 32 queries
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attn_fwd_item(const AttnArgs& a, int bx, int by, unsigned char* smem_raw) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item<1>(a);
+  const Item it = work_item<1>(a, bx, by);
   if (!it.live) return;
   const Sent se = it.se;
   const int q0 = it.tile * 32;
@@ -254,6 +256,16 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_kernel(const AttnArgs a) {
   if (!qvalid) return;
   if (g == 0) a.lse[(size_t)h * a.Nq + se.q0 + q] = (m + log2f(l)) * kLn2;
 }
+// Persistent: the launch fills the chip once and every work-group walks through the work items with the
+// grid's stride.  A wavefront that ended after each item would first wait for its stores to land; here the
+// next item's loads go out right behind them.
+template <int DH>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH <= 64 ? 3 : 1, DH <= 64 ? 3 : 1)))
+attn_fwd_kernel(const AttnArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int total = a.vgx * a.vgy;
+  for (int v = blockIdx.x; v < total; v += gridDim.x) attn_fwd_item<DH>(a, v % a.vgx, v / a.vgx, smem_raw);
+}
 
 // ------------------------------------------------------------------------------------------------
 // backward, dK and dV: the wavefront owns 32 keys
@@ -263,7 +275,7 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_dkv_kernel(const AttnArgs a
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   constexpr int WAVE_LDS = 2 * 32 * PR * 2 + 2 * 32 * 4;  // Q and dO tiles, lse and D of the tile's queries
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item<0>(a);
+  const Item it = work_item<0>(a, blockIdx.x, blockIdx.y);
   if (!it.live) return;
   const Sent se = it.se;
   const int k0 = it.tile * 32;
@@ -357,7 +369,7 @@ template <int DH>
 __global__ void __launch_bounds__(kThreads) attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item<0>(a);
+  const Item it = work_item<0>(a, blockIdx.x, blockIdx.y);
   if (!it.live) return;
   const Sent se = it.se;
   const int q0 = it.tile * 32;
@@ -429,10 +441,9 @@ constexpr int fused_wave_lds() {
   return (2 * NT + 1) * 32 * (DH + 8) * 2 + 32 * kDsPitch * 2 + 2 * 32 * NT * 4;  // Q and dO tiles, one K tile, dS, lse and D
 }
 template <int DH, int NT>
-__global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attn_bwd_fused_item(const AttnArgs& a, int bx, unsigned char* smem_raw) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, TILE = 32 * PR;
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Item it = work_item<2>(a, NT - 1);
+  const Item it = work_item<2>(a, bx, 0, NT - 1);
   if (!it.live) return;
   const Sent se = it.se;
   const int tmax = max(se.Tq, se.Tk);
@@ -556,6 +567,20 @@ __global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs
   for (int qt = 0; qt < NT; ++qt)
     if (qt < nqt) store_rows<DH>(Qs + qt * TILE, dQt[qt], 1.f, a.dQ + (size_t)se.q0 * a.lddq + h * DH, a.lddq, qt * 32, se.Tq, lane);
 }
+// Persistent, as the forward kernel, for sentences of up to 64 positions; the instances for longer ones need
+// every register for one item (the loop form spills) and take one item per work-group.
+template <int DH, int NT>
+__global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  if constexpr (NT <= 2) {
+    for (int v = blockIdx.x; v < a.vgx; v += gridDim.x) {
+      wave_sync();  // the wavefront's LDS tiles are free again
+      attn_bwd_fused_item<DH, NT>(a, v, smem_raw);
+    }
+  } else {
+    attn_bwd_fused_item<DH, NT>(a, blockIdx.x, smem_raw);
+  }
+}
 
 template <int DH>
 constexpr size_t tile_smem() { return (size_t)4 * 32 * (DH + 8) * sizeof(half_t); }   // one 32-row tile per wavefront
@@ -585,11 +610,34 @@ int64_t class_bound(int n_sent, int n_q_rows, int n_k_rows, int c) {
   return b < n_sent ? b : n_sent;
 }
 
+// Work-groups of `kern` that the device holds at once (occupancy x compute units): the grid of a persistent launch.
+template <typename Kern>
+int resident_blocks(Kern kern, int threads, size_t smem, int* out) {
+  int per_cu = 0, dev = 0, cus = 0;
+  NMT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), threads, smem));
+  NMT_HIP_CHECK(hipGetDevice(&dev));
+  NMT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  *out = (per_cu > 0 ? per_cu : 1) * (cus > 0 ? cus : 1);
+  if (const char* e = getenv("NMT_ATTN_PERSIST"))  // tuning aid: 0 = one work item per work-group
+    if (!atoi(e)) *out = 0x7fffffff;
+  return NMT_OK;
+}
+
 template <int DH>
-int fwd_launch(const AttnArgs& a, hipStream_t stream) {
-  dim3 grid(a.B * ((a.H + 3) / 4), ceil_div(a.Tq, 32));
-  if (a.wl_qsent) grid = dim3((unsigned)(qtile_bound(a.B, a.Nq, a.Tq) * ((a.H + 3) / 4)), 1);
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, grid, dim3(kThreads), tile_smem<DH>(), stream, a);
+int fwd_launch(const AttnArgs& a0, hipStream_t stream) {
+  AttnArgs a = a0;
+  a.vgx = a.B * ((a.H + 3) / 4);
+  a.vgy = ceil_div(a.Tq, 32);
+  if (a.wl_qsent) {
+    a.vgx = (int)(qtile_bound(a.B, a.Nq, a.Tq) * ((a.H + 3) / 4));
+    a.vgy = 1;
+  }
+  static int resident = 0;  // (per head size: the function is a template)
+  if (!resident)
+    if (int rc = resident_blocks(attn_fwd_kernel<DH>, kThreads, tile_smem<DH>(), &resident)) return rc;
+  const int64_t total = (int64_t)a.vgx * a.vgy;
+  NMT_REQUIRE(total < (1ll << 31), "attention_fwd: too many work items");
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(total < resident ? total : resident)), dim3(kThreads), tile_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -600,7 +648,14 @@ int fused_launch(const AttnArgs& a, int n_k_rows, hipStream_t stream) {
   if (int rc = allow_big_lds(attn_bwd_fused_kernel<DH, NT>, smem)) return rc;
   const int64_t n = a.wl_sent ? class_bound(a.B, a.Nq, n_k_rows, NT - 1) : a.B;
   if (n == 0) return NMT_OK;
-  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3((unsigned)(n * ((a.H + kWaves - 1) / kWaves))), dim3(64 * kWaves), smem, stream, a);
+  AttnArgs b = a;
+  b.vgx = (int)(n * ((a.H + kWaves - 1) / kWaves));
+  b.vgy = 1;
+  static int resident = 0;
+  if (NT > 2) resident = b.vgx;  // one item per work-group
+  if (!resident)
+    if (int rc = resident_blocks(attn_bwd_fused_kernel<DH, NT>, 64 * kWaves, smem, &resident)) return rc;
+  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3((unsigned)(b.vgx < resident ? b.vgx : resident)), dim3(64 * kWaves), smem, stream, b);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
