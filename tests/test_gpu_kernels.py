@@ -136,6 +136,15 @@ def test_gemm_persistent_form_matches_oracle_and_the_tile_per_work_group_form():
     for a, b2 in zip(got["0"], got["2"]):
         assert torch.isfinite(a).all()
         assert torch.equal(a.view(torch.int16), b2.view(torch.int16))
+    # contractions shorter than one k-tile, and not a multiple of it: the requests that run ahead into the
+    # next tile then lie partly or wholly past k
+    for K2 in (8, 40, 136):
+        x2, W2 = f16(rng.normal(size=(M, K2))), f16(rng.normal(size=(N, K2)) / 4)
+        A.nmt_op_gemm(dev16(x2), 0, K2, dev16(W2), 0, K2, dC, N, M, N, K2, bias=db)
+        assert_close16(host(dC), O.linear_fwd(x2, W2, b), f"persistent, k={K2}")
+        Wt2 = f16(rng.normal(size=(K2, N)) / 4)
+        A.nmt_op_gemm(dev16(x2), 0, K2, dev16(Wt2), 1, N, dC, N, M, N, K2)
+        assert_close16(host(dC), x2 @ Wt2, f"persistent, k-major B, k={K2}")
 
 
 def test_gemm_epilogues_match_oracle():
