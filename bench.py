@@ -52,26 +52,28 @@ def model_flops_packed(model, src_lens, tgt_lens):
 
 
 def gemm_shapes(model, Ns, Nt):
-    """(M, N, K, a_t, b_t, count) of every GEMM launch of one forward + backward pass over Ns source
-    and Nt target positions."""
+    """(M, N, K, a_t, b_t, count, epilogue) of every GEMM of one forward + backward pass over Ns source and
+    Nt target positions.  epilogue: what the step's kernel does besides the product, because it decides
+    which kernel form runs: "bias" / "bias_relu" (forward), "none", "add" (an input gradient that adds the
+    gradient arriving over the residual branch, or the encoder-output gradient of the previous layer),
+    "relu_mask" (the input gradient through the ReLU)."""
     d, F, V, Le, Ld = model["d_model"], model["d_ff"], model["vocab"], model["enc_layers"], model["dec_layers"]
     out = []
 
-    def linear(N, n_in, n_out, count, wgrad=True, dgrad=True):
-        out.append((N, n_out, n_in, 0, 0, count))                 # y = x W^T
-        if dgrad:
-            out.append((N, n_in, n_out, 0, 1, count))             # dx = dy W
-        if wgrad:
-            out.append((n_out, n_in, N, 1, 1, count))             # dW = dy^T x
+    def linear(N, n_in, n_out, count, fwd="bias", dgrad="add"):
+        out.append((N, n_out, n_in, 0, 0, count, fwd))              # y = x W^T + b
+        out.append((N, n_in, n_out, 0, 1, count, dgrad))            # dx = dy W
+        out.append((n_out, n_in, N, 1, 1, count, "none"))           # dW = dy^T x
 
     for N, L in ((Ns, Le), (Nt, Ld)):
-        linear(N, d, 3 * d, L)
-        linear(N, d, d, L)
-        linear(N, d, F, L)
-        linear(N, F, d, L)
-    linear(Nt, d, d, 2 * Ld)          # cross-attention query and output projections
-    linear(Ns, d, 2 * d, Ld)          # cross-attention key/value projection
-    linear(Nt, d, V, 1)               # vocabulary projection
+        linear(N, d, 3 * d, L)                                      # q, k, v
+        linear(N, d, d, L, dgrad="none")                            # attention output projection
+        linear(N, d, F, L, fwd="bias_relu")                         # feed-forward, first layer
+        linear(N, F, d, L, dgrad="relu_mask")                       # feed-forward, second layer
+    linear(Nt, d, d, Ld)                                            # cross-attention queries
+    linear(Nt, d, d, Ld, dgrad="none")                              # cross-attention output projection
+    linear(Ns, d, 2 * d, Ld)                                        # cross-attention keys and values
+    linear(Nt, d, V, 1, fwd="none", dgrad="none")                   # vocabulary projection
     return out
 
 
@@ -272,8 +274,8 @@ def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
     each): algorithmic FLOPs / summed average durations = achieved rate of the GEMM kernel."""
     agg = {}
     for s in pass_rows:
-        for (M, N, K, a_t, b_t, count) in gemm_shapes(model, *s):
-            key = (M, N, K, a_t, b_t)
+        for (M, N, K, a_t, b_t, count, epi) in gemm_shapes(model, *s):
+            key = (M, N, K, a_t, b_t, epi)
             agg[key] = agg.get(key, 0) + count
     tot_flops = tot_ms = 0.0
     n_launch = 0
@@ -281,7 +283,7 @@ def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
     per_kind = {}
     cache = {}
     partial = torch.empty(16 << 20, dtype=torch.float32, device="cuda")   # the step's partial-sum scratch size
-    for (M, N, K, a_t, b_t), count in agg.items():
+    for (M, N, K, a_t, b_t, epi), count in agg.items():
         rows_a, cols_a = (K, M) if a_t else (M, K)
         rows_b, cols_b = (K, N) if b_t else (N, K)
         bufs = cache.get((rows_a, cols_a, rows_b, cols_b, M, N))
@@ -293,8 +295,12 @@ def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
         a, b, c = bufs
         if a_t and b_t:   # weight gradient: as in the step, the library may cut the contraction into pieces (fp32 partial sums)
             ms = _timed(torch, lambda: A.nmt_op_gemm_splitk(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K, partial, 0), 10)
-        else:
-            ms = _timed(torch, lambda: A.nmt_op_gemm(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K), 10)
+        else:             # with the epilogue the step uses for this product
+            bias = torch.zeros(N, device="cuda", dtype=torch.float16) if epi.startswith("bias") else None
+            other = torch.randn(M, N, device="cuda", dtype=torch.float16) if epi in ("add", "relu_mask") else None
+            ms = _timed(torch, lambda: A.nmt_op_gemm(a, a_t, cols_a, b, b_t, cols_b, c, N, M, N, K, bias, epi == "bias_relu", None,
+                                                      other if epi == "add" else None, other if epi == "relu_mask" else None), 10)
+            del other
         fl = 2.0 * M * N * K
         tot_flops += fl * count
         tot_ms += ms * count

@@ -366,6 +366,27 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   constexpr int QC = SW / 4;    // 16-byte chunks per staged row (8, 16 or 32)
   auto swz = [](int row, int chunk) { return QC >= 16 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7)); };
   const GemmEpilogue& ep = g.ep;
+  // The addend (or the ReLU mask source) of the wave's whole share is requested up front, into registers
+  // the fragments no longer need, so that its latency is paid once and behind the staging of the first rows
+  // rather than once per 32 rows.  (Reading it all before any store is also what lets it alias C.)
+  constexpr int kPre = TM * (WN / SW) * (CH / 2);
+  constexpr bool PRELOAD = kPre <= 16;
+  const half_t* pre_src = ep.add ? ep.add : ep.relu_src;
+  half8_t pre[PRELOAD ? kPre : 1];
+  if constexpr (PRELOAD) {
+    if (pre_src && !g.partial) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jg = 0; jg < WN / SW; ++jg)
+#pragma unroll
+          for (int it = 0; it < CH / 2; ++it) {
+            const int q = it * 64 + lane;
+            const int gr = m0 + wm * WM + i * 32 + q / CH, gc = n0 + wn * WN + jg * SW + (q % CH) * 8;
+            pre[(i * (WN / SW) + jg) * (CH / 2) + it] = (gr < g.M && gc < g.N) ? ld_half8(pre_src + (size_t)gr * g.ldc + gc) : zero_half8();
+          }
+    }
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -417,12 +438,16 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
           }
           const size_t off = (size_t)gr * g.ldc + gc;
           if (ep.add) {
-            const half8_t a = ld_half8(ep.add + off);
+            half8_t a;
+            if constexpr (PRELOAD) a = pre[(i * (WN / SW) + jg) * (CH / 2) + it];
+            else a = ld_half8(ep.add + off);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += (float)a[e];
           }
           if (ep.relu_src) {
-            const half8_t h = ld_half8(ep.relu_src + off);
+            half8_t h;
+            if (PRELOAD && !ep.add) h = pre[(i * (WN / SW) + jg) * (CH / 2) + it];
+            else h = ld_half8(ep.relu_src + off);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = ((float)h[e] > 0.f) ? v[e] * ep.mask_scale : 0.f;
           }
