@@ -854,6 +854,7 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
       pg.tiles_m = ceil_div(M, 256);
       pg.tiles_n = ceil_div(N, 256);
       pg.group_m = (pg.tiles_n >= 12 && pg.tiles_n <= 16) ? 16 : 8;
+      if (const char* e = getenv("NMT_GEMM_GROUP")) pg.group_m = atoi(e) > 0 ? atoi(e) : pg.group_m;
       pg.partial = nullptr;
       if (!b_t) hipLaunchKernelGGL((gemm_persistent_kernel<false, false, 64, 2>), dim3(256), dim3(512), 0, stream, pg);
       else hipLaunchKernelGGL((gemm_persistent_kernel<false, true, 32, 4>), dim3(256), dim3(512), 0, stream, pg);
