@@ -266,7 +266,7 @@ def phase_leg(sess, tr, dbatches, ntoks, torch):
 # HBM-side bytes per product of the default workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated against
 # kernels of known size; profiles/bench_big_accum_gemm_hbm_traffic.txt): 160.8 GB per update over 201 products,
 # for 87.4 GB of algorithmic operand + result bytes.
-MEASURED_GEMM_TRAFFIC = {"bytes_per_launch": 800e6, "algorithmic_bytes_per_launch": 435e6, "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
+MEASURED_GEMM_TRAFFIC = {"bytes_per_launch": 737e6, "algorithmic_bytes_per_launch": 435e6, "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
 
 
 def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
