@@ -147,6 +147,44 @@ def test_gemm_persistent_form_matches_oracle_and_the_tile_per_work_group_form():
         assert_close16(host(dC), x2 @ Wt2, f"persistent, k-major B, k={K2}")
 
 
+def test_gemm_tile_order_changes_no_bit():
+    """The order in which work-groups take the tiles (rows walked in groups, runs of tiles per XCD, runs of
+    (k-split, tile) pairs) only decides who computes what: for any group size every tile is written exactly
+    once and holds the same bits.  Ragged 130 x 17 tiles (persistent and tile-per-work-group form) and a
+    weight gradient cut along k."""
+    import os
+    rng = np.random.default_rng(31)
+    M, N, K = 826 * 40 + 8, 4104, 72
+    dx, dW = dev16(f16(rng.normal(size=(M, K)))), dev16(f16(rng.normal(size=(N, K)) / 8))
+    Mw, Nw, Kw = 2048, 2040, 1500
+    dAw, dBw = dev16(f16(rng.normal(size=(Kw, Mw)))), dev16(f16(rng.normal(size=(Kw, Nw)) / 32))
+    part = torch.empty(3 * Mw * Nw, dtype=torch.float32, device=DEV)
+
+    def run():
+        outs = []
+        for persist in ("0", "1"):
+            os.environ["NMT_GEMM_PERSIST"] = persist
+            c = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+            A.nmt_op_gemm(dx, 0, K, dW, 0, K, c, N, M, N, K)
+            outs.append(c)
+        c = torch.full((Mw, Nw), float("nan"), dtype=torch.float16, device=DEV)
+        A.nmt_op_gemm_splitk(dAw, 1, Mw, dBw, 1, Nw, c, Nw, Mw, Nw, Kw, part, 3)
+        outs.append(c)
+        return outs
+
+    try:
+        ref = run()                                   # the built-in group size
+        assert all(torch.isfinite(c).all() for c in ref)
+        assert torch.equal(ref[0].view(torch.int16), ref[1].view(torch.int16))
+        for group in ("1", "3", "16", "200"):         # 200: more rows per group than there are tile rows
+            os.environ["NMT_GEMM_GROUP"] = group
+            for a, b in zip(ref, run()):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), group
+    finally:
+        os.environ.pop("NMT_GEMM_GROUP", None)
+        os.environ.pop("NMT_GEMM_PERSIST", None)
+
+
 def test_gemm_epilogues_match_oracle():
     rng = np.random.default_rng(5)
     M, N, K, n_pos = 3 * 50, 256, 64, 50
