@@ -89,6 +89,10 @@ def load():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1806_00187_amd.build`")
+        # torch first: the library then binds to the HIP runtime torch has already loaded, the one that owns
+        # the tensors' memory and streams (loaded the other way round, the process ends up with two runtimes
+        # and the library's own sees no device)
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(lib, name)
