@@ -10,14 +10,25 @@ Adam with the warmup / inverse-sqrt learning-rate schedule (model section).
 It shares no code with the HIP library and imports nothing from it.  Only tests,
 the smoke check and the benchmark's CPU-baseline leg may import this module.
 
-All arithmetic is float64; logs are natural.  fp16 *storage* is emulated only where it
-decides the overflow predicate (per-micro-batch gradients rounded to fp16 before
-they are accumulated in wide precision).
+All arithmetic is float64; logs are natural.  Two precisions of the forward / backward pass:
+  * storage="fp64" (default): every tensor stays float64; fp16 *storage* is emulated only where
+    it decides the overflow predicate (per-micro-batch gradients rounded to fp16 before they
+    are accumulated in wide precision).  This is the form the finite-difference and autograd
+    pins check.
+  * storage="fp16": the precision "Half-Precision Training" states -- all forward-backward
+    computations in FP16, the loss in FP32.  Every tensor one operator hands to the next
+    (embedding output, each projection's output, attention probabilities and output, each
+    LayerNorm output, logits, and every activation gradient on the way back) is rounded to IEEE
+    binary16 (nearest even) where it is produced; sums inside an operator (dot products,
+    softmax and LayerNorm statistics, the loss) stay wide.  Binary decisions taken by floating
+    point (the ReLU gates) are thereby taken on fp16 values, as the method takes them.
 
 Parity pins (tests/test_oracle_*.py): finite differences of the loss, an independent
 torch-autograd model, accumulation equality, padding invariance, loss-scale
 invariance, closed forms of the label-smoothed loss, LayerNorm identities, Adam and
-schedule closed forms, Philox known-answer vectors.
+schedule closed forms, Philox known-answer vectors; for storage="fp16": the rounding function
+against hand-computed binary16 neighbours, every stored tensor exactly representable, identical
+results to the fp64 form when nothing needs rounding, and closeness to the fp64 form.
 """
 from __future__ import annotations
 
@@ -155,13 +166,17 @@ def _merge_heads(x):
     return x.transpose(0, 2, 1, 3).reshape(B * T, h * dh)
 
 
-def attention_fwd(q, k, v, masked, B, Tq, Tk, h):
-    """q [B*Tq,d], k,v [B*Tk,d]; masked: bool [B,Tq,Tk], True = this key may not be seen."""
+def attention_fwd(q, k, v, masked, B, Tq, Tk, h, stored=None):
+    """q [B*Tq,d], k,v [B*Tk,d]; masked: bool [B,Tq,Tk], True = this key may not be seen.
+    stored: rounding applied to the probabilities where they are handed to the product with V
+    (None: none)."""
     dh = q.shape[1] // h
     qh, kh, vh = _split_heads(q, B, Tq, h), _split_heads(k, B, Tk, h), _split_heads(v, B, Tk, h)
     a = qh @ kh.transpose(0, 1, 3, 2) / math.sqrt(dh)
     a = np.where(masked[:, None, :, :], -np.inf, a)
     p = softmax_rows(a)
+    if stored is not None:
+        p = stored(p)
     o = p @ vh
     return _merge_heads(o), (qh, kh, vh, p)
 
@@ -218,18 +233,40 @@ def _drop(x, keep, p):
     return x * keep / (1.0 - float(np.float32(p)))
 
 
+def fp16_round(x):
+    """IEEE binary16 round-to-nearest-even of every element (|x| >= 65520 -> +-inf), widened again."""
+    with np.errstate(over="ignore"):
+        return np.asarray(x).astype(np.float16).astype(np.float64)
+
+
+def _identity(x):
+    return x
+
+
+def _stored(storage: str):
+    """What happens to a tensor where one operator hands it to the next."""
+    if storage == "fp64":
+        return _identity
+    if storage == "fp16":
+        return fp16_round
+    raise ValueError(f"storage must be 'fp64' or 'fp16', not {storage!r}")
+
+
 def _sublayer_out(resid, sub, keep, p, gamma, beta, eps):
     """x <- LayerNorm(x + Dropout(Sublayer(x))): normalisation after the residual."""
     return layernorm_fwd(resid + _drop(sub, keep, p), gamma, beta, eps)
 
 
 def forward_loss(P, cfg: Config, src, tgt_in, tgt_out, *, training=True, step=0, micro=0,
-                 sent_uid=None):
+                 sent_uid=None, storage="fp64"):
     """One forward pass and the (unscaled) label-smoothed loss.
 
     P: dict name -> float64 array (values of the fp16 weights).  src [B,S], tgt_in / tgt_out
-    [B,T]: int ids, right-padded with cfg.pad_id.  Returns (loss_sum in nats, n_tok, cache).
+    [B,T]: int ids, right-padded with cfg.pad_id.  storage: "fp64", or "fp16" to round every
+    tensor handed from one operator to the next to binary16 ("Half-Precision Training"; see the
+    module header).  Returns (loss_sum in nats, n_tok, cache); backward() follows the cache's mode.
     """
+    st = _stored(storage)
     src, tgt_in, tgt_out = (np.asarray(a, dtype=np.int64) for a in (src, tgt_in, tgt_out))
     B, S = src.shape
     T = tgt_in.shape[1]
@@ -243,7 +280,8 @@ def forward_loss(P, cfg: Config, src, tgt_in, tgt_out, *, training=True, step=0,
 
     E = P["embed"]
     cache = {"B": B, "S": S, "T": T, "src": src, "tgt_in": tgt_in, "tgt_out": tgt_out,
-             "p_res": p_res, "p_act": p_act, "enc": [], "dec": []}
+             "p_res": p_res, "p_act": p_act, "enc": [], "dec": [], "storage": storage}
+    att_st = None if storage == "fp64" else st
 
     src_pad = (src == cfg.pad_id)                                    # [B,S]
     tgt_pad = (tgt_in == cfg.pad_id)                                 # [B,T]
@@ -254,122 +292,136 @@ def forward_loss(P, cfg: Config, src, tgt_in, tgt_out, *, training=True, step=0,
 
     # ---- encoder -----------------------------------------------------------------
     k_es = keep(SITE_EMB_SRC, S, d, p_res)
-    x = _drop(math.sqrt(d) * E[src.reshape(-1)] + np.tile(positional_encoding(S, d), (B, 1)), k_es, p_res)
+    x = st(_drop(math.sqrt(d) * E[src.reshape(-1)] + np.tile(positional_encoding(S, d), (B, 1)), k_es, p_res))
     cache["keep_emb_src"] = k_es
     for l in range(Le):
         pre = f"enc{l}."
         c = {"x_in": x}
-        qkv = linear_fwd(x, P[pre + "attn.wqkv"], P[pre + "attn.bqkv"])
-        o, c["attn"] = attention_fwd(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], enc_mask, B, S, S, h)
+        qkv = st(linear_fwd(x, P[pre + "attn.wqkv"], P[pre + "attn.bqkv"]))
+        o, c["attn"] = attention_fwd(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], enc_mask, B, S, S, h, att_st)
+        o = st(o)
         c["o"] = o
-        s1 = linear_fwd(o, P[pre + "attn.wo"], P[pre + "attn.bo"])
+        s1 = st(linear_fwd(o, P[pre + "attn.wo"], P[pre + "attn.bo"]))
         c["keep1"] = keep(layer_site(l, KIND_SELF_RES), S, d, p_res)
         x1, c["ln1"] = _sublayer_out(x, s1, c["keep1"], p_res, P[pre + "ln1.g"], P[pre + "ln1.b"], cfg.ln_eps)
+        x1 = st(x1)
         c["x1"] = x1
         hpre = linear_fwd(x1, P[pre + "ffn.w1"], P[pre + "ffn.b1"])
         c["keep_act"] = keep(layer_site(l, KIND_FFN_ACT), S, cfg.d_ff, p_act)
-        hact = _drop(np.maximum(hpre, 0.0), c["keep_act"], p_act)
+        c["relu"] = st(np.maximum(hpre, 0.0))      # what the gate of the backward pass looks at
+        hact = st(_drop(np.maximum(hpre, 0.0), c["keep_act"], p_act))
         c["hpre"], c["hact"] = hpre, hact
-        s2 = linear_fwd(hact, P[pre + "ffn.w2"], P[pre + "ffn.b2"])
+        s2 = st(linear_fwd(hact, P[pre + "ffn.w2"], P[pre + "ffn.b2"]))
         c["keep2"] = keep(layer_site(l, KIND_FFN_RES), S, d, p_res)
         x, c["ln2"] = _sublayer_out(x1, s2, c["keep2"], p_res, P[pre + "ln2.g"], P[pre + "ln2.b"], cfg.ln_eps)
+        x = st(x)
         cache["enc"].append(c)
     enc_out = x
     cache["enc_out"] = enc_out
 
     # ---- decoder -----------------------------------------------------------------
     k_et = keep(SITE_EMB_TGT, T, d, p_res)
-    x = _drop(math.sqrt(d) * E[tgt_in.reshape(-1)] + np.tile(positional_encoding(T, d), (B, 1)), k_et, p_res)
+    x = st(_drop(math.sqrt(d) * E[tgt_in.reshape(-1)] + np.tile(positional_encoding(T, d), (B, 1)), k_et, p_res))
     cache["keep_emb_tgt"] = k_et
     for l in range(Ld):
         pre = f"dec{l}."
         li = Le + l
         c = {"x_in": x}
-        qkv = linear_fwd(x, P[pre + "self.wqkv"], P[pre + "self.bqkv"])
-        o, c["self"] = attention_fwd(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], self_mask, B, T, T, h)
+        qkv = st(linear_fwd(x, P[pre + "self.wqkv"], P[pre + "self.bqkv"]))
+        o, c["self"] = attention_fwd(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], self_mask, B, T, T, h, att_st)
+        o = st(o)
         c["o_self"] = o
-        s1 = linear_fwd(o, P[pre + "self.wo"], P[pre + "self.bo"])
+        s1 = st(linear_fwd(o, P[pre + "self.wo"], P[pre + "self.bo"]))
         c["keep1"] = keep(layer_site(li, KIND_SELF_RES), T, d, p_res)
         x1, c["ln1"] = _sublayer_out(x, s1, c["keep1"], p_res, P[pre + "ln1.g"], P[pre + "ln1.b"], cfg.ln_eps)
+        x1 = st(x1)
         c["x1"] = x1
-        q = linear_fwd(x1, P[pre + "cross.wq"], P[pre + "cross.bq"])
-        kv = linear_fwd(enc_out, P[pre + "cross.wkv"], P[pre + "cross.bkv"])
-        o, c["cross"] = attention_fwd(q, kv[:, :d], kv[:, d:], cross_mask, B, T, S, h)
+        q = st(linear_fwd(x1, P[pre + "cross.wq"], P[pre + "cross.bq"]))
+        kv = st(linear_fwd(enc_out, P[pre + "cross.wkv"], P[pre + "cross.bkv"]))
+        o, c["cross"] = attention_fwd(q, kv[:, :d], kv[:, d:], cross_mask, B, T, S, h, att_st)
+        o = st(o)
         c["o_cross"] = o
-        s2 = linear_fwd(o, P[pre + "cross.wo"], P[pre + "cross.bo"])
+        s2 = st(linear_fwd(o, P[pre + "cross.wo"], P[pre + "cross.bo"]))
         c["keep2"] = keep(layer_site(li, KIND_CROSS_RES), T, d, p_res)
         x2, c["ln2"] = _sublayer_out(x1, s2, c["keep2"], p_res, P[pre + "ln2.g"], P[pre + "ln2.b"], cfg.ln_eps)
+        x2 = st(x2)
         c["x2"] = x2
         hpre = linear_fwd(x2, P[pre + "ffn.w1"], P[pre + "ffn.b1"])
         c["keep_act"] = keep(layer_site(li, KIND_FFN_ACT), T, cfg.d_ff, p_act)
-        hact = _drop(np.maximum(hpre, 0.0), c["keep_act"], p_act)
+        c["relu"] = st(np.maximum(hpre, 0.0))
+        hact = st(_drop(np.maximum(hpre, 0.0), c["keep_act"], p_act))
         c["hpre"], c["hact"] = hpre, hact
-        s3 = linear_fwd(hact, P[pre + "ffn.w2"], P[pre + "ffn.b2"])
+        s3 = st(linear_fwd(hact, P[pre + "ffn.w2"], P[pre + "ffn.b2"]))
         c["keep3"] = keep(layer_site(li, KIND_FFN_RES), T, d, p_res)
         x, c["ln3"] = _sublayer_out(x2, s3, c["keep3"], p_res, P[pre + "ln3.g"], P[pre + "ln3.b"], cfg.ln_eps)
+        x = st(x)
         cache["dec"].append(c)
     cache["dec_out"] = x
 
     # ---- output projection (tied to the embedding) and loss ------------------------
-    z = x @ E.T
+    z = st(x @ E.T)
     loss_sum, n_tok, dz = label_smoothed_nll(z, tgt_out.reshape(-1), cfg.pad_id, cfg.label_smoothing)
     cache["logits"] = z
     cache["dz_unit"] = dz
     return loss_sum, n_tok, cache
 
 
-def backward(P, cfg: Config, cache, loss_scale: float, gate_flip=None):
-    """Gradient of loss_scale * loss_sum with respect to every parameter (dict of float64).
-
-    gate_flip (tests only): dict "enc0.ffn." / "dec1.ffn." ... -> bool array [N, d_ff]; the ReLU
-    gates marked True are taken the other way in this backward pass.  Used to measure how much of a
-    gradient hangs on gates whose pre-activation is too close to zero for fp16 arithmetic to decide."""
+def backward(P, cfg: Config, cache, loss_scale: float):
+    """Gradient of loss_scale * loss_sum with respect to every parameter (dict of float64), in the
+    storage mode of the forward pass that made `cache`: with "fp16" every activation gradient is
+    rounded to binary16 where one operator hands it to the next (a residual fan-in is one operator:
+    the two branches are added wide and the sum is rounded), the weight gradients are formed wide
+    from those rounded tensors (their own rounding is to_fp16_storage's business)."""
     B, S, T = cache["B"], cache["S"], cache["T"]
     d, h, Le, Ld = cfg.d_model, cfg.n_heads, cfg.enc_layers, cfg.dec_layers
     p_res, p_act = cache["p_res"], cache["p_act"]
+    st = _stored(cache.get("storage", "fp64"))
     G = {name: np.zeros_like(val) for name, val in P.items()}
     E = P["embed"]
 
-    dz = cache["dz_unit"] * loss_scale
+    dz = st(cache["dz_unit"] * loss_scale)
     G["embed"] += dz.T @ cache["dec_out"]
-    dx = dz @ E
-    d_enc_out = np.zeros_like(cache["enc_out"])
+    dx = st(dz @ E)
+    d_enc_out = None
 
     def ffn_bwd(pre, c, x_in, dsub):
-        """dsub: gradient at the FFN output (after residual dropout was undone). Returns d x_in."""
+        """dsub: gradient at the FFN output (after residual dropout was undone). Returns d x_in
+        (wide: the caller adds the residual branch before the sum is stored)."""
         dh, G[pre + "ffn.w2"], G[pre + "ffn.b2"] = linear_bwd(c["hact"], P[pre + "ffn.w2"], dsub)
-        dh = _drop(dh, c["keep_act"], p_act)
-        c["d_gate"] = dh                       # gradient arriving at the ReLU gate (kept for tests)
-        gate = c["hpre"] > 0.0
-        if gate_flip is not None and pre + "ffn." in gate_flip:
-            gate = gate ^ gate_flip[pre + "ffn."]
-        dh = dh * gate
+        dh = st(_drop(dh, c["keep_act"], p_act) * (c["relu"] > 0.0))
         dxi, G[pre + "ffn.w1"], G[pre + "ffn.b1"] = linear_bwd(x_in, P[pre + "ffn.w1"], dh)
         return dxi
+
+    def attn_bwd(c_attn, do, Tq, Tk):
+        dq, dk, dv = attention_bwd(do, c_attn, B, Tq, Tk, h)
+        return st(dq), st(dk), st(dv)
 
     for l in reversed(range(Ld)):
         pre = f"dec{l}."
         c = cache["dec"][l]
         dy, G[pre + "ln3.g"], G[pre + "ln3.b"] = layernorm_bwd(dx, P[pre + "ln3.g"], c["ln3"])
-        dx2 = dy + ffn_bwd(pre, c, c["x2"], _drop(dy, c["keep3"], p_res))
+        dy = st(dy)
+        dx2 = st(dy + ffn_bwd(pre, c, c["x2"], st(_drop(dy, c["keep3"], p_res))))
         # encoder-decoder attention
         dy, G[pre + "ln2.g"], G[pre + "ln2.b"] = layernorm_bwd(dx2, P[pre + "ln2.g"], c["ln2"])
+        dy = st(dy)
         do, G[pre + "cross.wo"], G[pre + "cross.bo"] = linear_bwd(c["o_cross"], P[pre + "cross.wo"],
-                                                                  _drop(dy, c["keep2"], p_res))
-        dq, dk, dv = attention_bwd(do, c["cross"], B, T, S, h)
+                                                                  st(_drop(dy, c["keep2"], p_res)))
+        dq, dk, dv = attn_bwd(c["cross"], st(do), T, S)
         dx1q, G[pre + "cross.wq"], G[pre + "cross.bq"] = linear_bwd(c["x1"], P[pre + "cross.wq"], dq)
         dkv = np.concatenate([dk, dv], axis=1)
         de, G[pre + "cross.wkv"], G[pre + "cross.bkv"] = linear_bwd(cache["enc_out"], P[pre + "cross.wkv"], dkv)
-        d_enc_out += de
-        dx1 = dy + dx1q
+        d_enc_out = st(de) if d_enc_out is None else st(d_enc_out + de)   # every decoder layer reads the encoder output
+        dx1 = st(dy + dx1q)
         # masked self-attention
         dy, G[pre + "ln1.g"], G[pre + "ln1.b"] = layernorm_bwd(dx1, P[pre + "ln1.g"], c["ln1"])
+        dy = st(dy)
         do, G[pre + "self.wo"], G[pre + "self.bo"] = linear_bwd(c["o_self"], P[pre + "self.wo"],
-                                                                _drop(dy, c["keep1"], p_res))
-        dq, dk, dv = attention_bwd(do, c["self"], B, T, T, h)
+                                                                st(_drop(dy, c["keep1"], p_res)))
+        dq, dk, dv = attn_bwd(c["self"], st(do), T, T)
         dqkv = np.concatenate([dq, dk, dv], axis=1)
         dxi, G[pre + "self.wqkv"], G[pre + "self.bqkv"] = linear_bwd(c["x_in"], P[pre + "self.wqkv"], dqkv)
-        dx = dy + dxi
+        dx = st(dy + dxi)
     # target embedding: x = drop(sqrt(d) E[id] + PE)
     demb = _drop(dx, cache["keep_emb_tgt"], p_res) * math.sqrt(d)
     np.add.at(G["embed"], cache["tgt_in"].reshape(-1), demb)
@@ -379,14 +431,16 @@ def backward(P, cfg: Config, cache, loss_scale: float, gate_flip=None):
         pre = f"enc{l}."
         c = cache["enc"][l]
         dy, G[pre + "ln2.g"], G[pre + "ln2.b"] = layernorm_bwd(dx, P[pre + "ln2.g"], c["ln2"])
-        dx1 = dy + ffn_bwd(pre, c, c["x1"], _drop(dy, c["keep2"], p_res))
+        dy = st(dy)
+        dx1 = st(dy + ffn_bwd(pre, c, c["x1"], st(_drop(dy, c["keep2"], p_res))))
         dy, G[pre + "ln1.g"], G[pre + "ln1.b"] = layernorm_bwd(dx1, P[pre + "ln1.g"], c["ln1"])
+        dy = st(dy)
         do, G[pre + "attn.wo"], G[pre + "attn.bo"] = linear_bwd(c["o"], P[pre + "attn.wo"],
-                                                                _drop(dy, c["keep1"], p_res))
-        dq, dk, dv = attention_bwd(do, c["attn"], B, S, S, h)
+                                                                st(_drop(dy, c["keep1"], p_res)))
+        dq, dk, dv = attn_bwd(c["attn"], st(do), S, S)
         dqkv = np.concatenate([dq, dk, dv], axis=1)
         dxi, G[pre + "attn.wqkv"], G[pre + "attn.bqkv"] = linear_bwd(c["x_in"], P[pre + "attn.wqkv"], dqkv)
-        dx = dy + dxi
+        dx = st(dy + dxi)
     demb = _drop(dx, cache["keep_emb_src"], p_res) * math.sqrt(d)
     np.add.at(G["embed"], cache["src"].reshape(-1), demb)
     return G
@@ -398,8 +452,7 @@ def backward(P, cfg: Config, cache, loss_scale: float, gate_flip=None):
 def to_fp16_storage(G):
     """Round each gradient to IEEE binary16 (nearest even; |x| >= 65520 becomes +-inf) and
     widen again: the value a 16-bit gradient buffer would hold."""
-    with np.errstate(over="ignore"):
-        return {k: v.astype(np.float16).astype(np.float64) for k, v in G.items()}
+    return {k: fp16_round(v) for k, v in G.items()}
 
 
 def accumulate(acc, g16, first: bool):
@@ -456,7 +509,7 @@ class LossScaler:
 
 
 def train_update(P16, master, m, v, cfg, micro_batches, scaler: LossScaler, t, lr, betas=(0.9, 0.98),
-                 eps=1e-8, step=None, scale_override=None):
+                 eps=1e-8, step=None, scale_override=None, storage="fp64"):
     """One weight update from k micro-batches.  Returns dict with loss, n_tok, flag and the new
     fp16 weights.  `t` is the 1-based Adam step to use if the update is applied."""
     step = t if step is None else step
@@ -464,7 +517,7 @@ def train_update(P16, master, m, v, cfg, micro_batches, scaler: LossScaler, t, l
     acc, loss_tot, ntok_tot = None, 0.0, 0
     for j, mb in enumerate(micro_batches):
         loss, ntok, cache = forward_loss(P16, cfg, mb["src"], mb["tgt_in"], mb["tgt_out"], training=True,
-                                         step=step, micro=j, sent_uid=mb.get("sent_uid"))
+                                         step=step, micro=j, sent_uid=mb.get("sent_uid"), storage=storage)
         g16 = to_fp16_storage(backward(P16, cfg, cache, S_loss))
         acc = accumulate(acc, g16, j == 0)
         loss_tot += loss

@@ -225,3 +225,111 @@ def test_update_skips_on_forced_overflow_and_applies_otherwise():
     k = "enc0.ffn.w1"
     nz = np.abs(out["grad"][k]) > 1e-6
     assert np.abs(np.abs(master[k] - snap[k])[nz] - 5e-4).max() < 1e-6
+
+
+# ---- storage="fp16": forward and backward tensors held in binary16 ("Half-Precision Training") ------
+def test_fp16_round_matches_hand_computed_binary16_neighbours():
+    u = 2.0 ** -10                     # spacing of binary16 in [1, 2)
+    cases = [(1.0 + u / 2, 1.0),                       # tie -> even mantissa
+             (1.0 + u / 2 + 2.0 ** -30, 1.0 + u),      # just above the tie
+             (1.0 + 3 * u / 2, 1.0 + 2 * u),           # tie -> even mantissa (upwards)
+             (1.0 + u / 4, 1.0), (0.1, 0.0999755859375),
+             (65504.0, 65504.0), (65519.9, 65504.0), (65520.0, np.inf),
+             (2.0 ** -24, 2.0 ** -24),                 # smallest subnormal
+             (2.0 ** -25, 0.0),                        # tie between 0 and the smallest subnormal -> 0
+             (2.0 ** -25 * 1.001, 2.0 ** -24), (3 * 2.0 ** -25, 2.0 ** -23)]
+    x = np.array([c[0] for c in cases])
+    want = np.array([c[1] for c in cases])
+    assert (O.fp16_round(x) == want).all()
+    assert (O.fp16_round(-x) == -want).all()
+
+
+def _all_arrays(obj):
+    if isinstance(obj, np.ndarray) and obj.dtype == np.float64:
+        yield obj
+    elif isinstance(obj, dict):
+        for v in obj.values():
+            yield from _all_arrays(v)
+    elif isinstance(obj, (list, tuple)):
+        for v in obj:
+            yield from _all_arrays(v)
+
+
+def test_fp16_storage_holds_every_handed_over_tensor_in_binary16():
+    cfg, P, batch = _setup(dropout=0.2, act_dropout=0.1, B=6, S=9, T=8)
+    P = {k: O.fp16_round(v) for k, v in P.items()}
+    _, _, cache = O.forward_loss(P, cfg, **batch, step=1, storage="fp16")
+    handed = ["x_in", "o", "o_self", "o_cross", "x1", "x2", "hact", "relu"]
+    n = 0
+    for side in ("enc", "dec"):
+        for c in cache[side]:
+            for key in handed:
+                if key in c:
+                    assert (O.fp16_round(c[key]) == c[key]).all(), (side, key)
+                    n += 1
+            for key in ("attn", "self", "cross"):
+                if key in c:   # q, k, v heads and the probabilities
+                    assert all((O.fp16_round(a) == a).all() for a in c[key]), (side, key)
+    assert n == 2 * 5 + 2 * 7
+    for key in ("enc_out", "dec_out", "logits"):
+        assert (O.fp16_round(cache[key]) == cache[key]).all(), key
+    # what is summed inside an operator stays wide: pre-activations and LayerNorm's normalised rows
+    assert not (O.fp16_round(cache["enc"][0]["hpre"]) == cache["enc"][0]["hpre"]).all()
+    assert not (O.fp16_round(cache["enc"][0]["ln1"][0]) == cache["enc"][0]["ln1"][0]).all()
+    # ... and the fp64 form rounds nothing
+    _, _, wide = O.forward_loss(P, cfg, **batch, step=1)
+    assert not (O.fp16_round(wide["dec_out"]) == wide["dec_out"]).all()
+
+
+def test_fp16_storage_differs_from_fp64_form_by_the_roundings_only(monkeypatch):
+    """With the rounding function replaced by the identity the fp16 form must reproduce the fp64
+    form bit for bit: it adds roundings, no other arithmetic."""
+    cfg, P, batch = _setup(dropout=0.2, act_dropout=0.1, B=5, S=8, T=9)
+    loss, ntok, cache = O.forward_loss(P, cfg, **batch, step=4, micro=2)
+    G = O.backward(P, cfg, cache, 64.0)
+    monkeypatch.setattr(O, "fp16_round", lambda x: np.asarray(x, dtype=np.float64))
+    loss2, ntok2, cache2 = O.forward_loss(P, cfg, **batch, step=4, micro=2, storage="fp16")
+    G2 = O.backward(P, cfg, cache2, 64.0)
+    assert loss2 == loss and ntok2 == ntok
+    for k in G:
+        assert (G2[k] == G[k]).all(), k
+
+
+def test_fp16_storage_stays_close_to_the_fp64_form():
+    """binary16 keeps 11 significant bits: loss and gradients move by fractions of a percent, not more
+    (a misplaced or doubled rounding, or a rounding of a sum that must stay wide, shows up here)."""
+    model = dict(enc_layers=2, dec_layers=2, d_model=64, n_heads=4, d_ff=128, vocab=200)
+    cfg, P, batch = _setup(dropout=0.1, B=16, S=12, T=11, model=model)
+    P = {k: O.fp16_round(v) for k, v in P.items()}
+    loss, ntok, cache = O.forward_loss(P, cfg, **batch, step=1)
+    G = O.backward(P, cfg, cache, 128.0)
+    loss16, ntok16, cache16 = O.forward_loss(P, cfg, **batch, step=1, storage="fp16")
+    G16 = O.backward(P, cfg, cache16, 128.0)
+    assert ntok16 == ntok and abs(loss16 - loss) / loss < 1e-3
+    d = cfg.d_model
+    for k in G:
+        a, b = G16[k], G[k]
+        if k.endswith("bqkv"):       # the key-bias third is zero in exact arithmetic
+            a, b = np.delete(a, slice(d, 2 * d)), np.delete(b, slice(d, 2 * d))
+        elif k.endswith("bkv"):
+            a, b = a[d:], b[d:]
+        assert np.linalg.norm(a - b) <= 3e-2 * np.linalg.norm(b), (k, np.linalg.norm(a - b) / np.linalg.norm(b))
+    # gates are decided on the stored (rounded) activation
+    c = cache16["dec"][0]
+    assert ((c["relu"] > 0) == (O.fp16_round(np.maximum(c["hpre"], 0.0)) > 0)).all()
+
+
+def test_fp16_storage_overflow_in_an_activation_gradient_reaches_the_flag():
+    """A loss scale so large that the gradient at the logits leaves the binary16 range: the inf / NaN it
+    turns into must arrive in the weight gradients and set the overflow flag (scaler halves, update skipped)."""
+    cfg, P, batch = _setup(dropout=0.1)
+    master = {k: v.copy() for k, v in P.items()}
+    m = {k: np.zeros_like(v) for k, v in P.items()}
+    v = {k: np.zeros_like(val) for k, val in P.items()}
+    scaler = O.LossScaler(128.0)
+    with np.errstate(invalid="ignore", over="ignore"):
+        out = O.train_update(P, master, m, v, cfg, [batch], scaler, t=1, lr=5e-4, scale_override=128.0 * 2 ** 20, storage="fp16")
+    assert out["flag"] == 1 and scaler.scale == 64.0
+    assert all((master[k] == P[k]).all() for k in master)
+    out = O.train_update(P, master, m, v, cfg, [batch], scaler, t=1, lr=5e-4, storage="fp16")
+    assert out["flag"] == 0
