@@ -43,6 +43,8 @@ typedef struct {
   int32_t pad_id;                 /* id of the padding symbol                              */
   float dropout;                  /* on each sub-layer output before the residual add, and
                                      on the embedding + position sum                       */
+  float attn_dropout;             /* on the attention probabilities: not built, must be 0
+                                     (nmt_create returns NMT_EINVAL otherwise)             */
   float act_dropout;              /* after the ReLU of the feed-forward layer              */
   float label_smoothing;          /* weight of the uniform prior over the vocabulary       */
   float ln_eps;                   /* variance floor of layer normalisation                 */
@@ -78,7 +80,8 @@ int nmt_bind(nmt_ctx* ctx, void* d_w16, void* d_g16, float* d_master32, float* d
  * Hyperparameters", "Half-Precision Training").  d_src [B,S], d_tgt_in [B,T], d_tgt_out [B,T]:
  * int32 ids right-padded with pad_id; every sentence has at least one token.
  * The gradient of loss_scale * (sum of token losses) with respect to the logits is left in
- * the workspace for nmt_backward ("scale the loss right after the forward pass").
+ * the workspace for nmt_backward: the loss is scaled at the end of the forward pass, before any
+ * fp16 gradient exists ("Half-Precision Training").
  * step (< 2^24) and micro_idx (< 256) select the dropout streams; d_sent_uid [B] (uint32, may
  * be NULL = row index) names each sentence so its dropout mask does not depend on batching.
  * training == 0 disables dropout.
@@ -132,12 +135,18 @@ int nmt_forward_loss_packed(nmt_ctx* ctx, int32_t n_sent, const nmt_sentence* d_
 
 /* Backward pass in fp16 of the last nmt_forward_loss / nmt_forward_loss_group /
  * nmt_forward_loss_packed; writes every element of g16 with nmt_grad_scale(ctx) times the gradient
- * of loss_scale * loss_sum ("perform the backward pass as usual"). */
+ * of loss_scale * loss_sum.  Nothing in it knows about the scale: it is an ordinary reverse pass over
+ * fp16 tensors ("Half-Precision Training"). */
 int nmt_backward(nmt_ctx* ctx, void* stream);
 
 /* Gradient accumulation over sub-batches ("Training with Larger Batches"):
  * first != 0: acc32 = float(g16) / s; else acc32 += float(g16) / s, where s = nmt_grad_scale(ctx). */
 int nmt_accumulate(nmt_ctx* ctx, int32_t first, void* stream);
+
+/* Running totals over the sub-batches of one update, kept on the device so that the caller's loop needs no
+ * host arithmetic: adds the loss sum and token count the last forward call wrote (its d_loss_sum / d_ntok)
+ * to *d_loss_total / *d_ntok_total (first != 0: overwrites them).  Call after the forward call, on its stream. */
+int nmt_accumulate_loss(nmt_ctx* ctx, int32_t first, float* d_loss_total, int32_t* d_ntok_total, void* stream);
 
 /* The power-of-two factor s <= 1 by which the last forward call's pass scales what it writes to g16:
  * g16 = fp16(s * gradient of loss_scale * loss_sum).  s = 1 for passes of fewer than 8192 target
@@ -152,9 +161,10 @@ float nmt_grad_scale(const nmt_ctx* ctx);
  * content is meaningless when the flag is set). */
 int nmt_check_overflow(nmt_ctx* ctx, float inv_scale, int32_t* d_flag, void* stream);
 
-/* Adam on the fp32 master weights with gradient acc32, then w16 = round-to-nearest-even of the
- * new master weights.  t is the 1-based update count.  If *d_flag != 0 the call changes
- * nothing (the update is skipped on overflow). */
+/* Adam ("Models and Hyperparameters": beta1 0.9, beta2 0.98, epsilon 1e-8) on the fp32 master weights
+ * with gradient acc32 -- the optimizer runs in fp32 ("Half-Precision Training") -- then w16 =
+ * round-to-nearest-even of the new master weights.  t is the 1-based update count.  If *d_flag != 0 the
+ * call changes nothing (the update is skipped on overflow). */
 int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, float eps, int32_t t,
                   const int32_t* d_flag, void* stream);
 
@@ -163,9 +173,26 @@ int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, float eps, i
  * reaches `window` (2000 in the paper) scale *= 2, clean = 0.  Returns NMT_EINVAL if the scale
  * would fall below 2^-14. */
 int nmt_scaler_update(float* scale /*host*/, int32_t* clean /*host*/, int32_t overflow, int32_t window);
-/* Learning rate of update t (1-based): linear warm-up to `peak` over `warmup` updates, then
- * proportional to the inverse square root of t. */
+/* Learning rate of update t (1-based) as in "Models and Hyperparameters": linear warm-up to `peak`
+ * (5e-4, or 1e-3 with large batches) over `warmup` (4000) updates, then proportional to the inverse
+ * square root of t. */
 double nmt_lr_schedule(int64_t t, double peak, int64_t warmup);
+
+/* Host only.  Debug export for the parity tests: the place, inside the caller's workspace, of an activation the
+ * last forward call saved for its backward pass.  name: "enc<l>.ffn.h" / "dec<l>.ffn.h" (the feed-forward
+ * hidden activation after ReLU and dropout, fp16 [rows, d_ff]; an element > 0 is an open ReLU gate) or
+ * "enc<l>.out" / "dec<l>.out" (the block's output, fp16 [rows, d_model]); rows = source / target positions of
+ * the pass, in its row order.  The memory stays the caller's; it is overwritten by the next forward call. */
+int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_ptr, int64_t* rows, int64_t* cols);
+
+/* Host only.  Process-wide switches of launch forms, for tests and profiling; none of them changes a
+ * result bit.  name: "gemm_group" (tile rows swept together, >= 1; default 4), "gemm_persist" (0 never /
+ * 1 where the epilogue loads nothing per element / 2 always the persistent GEMM form; default 1),
+ * "attn_persist" (0: one attention work item per work-group; default 1), "worklists" (0: attention
+ * kernels enumerate every (sentence, tile); default 1), "one_stream" (1: nmt_backward enqueues the weight
+ * gradients on the caller's stream; default 0), "defaults" (value ignored: all of the above back to default).
+ * Unknown names and values out of range return NMT_EINVAL. */
+int nmt_tuning(const char* name, int32_t value);
 
 /* ------------------------------------------------------------------------------------------
  * Kernel-level entry points (used by the per-kernel parity tests and by profiling).

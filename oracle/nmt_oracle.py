@@ -366,12 +366,18 @@ def forward_loss(P, cfg: Config, src, tgt_in, tgt_out, *, training=True, step=0,
     return loss_sum, n_tok, cache
 
 
-def backward(P, cfg: Config, cache, loss_scale: float):
+def backward(P, cfg: Config, cache, loss_scale: float, gates=None):
     """Gradient of loss_scale * loss_sum with respect to every parameter (dict of float64), in the
     storage mode of the forward pass that made `cache`: with "fp16" every activation gradient is
     rounded to binary16 where one operator hands it to the next (a residual fan-in is one operator:
     the two branches are added wide and the sum is rounded), the weight gradients are formed wide
-    from those rounded tensors (their own rounding is to_fp16_storage's business)."""
+    from those rounded tensors (their own rounding is to_fp16_storage's business).
+
+    gates (tests only): dict "enc0.ffn." / "dec1.ffn." ... -> bool array [N, d_ff] of ReLU decisions to
+    differentiate through instead of this pass's own (pre-activation > 0).  A gate whose pre-activation is
+    smaller than the rounding effects of reduced-precision arithmetic has no unique decision; a test that
+    compares gradients of two implementations first checks that they differ on such gates only
+    (undecided_relu_gates) and then compares the gradients for one and the same set of decisions."""
     B, S, T = cache["B"], cache["S"], cache["T"]
     d, h, Le, Ld = cfg.d_model, cfg.n_heads, cfg.enc_layers, cfg.dec_layers
     p_res, p_act = cache["p_res"], cache["p_act"]
@@ -388,7 +394,10 @@ def backward(P, cfg: Config, cache, loss_scale: float):
         """dsub: gradient at the FFN output (after residual dropout was undone). Returns d x_in
         (wide: the caller adds the residual branch before the sum is stored)."""
         dh, G[pre + "ffn.w2"], G[pre + "ffn.b2"] = linear_bwd(c["hact"], P[pre + "ffn.w2"], dsub)
-        dh = st(_drop(dh, c["keep_act"], p_act) * (c["relu"] > 0.0))
+        gate = c["relu"] > 0.0
+        if gates is not None and pre + "ffn." in gates:
+            gate = np.asarray(gates[pre + "ffn."], dtype=bool).reshape(gate.shape)
+        dh = st(_drop(dh, c["keep_act"], p_act) * gate)
         dxi, G[pre + "ffn.w1"], G[pre + "ffn.b1"] = linear_bwd(x_in, P[pre + "ffn.w1"], dh)
         return dxi
 
@@ -444,6 +453,20 @@ def backward(P, cfg: Config, cache, loss_scale: float):
     demb = _drop(dx, cache["keep_emb_src"], p_res) * math.sqrt(d)
     np.add.at(G["embed"], cache["src"].reshape(-1), demb)
     return G
+
+
+def undecided_relu_gates(P, cfg: Config, cache, width=8.0):
+    """Per feed-forward layer ("enc0.ffn." ...): bool [N, d_ff], True where the sign of the pre-activation
+    is not decided at fp16 precision: |x W1^T + b1| <= width * 2^-11 * sqrt(sum_k (x_k W1_jk)^2), i.e. within
+    `width` times the rms effect of rounding each term of the dot product to 11 significant bits (binary16
+    keeps 11; the layer input has been through that rounding at every operator before it)."""
+    out = {}
+    for side, key_x in (("enc", "x1"), ("dec", "x2")):
+        for l, c in enumerate(cache[side]):
+            pre = f"{side}{l}.ffn."
+            x, W1 = c[key_x], P[pre + "w1"]
+            out[pre] = np.abs(c["hpre"]) <= width * 2.0 ** -11 * np.sqrt((x * x) @ (W1 * W1).T)
+    return out
 
 
 # ----------------------------------------------------------------------------------------

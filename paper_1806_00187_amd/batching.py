@@ -1,5 +1,5 @@
-"""Sub-batch construction (host logic; section "Time-balanced sub-batches" of the analysis of
-stragglers).  Two rules over a population of sentence pairs sorted by length:
+"""Sub-batch construction (host logic; section "Analysis of Stragglers", the paragraph on sub-batches
+that take about the same time to process).  Two rules over a population of sentence pairs sorted by length:
 
 * token budget: as many sentences as fit B * max(S, T) <= N (the baseline rule);
 * time balance: a table estimates the processing time of a sub-batch from its number of sentences

@@ -22,7 +22,7 @@ class NmtError(RuntimeError):
 class nmt_config(C.Structure):
     _fields_ = [("enc_layers", C.c_int32), ("dec_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("pad_id", C.c_int32), ("dropout", C.c_float),
-                ("act_dropout", C.c_float), ("label_smoothing", C.c_float), ("ln_eps", C.c_float), ("seed", C.c_uint64),
+                ("attn_dropout", C.c_float), ("act_dropout", C.c_float), ("label_smoothing", C.c_float), ("ln_eps", C.c_float), ("seed", C.c_uint64),
                 ("max_sentences", C.c_int32), ("max_len", C.c_int32)]
 
 
@@ -56,6 +56,9 @@ _SIGNATURES = {
     "nmt_forward_loss_packed": (C.c_int, [_P, _I32, _P, _I64, _I64, _I32, _I32, _P, _P, _P, _F, _U32, _I32, _P, _P, _P]),
     "nmt_backward": (C.c_int, [_P, _P]),
     "nmt_accumulate": (C.c_int, [_P, _I32, _P]),
+    "nmt_accumulate_loss": (C.c_int, [_P, _I32, _P, _P, _P]),
+    "nmt_tuning": (C.c_int, [C.c_char_p, _I32]),
+    "nmt_debug_activation": (C.c_int, [_P, C.c_char_p, C.POINTER(_P), C.POINTER(_I64), C.POINTER(_I64)]),
     "nmt_check_overflow": (C.c_int, [_P, _F, _P, _P]),
     "nmt_adam_step": (C.c_int, [_P, _F, _F, _F, _F, _I32, _P, _P]),
     "nmt_scaler_update": (C.c_int, [C.POINTER(C.c_float), C.POINTER(_I32), _I32, _I32]),
@@ -227,6 +230,21 @@ def nmt_backward(ctx, stream=None):
 
 def nmt_accumulate(ctx, first, stream=None):
     _check(load().nmt_accumulate(ctx, 1 if first else 0, _stream(stream)))
+
+
+def nmt_accumulate_loss(ctx, first, loss_total, ntok_total, stream=None):
+    _check(load().nmt_accumulate_loss(ctx, 1 if first else 0, _p(loss_total), _p(ntok_total), _stream(stream)))
+
+
+def nmt_debug_activation(ctx, name):
+    """(device address, rows, cols) of a saved fp16 activation of the last forward pass."""
+    ptr, rows, cols = C.c_void_p(), C.c_int64(), C.c_int64()
+    _check(load().nmt_debug_activation(ctx, name.encode(), C.byref(ptr), C.byref(rows), C.byref(cols)))
+    return ptr.value, rows.value, cols.value
+
+
+def nmt_tuning(name, value=0):
+    _check(load().nmt_tuning(name.encode(), int(value)))
 
 
 def nmt_check_overflow(ctx, inv_scale, flag, stream=None):

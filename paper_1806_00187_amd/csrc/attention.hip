@@ -613,13 +613,9 @@ int64_t class_bound(int n_sent, int n_q_rows, int n_k_rows, int c) {
 // Work-groups of `kern` that the device holds at once (occupancy x compute units): the grid of a persistent launch.
 template <typename Kern>
 int resident_blocks(Kern kern, int threads, size_t smem, int* out) {
-  int per_cu = 0, dev = 0, cus = 0;
+  int per_cu = 0;
   NMT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), threads, smem));
-  NMT_HIP_CHECK(hipGetDevice(&dev));
-  NMT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  *out = (per_cu > 0 ? per_cu : 1) * (cus > 0 ? cus : 1);
-  if (const char* e = getenv("NMT_ATTN_PERSIST"))  // tuning aid: 0 = one work item per work-group
-    if (!atoi(e)) *out = 0x7fffffff;
+  *out = (per_cu > 0 ? per_cu : 1) * device_info().cus;
   return NMT_OK;
 }
 
@@ -637,7 +633,8 @@ int fwd_launch(const AttnArgs& a0, hipStream_t stream) {
     if (int rc = resident_blocks(attn_fwd_kernel<DH>, kThreads, tile_smem<DH>(), &resident)) return rc;
   const int64_t total = (int64_t)a.vgx * a.vgy;
   NMT_REQUIRE(total < (1ll << 31), "attention_fwd: too many work items");
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(total < resident ? total : resident)), dim3(kThreads), tile_smem<DH>(), stream, a);
+  const int64_t grid = (total < resident || !tuning().attn_persist) ? total : resident;  // (not persistent: one work item per work-group)
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)grid), dim3(kThreads), tile_smem<DH>(), stream, a);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -652,10 +649,11 @@ int fused_launch(const AttnArgs& a, int n_k_rows, hipStream_t stream) {
   b.vgx = (int)(n * ((a.H + kWaves - 1) / kWaves));
   b.vgy = 1;
   static int resident = 0;
-  if (NT > 2) resident = b.vgx;  // one item per work-group
-  if (!resident)
+  if (NT <= 2 && !resident)
     if (int rc = resident_blocks(attn_bwd_fused_kernel<DH, NT>, 64 * kWaves, smem, &resident)) return rc;
-  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3((unsigned)(b.vgx < resident ? b.vgx : resident)), dim3(64 * kWaves), smem, stream, b);
+  // (the instances for longer sentences, and everything with the persistent form switched off: one item per work-group)
+  const int grid = (NT > 2 || b.vgx < resident || !tuning().attn_persist) ? b.vgx : resident;
+  hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3((unsigned)grid), dim3(64 * kWaves), smem, stream, b);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }
@@ -707,7 +705,7 @@ int launch_attention_fwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
                          const int4* sent_tab, int n_q_rows, const AttnWork* work, hipStream_t stream) {
   AttnArgs a = {};
   a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
-  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qsent = work->qsent; a.wl_qtile = work->qtile; }
+  if (sent_tab && work && tuning().worklists) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qsent = work->qsent; a.wl_qtile = work->qtile; }
   a.Q = Q; a.K = K; a.V = V; a.Out = O; a.lse = lse; a.key_ids = key_ids;
   a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.ldo = ldo;
   a.pad_id = pad_id; a.causal = causal; a.B = B; a.H = H; a.Tq = Tq; a.Tk = Tk;
@@ -729,7 +727,7 @@ int launch_attention_bwd(const half_t* Q, int ldq, const half_t* K, int ldk, con
                          const int4* sent_tab, int n_q_rows, const AttnWork* work, hipStream_t stream) {
   AttnArgs a = {};
   a.tab = sent_tab; a.Nq = sent_tab ? n_q_rows : B * Tq;
-  if (sent_tab && work && !getenv("NMT_NO_WORKLISTS")) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qsent = work->qsent; a.wl_qtile = work->qtile; }
+  if (sent_tab && work && tuning().worklists) { a.wl_counts = work->counts; a.wl_sent = work->by_tiles; a.wl_qsent = work->qsent; a.wl_qtile = work->qtile; }
   const int n_k_rows = work ? work->n_k_rows : 0;
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.lse = const_cast<float*>(lse); a.key_ids = key_ids;
   a.dQ = dQ; a.dK = dK; a.dV = dV;

@@ -39,6 +39,22 @@ void nmt_set_error(const char* fmt, ...);
 
 #define NMT_LAUNCH_CHECK() NMT_HIP_CHECK(hipGetLastError())
 
+// ---- the device and the launch-form switches ------------------------------------------------------
+// Compute units and XCDs (dies with an L2 of their own) of the current device, asked of the runtime once.
+struct DeviceInfo {
+  int cus = 256, xcds = 8;
+};
+const DeviceInfo& device_info();
+// Process-wide switches of launch forms (nmt_tuning): which work-group computes what, never what is computed.
+struct Tuning {
+  int gemm_group = 4;     // tile rows swept column by column before the next rows
+  int gemm_persist = 1;   // 0: never the persistent GEMM form, 1: for epilogues that load nothing per element, 2: always
+  int attn_persist = 1;   // 0: one attention work item per work-group
+  int worklists = 1;      // 0: attention kernels enumerate every (sentence, tile) instead of taking work lists
+  int one_stream = 0;     // 1: the backward pass's weight-gradient kernels run on the caller's stream, not beside it
+};
+Tuning& tuning();
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
@@ -188,6 +204,8 @@ int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const
                      int vocab, int32_t* scratch, hipStream_t stream, float scale = 1.f);
 int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipStream_t stream, float mult = 1.f);
 int launch_check_overflow(float* acc, int64_t n, float inv_scale, int32_t* flag, hipStream_t stream);
+// *loss_total (+)= *loss, *ntok_total (+)= *ntok (first: overwrite)
+int launch_add_scalars(const float* loss, const int32_t* ntok, float* loss_total, int32_t* ntok_total, int first, hipStream_t stream);
 int launch_adam(float* master, float* m, float* v, const float* g, half_t* w16, int64_t n, float lr, float b1,
                 float b2, float eps, int t, const int32_t* flag, hipStream_t stream);
 // Shapes of the sub-batches stacked row-wise in one pass (passed to the table kernel by value).

@@ -48,6 +48,7 @@ struct GemmArgs {
   half_t* C;
   int lda, ldb, ldc, M, N, K;
   int tiles_m, tiles_n, group_m;
+  int xcds;  // dies with their own L2: consecutive work-group ids go round-robin over them
   GemmEpilogue ep;
   // split-K: work-group (tile, z) contracts k in [z * k_chunk, min(K, (z + 1) * k_chunk)) and writes its
   // fp32 tile to partial[z][M][N]; partial == nullptr: one work-group per tile, epilogue, fp16 result
@@ -235,14 +236,14 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // Work-group -> (k-split, tile).  Consecutive work-group ids go round-robin over the 8 XCDs; undo
+  // Work-group -> (k-split, tile).  Consecutive work-group ids go round-robin over the XCDs; undo
   // that so each XCD (own L2) gets a contiguous run of tiles of as few k-splits as possible: the
   // tiles of one split read the same k-range of A and B and share those panels in L2.
   int pid, split;
   {
     const int nt = g.tiles_m * g.tiles_n, total = nt * (int)gridDim.y;
-    const int lin = (int)blockIdx.x + (int)blockIdx.y * nt, xcd = lin & 7, idx = lin >> 3;
-    const int base = total >> 3, rem = total & 7;
+    const int lin = (int)blockIdx.x + (int)blockIdx.y * nt, xcd = lin % g.xcds, idx = lin / g.xcds;
+    const int base = total / g.xcds, rem = total % g.xcds;
     const int at = xcd * base + (xcd < rem ? xcd : rem) + idx;
     split = at / nt;
     pid = at - split * nt;
@@ -501,7 +502,7 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
   const int nt = g.tiles_m * g.tiles_n;
 
   auto decode = [&](int lin, int& m0, int& n0) {
-    const int xcd = lin & 7, idx = lin >> 3, base = nt >> 3, rem = nt & 7;
+    const int xcd = lin % g.xcds, idx = lin / g.xcds, base = nt / g.xcds, rem = nt % g.xcds;
     const int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
     const int per_group = g.group_m * g.tiles_n;
     const int first = (pid / per_group) * g.group_m;
@@ -731,7 +732,6 @@ int launch_variant(const GemmArgs& g, int splits, hipStream_t stream) {
   return NMT_OK;
 }
 
-constexpr int kGroupM = 4;  // tile rows swept column by column before the next rows (see launch_tile)
 template <int BM, int BN, int BK, int NS, int NW = 4>
 int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t stream) {
   GemmArgs g = a;
@@ -740,8 +740,8 @@ int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t s
   // tile rows per sweep: the 32 tiles an XCD works on at a time form a patch of 4 rows x 8 columns (or
   // the result's whole width); between 2 and 8 the whole update is flat within 0.5 %, 4 measured best and
   // fetches least past L2, 12 and more cost 2 %
-  g.group_m = kGroupM;
-  if (const char* e = getenv("NMT_GEMM_GROUP")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
+  g.group_m = tuning().gemm_group;
+  g.xcds = device_info().xcds;
   if (splits > 1) {
     g.k_chunk = (int)round_up(ceil_div(g.K, splits), BK);
     splits = ceil_div(g.K, g.k_chunk);  // no empty split
@@ -763,12 +763,12 @@ int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t s
 }
 
 // Estimated efficiency of a tile shape on a (M, N) problem: useful fraction of the padded tiles,
-// times how well the tile count fills whole rounds of the 256 CUs, times a per-shape factor (small
+// times how well the tile count fills whole rounds of the compute units, times a per-shape factor (small
 // tiles re-read LDS more often per MFMA).
 double tile_score(int M, int N, int bm, int bn, int per_cu, double shape_eff) {
   const double tiles = (double)ceil_div(M, bm) * ceil_div(N, bn);
   const double useful = ((double)M * N) / (tiles * bm * bn);
-  const double slots = 256.0 * per_cu;
+  const double slots = (double)device_info().cus * per_cu;
   const double rounds = (tiles + slots - 1) / slots;
   const double fill = tiles / (double)((int64_t)rounds * slots);
   return useful * fill * shape_eff;
@@ -791,14 +791,16 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   const bool plain = !ep.bias && !ep.relu && !ep.drop.thr && !ep.add && !ep.relu_src;  // (out_scale is applied by the reduction)
   NMT_REQUIRE(splits <= 1 || (partial && plain), "gemm: splitting k needs a partial-sum buffer and no epilogue");
   NMT_REQUIRE(!partial || (reinterpret_cast<uintptr_t>(partial) & 15u) == 0, "gemm: partial-sum buffer must be 16-byte aligned");
-  GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, ep, partial, 0};
+  GemmArgs g{A, B, C, lda, ldb, ldc, M, N, K, 0, 0, 0, device_info().xcds, ep, partial, 0};
+  const int cus = device_info().cus;
   const int64_t plane = (int64_t)M * N;
   // Work-groups of 256 x 256 tiles run one per compute unit; they pay off once there are enough of them.
   const int64_t t256 = (int64_t)ceil_div(M, 256) * ceil_div(N, 256);
+  const int64_t full = 3 * (int64_t)cus / 4;  // large tiles from three quarters of a round on
   if (splits == 0) {  // choose: a short, wide problem (a weight gradient over many positions) is cut along k
     splits = 1;
-    if (partial && plain && t256 < 192) {
-      int64_t want = (256 + t256 / 2) / t256;                   // one work-group per compute unit
+    if (partial && plain && t256 < full) {
+      int64_t want = (cus + t256 / 2) / t256;                   // one work-group per compute unit
       want = want < K / 2048 ? want : K / 2048;                 // at least 2048 k per split
       want = want < partial_floats / plane ? want : partial_floats / plane;
       want = want < 64 ? want : 64;
@@ -807,29 +809,15 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   }
   NMT_REQUIRE(splits == 1 || plane * splits <= partial_floats, "gemm: partial-sum buffer of %lld floats too small for %d splits",
               (long long)partial_floats, splits);
-  if (const char* force = getenv("NMT_GEMM_TILE")) {  // tuning aid: force one tile shape
-    if (!strcmp(force, "256x256")) return launch_tile<256, 256, 32, 4>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "256x256w8")) return launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "256x256k64")) return launch_tile<256, 256, 64, 2, 8>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "256x128w8")) return launch_tile<256, 128, 64, 2, 8>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "256x128s3")) return launch_tile<256, 128, 32, 3, 4>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "128x256s3")) return launch_tile<128, 256, 32, 3, 4>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "256x128")) return launch_tile<256, 128, 32, 4>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "128x256")) return launch_tile<128, 256, 32, 4>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "128x128")) return launch_tile<128, 128, 64, 2>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "128x64")) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "64x128")) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, splits, stream);
-    if (!strcmp(force, "64x64")) return launch_tile<64, 64, 64, 2>(g, a_t, b_t, splits, stream);
-  }
-  if (t256 * splits >= 192) {
+  if (t256 * splits >= full) {
     // A last, partly filled round of 256 x 256 tiles leaves compute units idle for a whole tile's
     // time.  If that round is small, the rows it would cover are given to a second launch with small
     // tiles (two work-groups per compute unit), which costs about a third of a round.
-    const int tiles_n = ceil_div(N, 256), rounds = (int)(t256 / 256);
-    if (splits == 1 && rounds >= 1 && t256 % 256 != 0) {
-      const int main_tm = 256 * rounds / tiles_n, m_main = main_tm * 256, m_tail = M - m_main;
+    const int tiles_n = ceil_div(N, 256), rounds = (int)(t256 / cus);
+    if (splits == 1 && rounds >= 1 && t256 % cus != 0) {
+      const int main_tm = cus * rounds / tiles_n, m_main = main_tm * 256, m_tail = M - m_main;
       const int64_t tail128 = (int64_t)ceil_div(m_tail, 128) * ceil_div(N, 128);
-      const double cost_split = ceil_div((int64_t)main_tm * tiles_n, 256) + 0.3 * ceil_div(tail128, 512);
+      const double cost_split = ceil_div((int64_t)main_tm * tiles_n, cus) + 0.3 * ceil_div(tail128, 2 * cus);
       if (main_tm >= 1 && cost_split + 0.25 <= rounds + 1) {
         int rc = launch_gemm(A, a_t, lda, B, b_t, ldb, C, ldc, m_main, N, K, ep, stream, nullptr, 0, 1);
         if (rc != NMT_OK) return rc;
@@ -848,18 +836,16 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
     // (measured on the whole update).  Tuning aid: NMT_GEMM_PERSIST=0 never, =2 for every epilogue.
     // (Not for a k-major A: the one such product without a split, the vocabulary weight gradient, has so
     //  long a contraction that the tile change hardly counts, and measured 6 % slower in this form.)
-    const char* pe = getenv("NMT_GEMM_PERSIST");
-    const int pmode = pe ? atoi(pe) : 1;
+    const int pmode = tuning().gemm_persist;
     const bool loads_in_epilogue = ep.add || ep.relu_src || ep.drop.thr;
-    if (splits == 1 && t256 >= 512 && !a_t && pmode != 0 && (pmode == 2 || !loads_in_epilogue)) {
+    if (splits == 1 && t256 >= 2 * cus && !a_t && pmode != 0 && (pmode == 2 || !loads_in_epilogue)) {
       GemmArgs pg = g;
       pg.tiles_m = ceil_div(M, 256);
       pg.tiles_n = ceil_div(N, 256);
-      pg.group_m = kGroupM;
-      if (const char* e = getenv("NMT_GEMM_GROUP")) pg.group_m = atoi(e) > 0 ? atoi(e) : pg.group_m;
+      pg.group_m = tuning().gemm_group;
       pg.partial = nullptr;
-      if (!b_t) hipLaunchKernelGGL((gemm_persistent_kernel<false, false, 64, 2>), dim3(256), dim3(512), 0, stream, pg);
-      else hipLaunchKernelGGL((gemm_persistent_kernel<false, true, 32, 4>), dim3(256), dim3(512), 0, stream, pg);
+      if (!b_t) hipLaunchKernelGGL((gemm_persistent_kernel<false, false, 64, 2>), dim3(cus), dim3(512), 0, stream, pg);
+      else hipLaunchKernelGGL((gemm_persistent_kernel<false, true, 32, 4>), dim3(cus), dim3(512), 0, stream, pg);
       NMT_LAUNCH_CHECK();
       return NMT_OK;
     }

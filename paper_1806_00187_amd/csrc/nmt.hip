@@ -19,6 +19,36 @@ void nmt_set_error(const char* fmt, ...) {
 }
 extern "C" const char* nmt_last_error(void) { return g_err; }
 
+const DeviceInfo& device_info() {
+  static const DeviceInfo info = [] {
+    DeviceInfo d;
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) d.cus = v;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeNumberOfXccs, dev) == hipSuccess && v > 0) d.xcds = v;
+    }
+    (void)hipGetLastError();
+    return d;
+  }();
+  return info;
+}
+Tuning& tuning() {
+  static Tuning t;
+  return t;
+}
+extern "C" int nmt_tuning(const char* name, int32_t value) {
+  NMT_REQUIRE(name, "nmt_tuning: null name");
+  Tuning& t = tuning();
+  if (!strcmp(name, "gemm_group")) { NMT_REQUIRE(value >= 1, "nmt_tuning: gemm_group must be >= 1"); t.gemm_group = value; }
+  else if (!strcmp(name, "gemm_persist")) { NMT_REQUIRE(value >= 0 && value <= 2, "nmt_tuning: gemm_persist is 0, 1 or 2"); t.gemm_persist = value; }
+  else if (!strcmp(name, "attn_persist")) t.attn_persist = value != 0;
+  else if (!strcmp(name, "worklists")) t.worklists = value != 0;
+  else if (!strcmp(name, "one_stream")) t.one_stream = value != 0;
+  else if (!strcmp(name, "defaults")) t = Tuning{};
+  else NMT_REQUIRE(false, "nmt_tuning: unknown switch '%s'", name);
+  return NMT_OK;
+}
+
 DropDev make_drop(const nmt_dropout* d) {
   DropDev o = {};
   o.scale = 1.f;
@@ -102,6 +132,8 @@ struct nmt_ctx {
   float gscale = 1.f;  // power-of-two factor on everything the current pass writes to g16
   uint32_t step = 0;
   const int32_t *src = nullptr, *tgt_in = nullptr, *tgt_out = nullptr;
+  const float* last_loss = nullptr;   // where the last forward call wrote its loss sum and token count
+  const int32_t* last_ntok = nullptr;
   Plan plan;
   // second stream for the weight-gradient kernels of the backward pass (created on first use)
   hipStream_t side = nullptr;
@@ -271,6 +303,7 @@ extern "C" int nmt_create(const nmt_config* cfg, nmt_ctx** out) {
   NMT_REQUIRE(cfg->vocab >= 8 && cfg->vocab % 8 == 0 && cfg->vocab <= 65536, "nmt_create: vocab=%d must be a multiple of 8 in [8, 65536]", cfg->vocab);
   NMT_REQUIRE(cfg->pad_id >= 0 && cfg->pad_id < cfg->vocab, "nmt_create: pad_id outside the vocabulary");
   NMT_REQUIRE(cfg->dropout >= 0.f && cfg->dropout < 1.f && cfg->act_dropout >= 0.f && cfg->act_dropout < 1.f, "nmt_create: dropout outside [0, 1)");
+  NMT_REQUIRE(cfg->attn_dropout == 0.f, "nmt_create: dropout on the attention probabilities is not built (attn_dropout must be 0)");
   NMT_REQUIRE(cfg->label_smoothing >= 0.f && cfg->label_smoothing < 1.f, "nmt_create: label_smoothing outside [0, 1)");
   NMT_REQUIRE(cfg->ln_eps > 0.f, "nmt_create: ln_eps must be positive");
   NMT_REQUIRE(cfg->max_sentences >= 1 && cfg->max_len >= 1 && cfg->max_len <= 1024, "nmt_create: max_sentences >= 1 and 1 <= max_len <= 1024 required");
@@ -356,6 +389,8 @@ extern "C" int nmt_bind(nmt_ctx* ctx, void* d_w16, void* d_g16, float* d_master3
   ctx->ws = static_cast<unsigned char*>(d_workspace);
   ctx->ws_bytes = d_workspace ? ws_bytes : 0;
   ctx->have_fwd = false;
+  ctx->last_loss = nullptr;
+  ctx->last_ntok = nullptr;
   return NMT_OK;
 }
 
@@ -499,6 +534,7 @@ int forward_pass(nmt_ctx* c, const GroupDims& gd, const TableSource& tsrc, const
   c->gscale = 1.f;
   for (int64_t n = gd.Nt; n >= 8192; n >>= 1) c->gscale *= 0.5f;
   c->src = d_src; c->tgt_in = d_tgt_in; c->tgt_out = d_tgt_out;
+  c->last_loss = d_loss_sum; c->last_ntok = d_ntok;
 
   const nmt_config& k = c->cfg;
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
@@ -619,7 +655,7 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
   const Plan& p = c->plan;
   hipStream_t st = static_cast<hipStream_t>(stream), sd = c->side;
-  if (getenv("NMT_ONE_STREAM")) sd = st;  // profiling aid: no overlap, so per-kernel times are those of kernels running alone
+  if (tuning().one_stream) sd = st;  // profiling aid: no overlap, so per-kernel times are those of kernels running alone
   const Run r{c, st};   // input-gradient chain
   const Run w{c, sd};   // weight gradients
   const bool dropping = c->training && k.dropout > 0.f;
@@ -777,6 +813,14 @@ extern "C" int nmt_accumulate(nmt_ctx* ctx, int32_t first, void* stream) {
   NMT_REQUIRE(ctx && ctx->g16 && ctx->acc, "nmt_accumulate: g16 / acc32 not bound");
   return launch_accumulate(ctx->g16, ctx->acc, ctx->P, first, static_cast<hipStream_t>(stream), 1.f / ctx->gscale);
 }
+extern "C" int nmt_accumulate_loss(nmt_ctx* ctx, int32_t first, float* d_loss_total, int32_t* d_ntok_total, void* stream) {
+  NMT_REQUIRE(ctx && d_loss_total && d_ntok_total, "nmt_accumulate_loss: null argument");
+  if (!ctx->last_loss || !ctx->last_ntok) {
+    nmt_set_error("nmt_accumulate_loss: no forward call has been made");
+    return NMT_ESTATE;
+  }
+  return launch_add_scalars(ctx->last_loss, ctx->last_ntok, d_loss_total, d_ntok_total, first, static_cast<hipStream_t>(stream));
+}
 extern "C" int nmt_check_overflow(nmt_ctx* ctx, float inv_scale, int32_t* d_flag, void* stream) {
   NMT_REQUIRE(ctx && ctx->acc, "nmt_check_overflow: acc32 not bound");
   return launch_check_overflow(ctx->acc, ctx->P, inv_scale, d_flag, static_cast<hipStream_t>(stream));
@@ -787,6 +831,34 @@ extern "C" int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, f
   NMT_REQUIRE(d_flag, "nmt_adam_step: null flag");
   return launch_adam(ctx->master, ctx->m, ctx->v, ctx->acc, ctx->w16, ctx->P, lr, beta1, beta2, eps, t, d_flag,
                      static_cast<hipStream_t>(stream));
+}
+
+// Debug export: where a saved activation of the last forward pass lies in the workspace.
+extern "C" int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_ptr, int64_t* rows, int64_t* cols) {
+  NMT_REQUIRE(ctx && name && d_ptr && rows && cols, "nmt_debug_activation: null argument");
+  if (!ctx->last_loss || !ctx->ws) {
+    nmt_set_error("nmt_debug_activation: no forward call has been made");
+    return NMT_ESTATE;
+  }
+  const nmt_config& k = ctx->cfg;
+  int layer = -1, len = 0;
+  char side[4] = "", what[16] = "";
+  if (sscanf(name, "%3[a-z]%d.%15[a-z.]%n", side, &layer, what, &len) == 3 && name[len] == 0) {
+    const bool enc = !strcmp(side, "enc"), dec = !strcmp(side, "dec");
+    if ((enc && layer >= 0 && layer < k.enc_layers) || (dec && layer >= 0 && layer < k.dec_layers)) {
+      const int64_t n = enc ? ctx->Ns : ctx->Nt;
+      int64_t off = -1, width = k.d_model;
+      if (!strcmp(what, "ffn.h")) { off = enc ? ctx->plan.enc[layer].h : ctx->plan.dec[layer].h; width = k.d_ff; }
+      else if (!strcmp(what, "out")) off = enc ? ctx->plan.enc[layer].x2 : ctx->plan.dec[layer].x3;
+      if (off >= 0) {
+        *d_ptr = ctx->ws + off;
+        *rows = n;
+        *cols = width;
+        return NMT_OK;
+      }
+    }
+  }
+  NMT_REQUIRE(false, "nmt_debug_activation: unknown activation '%s'", name);
 }
 
 extern "C" int nmt_scaler_update(float* scale, int32_t* clean, int32_t overflow, int32_t window) {

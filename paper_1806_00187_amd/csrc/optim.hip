@@ -38,6 +38,10 @@ __global__ void __launch_bounds__(kThreads) accumulate_kernel(const half_t* __re
 }
 
 __global__ void set_flag_kernel(int32_t* flag, int32_t v) { *flag = v; }
+__global__ void add_scalars_kernel(const float* loss, const int32_t* ntok, float* loss_total, int32_t* ntok_total, int first) {
+  *loss_total = (first ? 0.f : *loss_total) + *loss;
+  *ntok_total = (first ? 0 : *ntok_total) + *ntok;
+}
 
 __device__ __forceinline__ bool non_finite(float x) { return (__float_as_uint(x) & 0x7F800000u) == 0x7F800000u; }
 
@@ -111,6 +115,12 @@ int launch_accumulate(const half_t* g16, float* acc, int64_t n, int first, hipSt
   NMT_REQUIRE(g16 && acc && n > 0, "accumulate: bad arguments");
   NMT_REQUIRE(aligned16(g16) && aligned16(acc), "accumulate: buffers must be 16-byte aligned");
   hipLaunchKernelGGL(accumulate_kernel, dim3(grid_for(n >> 3)), dim3(kThreads), 0, stream, g16, acc, n, first, mult);
+  NMT_LAUNCH_CHECK();
+  return NMT_OK;
+}
+
+int launch_add_scalars(const float* loss, const int32_t* ntok, float* loss_total, int32_t* ntok_total, int first, hipStream_t stream) {
+  hipLaunchKernelGGL(add_scalars_kernel, dim3(1), dim3(1), 0, stream, loss, ntok, loss_total, ntok_total, first);
   NMT_LAUNCH_CHECK();
   return NMT_OK;
 }

@@ -181,15 +181,12 @@ class Session:
         the device, which costs one more synchronisation."""
         step = t if step is None else step
         main = torch.cuda.current_stream(self.device)
-        self.loss_tot.zero_()
-        self.ntok_tot.zero_()
         if self.n_pipes == 1:
             for j, db in enumerate(dbatches):
                 self.forward_loss(db, loss_scale, step, j)
                 self.backward()
                 self.accumulate(j == 0)
-                self.loss_tot += self.loss_sum
-                self.ntok_tot += self.ntok
+                nmt.nmt_accumulate_loss(self.ctx, j == 0, self.loss_tot, self.ntok_tot)
         else:
             start = torch.cuda.Event()
             start.record(main)
@@ -205,8 +202,7 @@ class Session:
                     if prev is not None:
                         s.wait_event(prev)         # accumulate in sub-batch order
                     self.accumulate(j == 0, pipe=p)
-                    self.loss_tot += self.loss_sums[p]
-                    self.ntok_tot += self.ntoks[p]
+                    nmt.nmt_accumulate_loss(self.ctxs[p], j == 0, self.loss_tot, self.ntok_tot)
                     prev = torch.cuda.Event()
                     prev.record(s)
             main.wait_event(prev)
@@ -217,6 +213,14 @@ class Session:
         return float(self.loss_tot.item()), n_tok, int(self.flag.item())
 
     # ---- views for tests ----
+    def activation(self, name, pipe=0):
+        """A saved fp16 activation of the last forward pass as a view into the workspace tensor."""
+        ptr, rows, cols = nmt.nmt_debug_activation(self.ctxs[pipe], name)
+        ws = self.workspaces[pipe]
+        off = ptr - ws.data_ptr()
+        assert 0 <= off and off + rows * cols * 2 <= ws.numel()
+        return ws[off:off + rows * cols * 2].view(torch.float16).reshape(rows, cols)
+
     def tensor(self, flat, name):
         off, rows, cols = self.layout[name]
         return flat[off:off + rows * cols].reshape(rows, cols) if rows > 1 else flat[off:off + cols]

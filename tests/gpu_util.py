@@ -4,6 +4,28 @@ import torch
 
 DEV = "cuda:0"
 
+# Every gradient / weight comparison against the oracle leaves its figures here; tests/conftest.py prints
+# them at the end of the run (also under -q) and writes them to gpurun_out/parity_summary.json.
+PARITY = []
+
+
+def _digest(e):
+    name, worst = max(e.items(), key=lambda t: t[1])
+    vals = sorted(e.values())
+    return {"worst": float(worst), "worst_tensor": name, "median": float(vals[len(vals) // 2]),
+            "above_2e-2": {k: round(float(v), 5) for k, v in sorted(e.items()) if v > 2e-2}}
+
+
+def record_parity(case, errs, also=None, note=None):
+    """case: what was compared; errs: dict tensor name -> relative L2 error against the reference the test
+    asserts on; also: dict label -> such a dict against other references (recorded, not asserted)."""
+    rec = {"case": case, "tensors": len(errs), "asserted": _digest(errs)}
+    for label, e in (also or {}).items():
+        rec[label] = _digest(e)
+    if note:
+        rec["note"] = note
+    PARITY.append(rec)
+
 
 def dev16(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float16)).to(DEV)

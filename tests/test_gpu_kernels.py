@@ -103,7 +103,6 @@ def test_gemm_persistent_form_matches_oracle_and_the_tile_per_work_group_form():
     ReLU against the oracle (the default: epilogues that load nothing per element), then every epilogue
     (tuning mode 2) bit for bit against the one-tile-per-work-group kernel (mode 0): both add the same
     products in the same order."""
-    import os
     rng = np.random.default_rng(29)
     n_pos, B = 40, 826
     M, N, K = B * n_pos + 8, 4104, 72            # 130 x 17 tiles; the last row and column of tiles are partial
@@ -120,8 +119,8 @@ def test_gemm_persistent_form_matches_oracle_and_the_tile_per_work_group_form():
     drop = _drop(0.25, 50, 9, 1, 99, n_pos)
     got = {}
     try:
-        for mode in ("0", "2"):
-            os.environ["NMT_GEMM_PERSIST"] = mode
+        for mode in (0, 2):
+            A.nmt_tuning("gemm_persist", mode)
             outs = []
             for kw in (dict(bias=db, relu=True, drop=drop), dict(bias=db, add=add), dict(relu_src=hact, mask_scale=1.25)):
                 c = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
@@ -132,8 +131,8 @@ def test_gemm_persistent_form_matches_oracle_and_the_tile_per_work_group_form():
             outs.append(c)
             got[mode] = outs
     finally:
-        del os.environ["NMT_GEMM_PERSIST"]
-    for a, b2 in zip(got["0"], got["2"]):
+        A.nmt_tuning("defaults")
+    for a, b2 in zip(got[0], got[2]):
         assert torch.isfinite(a).all()
         assert torch.equal(a.view(torch.int16), b2.view(torch.int16))
     # contractions shorter than one k-tile, and not a multiple of it: the requests that run ahead into the
@@ -152,7 +151,6 @@ def test_gemm_tile_order_changes_no_bit():
     (k-split, tile) pairs) only decides who computes what: for any group size every tile is written exactly
     once and holds the same bits.  Ragged 130 x 17 tiles (persistent and tile-per-work-group form) and a
     weight gradient cut along k."""
-    import os
     rng = np.random.default_rng(31)
     M, N, K = 826 * 40 + 8, 4104, 72
     dx, dW = dev16(f16(rng.normal(size=(M, K)))), dev16(f16(rng.normal(size=(N, K)) / 8))
@@ -162,8 +160,8 @@ def test_gemm_tile_order_changes_no_bit():
 
     def run():
         outs = []
-        for persist in ("0", "1"):
-            os.environ["NMT_GEMM_PERSIST"] = persist
+        for persist in (0, 1):
+            A.nmt_tuning("gemm_persist", persist)
             c = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
             A.nmt_op_gemm(dx, 0, K, dW, 0, K, c, N, M, N, K)
             outs.append(c)
@@ -176,13 +174,12 @@ def test_gemm_tile_order_changes_no_bit():
         ref = run()                                   # the built-in group size
         assert all(torch.isfinite(c).all() for c in ref)
         assert torch.equal(ref[0].view(torch.int16), ref[1].view(torch.int16))
-        for group in ("1", "3", "16", "200"):         # 200: more rows per group than there are tile rows
-            os.environ["NMT_GEMM_GROUP"] = group
+        for group in (1, 3, 16, 200):                 # 200: more rows per group than there are tile rows
+            A.nmt_tuning("gemm_group", group)
             for a, b in zip(ref, run()):
                 assert torch.equal(a.view(torch.int16), b.view(torch.int16)), group
     finally:
-        os.environ.pop("NMT_GEMM_GROUP", None)
-        os.environ.pop("NMT_GEMM_PERSIST", None)
+        A.nmt_tuning("defaults")
 
 
 def test_gemm_epilogues_match_oracle():

@@ -67,7 +67,7 @@ def test_workspace_grows_with_the_batch_and_rejects_bad_shapes():
 
 
 @pytest.mark.parametrize("bad", [dict(d_model=60), dict(n_heads=3), dict(vocab=1001), dict(dropout=1.0), dict(max_len=4096),
-                                 dict(d_ff=10), dict(pad_id=-1), dict(ln_eps=0.0)])
+                                 dict(d_ff=10), dict(pad_id=-1), dict(ln_eps=0.0), dict(attn_dropout=0.1)])
 def test_create_rejects_invalid_configurations(bad):
     with pytest.raises(A.NmtError) as e:
         A.nmt_create(**_cfg(I.MODELS["tiny"], **bad))
@@ -109,3 +109,22 @@ def test_lr_schedule_matches_the_oracle():
     for t in (1, 17, 3999, 4000, 4001, 16000, 10 ** 6):
         assert A.nmt_lr_schedule(t, 1e-3) == pytest.approx(O.lr_schedule(t, 1e-3), rel=1e-15)
     assert A.nmt_lr_schedule(4000, 5e-4) == 5e-4
+
+
+def test_tuning_switches_accept_their_names_and_reject_others():
+    for name, value in (("gemm_group", 3), ("gemm_persist", 2), ("attn_persist", 0), ("worklists", 0), ("one_stream", 1), ("defaults", 0)):
+        A.nmt_tuning(name, value)
+    for name, value in (("gemm_group", 0), ("gemm_persist", 3), ("no_such_switch", 1)):
+        with pytest.raises(A.NmtError) as e:
+            A.nmt_tuning(name, value)
+        assert e.value.code == A.binding.NMT_EINVAL
+
+
+def test_loss_totals_need_a_forward_call():
+    ctx = A.nmt_create(**_cfg(I.MODELS["tiny"]))
+    lib = A.load()
+    import ctypes as C
+    buf = (C.c_float * 1)()
+    cnt = (C.c_int32 * 1)()
+    assert lib.nmt_accumulate_loss(ctx, 1, C.cast(buf, C.c_void_p), C.cast(cnt, C.c_void_p), None) == A.binding.NMT_ESTATE
+    A.nmt_destroy(ctx)
