@@ -280,6 +280,15 @@ int64_t nmt_op_colsum_scratch(int32_t cols);
 int nmt_op_colsum(const void* d_src, int32_t ld, void* d_dst, float* d_partial, int32_t rows,
                   int32_t cols, void* stream);
 
+/* nmt_op_colsum for callers that cannot allocate device memory and have no scratch buffer to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and same
+ * result bits; the partial sums live in a fixed device array of the library (8 MiB per GPU, held until the
+ * process ends) instead of d_partial, so cols is limited to 4096 (NMT_EINVAL beyond that, before anything
+ * is launched).  The call allocates and frees nothing.  All calls on one GPU share the array: calls that
+ * overlap on one GPU (different streams) race; calls on one stream are ordered and need no clearing in
+ * between (every partial sum read is written by the same call first). */
+int nmt_op_colsum_static(const void* d_src, int32_t ld, void* d_dst, int32_t rows, int32_t cols, void* stream);
+
 /* Embedding backward: d_gE[v, :] = fp16(float(d_gE[v, :]) + sqrt(d) * sum over positions r with
  * ids[r] == v of dropout-masked d_dx[r, :]), for two id streams (source then target) at once.
  * Deterministic: every sum is formed in a fixed order (increasing position within blocks of 64

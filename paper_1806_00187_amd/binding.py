@@ -75,6 +75,7 @@ _SIGNATURES = {
     "nmt_op_softmax_xent": (C.c_int, [_P, _P, _P, _I32, _I32, _I32, _F, _F, _P, _P, _P]),
     "nmt_op_colsum_scratch": (_I64, [_I32]),
     "nmt_op_colsum": (C.c_int, [_P, _I32, _P, _P, _I32, _I32, _P]),
+    "nmt_op_colsum_static": (C.c_int, [_P, _I32, _P, _I32, _I32, _P]),
     "nmt_op_embed_bwd_scratch": (_I64, [_I32, _I32, _I32]),
     "nmt_op_embed_bwd": (C.c_int, [_P, _P, _I32, _DP, _P, _P, _I32, _DP, _P, _I32, _I32, _P, _P]),
     "nmt_op_accumulate": (C.c_int, [_P, _P, _I64, _I32, _P]),
@@ -318,6 +319,10 @@ def nmt_op_colsum_scratch(cols):
 
 def nmt_op_colsum(src, ld, dst, partial, rows, cols, stream=None):
     _check(load().nmt_op_colsum(_p(src), ld, _p(dst), _p(partial), rows, cols, _stream(stream)))
+
+
+def nmt_op_colsum_static(src, ld, dst, rows, cols, stream=None):
+    _check(load().nmt_op_colsum_static(_p(src), ld, _p(dst), rows, cols, _stream(stream)))
 
 
 def nmt_op_embed_bwd_scratch(vocab, rows_total, d):

@@ -198,6 +198,7 @@ int launch_softmax_xent(half_t* logits, const int32_t* targets, float* row_loss,
                         float eps_ls, float loss_scale, float* loss_sum, int32_t* ntok, hipStream_t stream);
 int64_t colsum_scratch_floats(int cols);
 int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream, float scale = 1.f);
+int launch_colsum_static(const half_t* src, int ld, half_t* dst, int rows, int cols, hipStream_t stream);  // partial sums in a fixed device array
 int64_t embed_bwd_scratch_ints(int vocab, int rows_total, int d);
 int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const DropDev& drop_a,
                      const int32_t* ids_b, const half_t* dx_b, int rows_b, const DropDev& drop_b, half_t* gE, int d,

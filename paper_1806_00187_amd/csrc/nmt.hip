@@ -967,6 +967,10 @@ extern "C" int nmt_op_colsum(const void* d_src, int32_t ld, void* d_dst, float* 
                        static_cast<hipStream_t>(stream));
 }
 
+extern "C" int nmt_op_colsum_static(const void* d_src, int32_t ld, void* d_dst, int32_t rows, int32_t cols, void* stream) {
+  return launch_colsum_static(static_cast<const half_t*>(d_src), ld, static_cast<half_t*>(d_dst), rows, cols, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int64_t nmt_op_embed_bwd_scratch(int32_t vocab, int32_t rows_total, int32_t d) {
   return (vocab > 0 && rows_total > 0 && d > 0) ? embed_bwd_scratch_ints(vocab, rows_total, d) : NMT_EINVAL;
 }

@@ -4,6 +4,8 @@
 // deterministic embedding-gradient reduction.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -784,6 +786,44 @@ int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const h
 }
 
 int64_t colsum_scratch_floats(int cols) { return (int64_t)kColsumMaxSplits * cols; }
+
+// ------------------------------------------------------------------------------------------------
+// Column sums for callers that cannot allocate (code under graph capture, serving loops): the partial
+// sums live in a fixed device array instead of a caller-provided buffer.  Each GPU holds its own copy of
+// the array at its own address, looked up once per device; every call on a GPU shares that copy.
+// ------------------------------------------------------------------------------------------------
+constexpr int kStaticColsumMaxCols = 4096;
+static __device__ __align__(256) float scratch[(size_t)kColsumMaxSplits * kStaticColsumMaxCols];  // 8 MiB per GPU
+
+namespace {
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+// Device address of `scratch` on the current device (its name is only a host-side stand-in for it).
+int static_scratch(float** out) {
+  int dev = 0;
+  NMT_HIP_CHECK(hipGetDevice(&dev));
+  NMT_REQUIRE(dev >= 0 && dev < kMaxDevices, "colsum_static: device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    NMT_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    NMT_REQUIRE(p, "colsum_static: the scratch array has no device address");
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return NMT_OK;
+}
+}  // namespace
+
+int launch_colsum_static(const half_t* src, int ld, half_t* dst, int rows, int cols, hipStream_t stream) {
+  NMT_REQUIRE(cols > 0 && cols <= kStaticColsumMaxCols, "colsum_static: cols=%d outside [1, %d], the width the fixed scratch array holds", cols,
+              kStaticColsumMaxCols);
+  float* partial = nullptr;
+  if (int rc = static_scratch(&partial)) return rc;
+  // every partial sum the second kernel reads is written by the first one of the same call: nothing to clear
+  return launch_colsum(src, ld, dst, partial, rows, cols, stream, 1.f);
+}
 
 int launch_colsum(const half_t* src, int ld, half_t* dst, float* partial, int rows, int cols, hipStream_t stream, float scale) {
   NMT_REQUIRE(rows > 0 && cols > 0 && cols % 8 == 0 && ld % 8 == 0 && ld >= cols, "colsum: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
