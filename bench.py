@@ -1,11 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the MI355X NMT training step.
 
-One "step" is one weight update of Transformer-big in fp16 with dynamic loss scaling and
-gradient accumulation: 16 sub-batches of at most 3584 tokens (forward + loss, backward,
-accumulate), then overflow check + Adam.  Inputs are synthetic (seeded length / token
-distributions standing in for the paper's WMT sub-batches) and resident in HBM before the timed
-region starts.  Prints ONE JSON line; see the design doc for the field definitions.
+One "step" is one weight update of Transformer-big in fp16 with dynamic loss scaling over the 16
+sub-batches (at most 3584 tokens each) of configuration 4.  Two launch configurations of the same
+update are timed over the same number of steps and reported side by side:
+  * `value` / `ms_per_step`: the sentences of all 16 sub-batches packed into ONE forward + backward
+    pass (same sentences, dropout masks and sums; gradients summed in fp32 inside the weight-gradient
+    products), one accumulate call, overflow check + Adam -- the form a 288 GB GPU allows;
+  * `strict_order`: the method's literal loop, 16 x (forward + loss, backward, accumulate) over the
+    padded sub-batches one by one, then overflow check + Adam.
+Inputs are synthetic (seeded length / token distributions standing in for the paper's WMT
+sub-batches) and resident in HBM before the timed region starts.  Prints ONE JSON line; see
+the design doc for the field definitions.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big_accum|big|big40k|base]
 """
@@ -25,7 +31,7 @@ PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA peak (published)
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
 
 WORKLOAD_DESC = {
-    "big_accum": ("big", 16, "Transformer-big (6+6, d=1024, F=4096, 16 heads, V=32768), 16 sub-batches of <=3584 tokens per update"),
+    "big_accum": ("big", 16, "Transformer-big (6+6, d=1024, F=4096, 16 heads, V=32768), the 16 sub-batches of <=3584 tokens of one update"),
     "big": ("big", 1, "Transformer-big, one sub-batch of <=3584 tokens per update"),
     "big40k": ("big40k", 4, "Transformer-big with V=40000, 4 sub-batches of <=5120 tokens per update"),
     "base": ("base", 1, "Transformer-base (6+6, d=512), one sub-batch of <=3584 tokens per update"),
@@ -166,12 +172,15 @@ def main():
     achieved_tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     log(f"[bench] {ms_per_step:.2f} ms/update, {value:,.0f} target tok/s, {achieved_tflops:.1f} TFLOP/s, loss/token {loss / ntok:.3f}")
 
+    how = (f"all {k_micro} sub-batches packed into {n_pass} forward+backward pass(es) (no padding rows), accumulate x{n_pass}, overflow check, Adam"
+           if packed else f"{k_micro} padded sub-batches in groups of {group} per pass")
     result = {
         "metric": "target tokens/sec/GPU (train step, Transformer-big fp16)" if model_name != "base" else "target tokens/sec/GPU (train step)",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "micro_batches_per_update": k_micro,
+        "value_is": how,
+        "config": {"workload": f"{args.workload}: {desc}; timed as: {how}", "micro_batches_per_update": k_micro,
                    "target_tokens_per_update": tokens_per_step, "padded_shapes_BST": shapes, "loss_scale": tr.scale,
                    "overflow_updates_in_timed_region": int(sum(flags)), "sub_batches_per_pass": group, "passes_in_flight": sess.n_pipes,
                    "rows": "packed (no padding rows)" if packed else "padded", "source_positions_per_update": int(sum(r[0] for r in pass_rows)),
@@ -184,14 +193,15 @@ def main():
     }
 
     if not args.no_legs and (packed or group > 1):
-        result["strict_order"] = strict_leg(model, weights, batches, ntoks, Session, Trainer, torch, log)
+        result["strict_order"] = strict_leg(model, weights, batches, ntoks, shapes, args.steps, Session, Trainer, torch, log)
     if not args.no_legs:
         result["phases_ms_per_update"] = phase_leg(sess, tr, dbatches, ntoks, torch)
-        result["roofline"] = gemm_leg(model, pass_rows, A, torch, log,     # the dominant kernel
-                                      MEASURED_GEMM_TRAFFIC if (args.workload == "big_accum" and packed and group == 16) else None)
+        result["roofline"] = gemm_event_leg(sess, tr, dbatches, ntoks, A, torch, log,
+                                            read_profile_traffic() if (args.workload == "big_accum" and packed and group == 16) else None)
+        result["roofline"]["by_shape"] = gemm_leg(model, pass_rows, A, torch, log)
         result["hbm_kernels"] = hbm_leg(sess, torch)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(model, weights, batches[len(batches) // 2], k_micro, tokens_per_step, tr.scale, log)
+        result["cpu_baseline"] = cpu_baseline(model, weights, batches[:2], tokens_per_step, tr.scale, log)
     if result["roofline"] is None:      # --no-legs: only the end-to-end rate is known
         result["roofline"] = dict(result["whole_update"], traffic=None)
     sess.close()
@@ -211,9 +221,11 @@ def _timed(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def strict_leg(model, weights, batches, ntoks, Session, Trainer, torch, log):
-    """The same update in the paper's literal order: the 16 padded sub-batches one by one (forward + loss,
-    backward, accumulate each; three in flight on separate streams), then overflow check + Adam."""
+def strict_leg(model, weights, batches, ntoks, shapes, steps, Session, Trainer, torch, log):
+    """The same update in the method's literal order ("Training with Larger Batches"): the 16 padded sub-batches one by
+    one (forward + loss, backward, accumulate each; three in flight on separate streams, accumulation chained in
+    sub-batch order), then overflow check + Adam.  Timed over the same number of steps as the headline; the time
+    of each of the five calls summed over one update comes from a serial (one sub-batch in flight) pass."""
     sess = Session(model, weights, max_sentences=max(b["src"].shape[0] for b in batches), max_len=256, n_pipes=min(3, len(batches)))
     dbs = [sess.to_device(b) for b in batches]
     for b in batches:
@@ -222,7 +234,6 @@ def strict_leg(model, weights, batches, ntoks, Session, Trainer, torch, log):
     for _ in range(12):                                  # settle the loss scale
         if not tr.step(dbs, n_tok=sum(ntoks))[2]:
             break
-    steps = 3
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record(torch.cuda.current_stream())
@@ -231,9 +242,20 @@ def strict_leg(model, weights, batches, ntoks, Session, Trainer, torch, log):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
     sess.close()
-    log(f"[bench] strict order (16 padded sub-batches one by one, 3 in flight): {ms:.2f} ms/update, loss scale {tr.scale}")
-    return {"what": "16 padded sub-batches one by one (3 in flight), then overflow check + Adam", "ms_per_step": ms,
-            "value": sum(ntoks) / (ms * 1e-3), "unit": "tokens/s", "steps": steps, "loss_scale": tr.scale, "overflow_updates": int(sum(flags))}
+    # per-call times of the 16-call path (serial, so that the events of one call do not cover another's kernels)
+    serial = Session(model, weights, max_sentences=max(b["src"].shape[0] for b in batches), max_len=256)
+    sdbs = [serial.to_device(b) for b in batches]
+    str_ = Trainer(serial, peak_lr=1e-3, warmup=4000, init_scale=tr.scale)
+    str_.step(sdbs, n_tok=sum(ntoks))
+    phases = phase_leg(serial, str_, sdbs, ntoks, torch)
+    serial.close()
+    flops = sum(model_flops(model, *s_) for s_ in shapes)
+    tflops = flops / (ms * 1e-3) / 1e12
+    log(f"[bench] strict order (16 padded sub-batches one by one, 3 in flight): {ms:.2f} ms/update, {tflops:.1f} TFLOP/s, loss scale {tr.scale}")
+    return {"what": "16 x (forward+loss, backward, accumulate) over the padded sub-batches one by one (3 in flight), then overflow check + Adam",
+            "ms_per_step": ms, "value": sum(ntoks) / (ms * 1e-3), "unit": "tokens/s", "steps": steps, "loss_scale": tr.scale,
+            "overflow_updates": int(sum(flags)), "achieved_tflops": tflops, "frac_of_fp16_peak": tflops / PEAK_FP16_TFLOPS,
+            "phases_ms_per_update_serial": phases}
 
 
 def phase_leg(sess, tr, dbatches, ntoks, torch):
@@ -263,15 +285,51 @@ def phase_leg(sess, tr, dbatches, ntoks, torch):
     return acc
 
 
-# HBM-side bytes per product of the default workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated against
-# kernels of known size; profiles/bench_big_accum_gemm_hbm_traffic.txt): 160.8 GB per update over 201 products,
-# for 87.4 GB of algorithmic operand + result bytes.
-MEASURED_GEMM_TRAFFIC = {"bytes_per_launch": 737e6, "algorithmic_bytes_per_launch": 435e6, "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
+PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "bench_big_accum_gemm_hbm_traffic.txt")
 
 
-def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
-    """Every distinct GEMM of the update timed alone through nmt_op_gemm (HIP events, 10 launches
-    each): algorithmic FLOPs / summed average durations = achieved rate of the GEMM kernel."""
+def read_profile_traffic():
+    """HBM-side bytes per GEMM product of the default workload from the committed rocprofv3 --pmc summary (FETCH_SIZE /
+    WRITE_SIZE calibrated against kernels of known size): its line "per-product-bytes: moved=<n> algorithmic=<n>"."""
+    try:
+        import re
+        m = re.search(r"per-product-bytes:\s*moved=([0-9.e+]+)\s+algorithmic=([0-9.e+]+)", open(PROFILE_TRAFFIC).read())
+        return {"bytes_per_launch": float(m.group(1)), "algorithmic_bytes_per_launch": float(m.group(2)),
+                "source": "profiles/bench_big_accum_gemm_hbm_traffic.txt"}
+    except Exception:
+        return None
+
+
+def gemm_event_leg(sess, tr, dbatches, ntoks, A, torch, log, traffic, updates=3):
+    """The dominant kernel measured in the step itself: the timed update is run `updates` more times with a pair of
+    HIP events around every GEMM product on the stream it is launched on (weight-gradient products on the caller's
+    stream as well, so that every duration is that of a product running alone); algorithmic FLOPs 2 M N K of all
+    products / the sum of their durations."""
+    A.nmt_tuning("one_stream", 1)
+    A.nmt_tuning("gemm_timing", 1)
+    try:
+        A.nmt_gemm_timing()
+        for _ in range(updates):
+            for j, db in enumerate(dbatches):
+                sess.forward_loss(db, tr.scale, tr.t, j)
+                sess.backward()
+                sess.accumulate(j == 0)
+        ms, n, flops = A.nmt_gemm_timing()
+    finally:
+        A.nmt_tuning("defaults")
+    achieved = flops / ms / 1e9
+    log(f"[bench] GEMM products in the step (HIP events, one stream): {achieved:.1f} TFLOP/s over {n // updates} products per update, "
+        f"{ms / updates:.2f} ms per update")
+    return {"bound": "mfma", "kernel": "gemm_kernel / gemm_persistent_kernel (every GEMM product of the timed update, incl. split-k reduction)",
+            "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS, "traffic": traffic,
+            "how": f"HIP events around every product on its launch stream, {updates} updates of the timed step with the backward pass on one stream",
+            "launches_per_update": n // updates, "avg_launch_us": ms * 1e3 / n, "ms_per_update": ms / updates,
+            "algorithmic_flops_per_launch": flops / n}
+
+
+def gemm_leg(model, pass_rows, A, torch, log):
+    """Every distinct GEMM shape of the update timed alone through nmt_op_gemm on random operands (HIP events, 10
+    launches each): which shapes are fast and which are slow."""
     agg = {}
     for s in pass_rows:
         for (M, N, K, a_t, b_t, count, epi) in gemm_shapes(model, *s):
@@ -316,8 +374,7 @@ def gemm_leg(model, pass_rows, A, torch, log, traffic=None):
             best = (rate, [M, N, K, kind])
     achieved = tot_flops / tot_ms / 1e9
     log(f"[bench] GEMM leg: {achieved:.1f} TFLOP/s over {n_launch} launches, {tot_ms:.2f} ms per update; worst {worst}, best {best}")
-    return {"bound": "mfma", "kernel": "gemm_kernel / gemm_persistent_kernel (all GEMM launches of one update, each shape timed alone)",
-            "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS, "traffic": traffic,
+    return {"what": "each distinct shape timed alone on random operands", "achieved": achieved, "frac": achieved / PEAK_FP16_TFLOPS,
             "launches_per_update": n_launch, "avg_launch_us": tot_ms * 1e3 / n_launch, "ms_per_update": tot_ms,
             "by_kind_tflops": {k: v[0] / v[1] / 1e9 for k, v in per_kind.items()}, "worst_tflops": worst, "best_tflops": best}
 
@@ -338,10 +395,10 @@ def hbm_leg(sess, torch):
     return out
 
 
-def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, loss_scale, log):
-    """The fp64 numpy oracle timed on the host cores: forward + backward + fp16 rounding + accumulate
-    on the first 24 sentences of one sub-batch, and overflow check + Adam over all parameters once;
-    scaled to a whole update."""
+def cpu_baseline(model, weights, sample, tokens_per_update, loss_scale, log):
+    """The fp64 numpy oracle timed on the host cores: forward + backward + fp16 rounding + accumulate on two whole
+    sub-batches of the update, and overflow check + Adam over all parameters once; scaled to a whole update by
+    target tokens."""
     import numpy as np
     import nmt_inputs as I
     from oracle import nmt_oracle as O
@@ -350,32 +407,33 @@ def cpu_baseline(model, weights, batch, k_micro, tokens_per_update, loss_scale, 
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
     except Exception:
         cores = os.cpu_count() or 1
-    nb = min(24, batch["src"].shape[0])
-    sub = {k: v[:nb] for k, v in batch.items()}
-    ntok = int((sub["tgt_out"] != I.PAD).sum())
     cfg = O.Config(model["enc_layers"], model["dec_layers"], model["d_model"], model["n_heads"], model["d_ff"], model["vocab"],
                    dropout=model["dropout"])
     P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    acc, ntok, t_micro = None, 0, 0.0
+    for j, mb in enumerate(sample):
+        t0 = time.perf_counter()
+        loss, n, cache = O.forward_loss(P16, cfg, mb["src"], mb["tgt_in"], mb["tgt_out"], step=1, micro=j)
+        g = O.to_fp16_storage(O.backward(P16, cfg, cache, loss_scale))
+        acc = O.accumulate(acc, g, j == 0)
+        t_micro += time.perf_counter() - t0
+        ntok += n
+        del cache, g
     t0 = time.perf_counter()
-    loss, n, cache = O.forward_loss(P16, cfg, sub["src"], sub["tgt_in"], sub["tgt_out"], step=1, micro=0)
-    g = O.to_fp16_storage(O.backward(P16, cfg, cache, loss_scale))
-    acc = O.accumulate(None, g, True)
-    t_micro = time.perf_counter() - t0
-    del cache, g
-    t0 = time.perf_counter()
-    flag, un = O.check_overflow(acc, 1.0 / (loss_scale * n))
+    flag, un = O.check_overflow(acc, 1.0 / (loss_scale * ntok))
     m = {k: np.zeros_like(v) for k, v in P16.items()}
     v = {k: np.zeros_like(val) for k, val in P16.items()}
     O.adam_step(P16, m, v, un, 1e-3, 0.9, 0.98, 1e-8, 1, flag)
     t_update = time.perf_counter() - t0
-    per_token = t_micro / ntok
-    total = per_token * tokens_per_update + t_update
+    total = t_micro / ntok * tokens_per_update + t_update
     val = tokens_per_update / total
-    log(f"[bench] oracle: {t_micro:.1f}s for {ntok} tokens, {t_update:.1f}s for overflow check + Adam (flag {flag}); {val:.1f} tok/s on {cores} threads")
+    shapes = [(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1]) for b in sample]
+    log(f"[bench] oracle: {t_micro:.1f}s for {ntok} tokens in {len(sample)} sub-batches, {t_update:.1f}s for overflow check + Adam (flag {flag}); "
+        f"{val:.1f} tok/s on {cores} threads")
     return {"value": val, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"fp64 numpy oracle: forward+backward+fp16 rounding+accumulate on the first {nb} sentences ({ntok} target tokens) of one "
-                      f"sub-batch ({t_micro:.1f} s), overflow check + Adam over all parameters once ({t_update:.1f} s), scaled to one update of "
-                      f"{tokens_per_update} tokens"}
+            "sample": f"fp64 numpy oracle: forward+backward+fp16 rounding+accumulate on {len(sample)} whole sub-batches of the update, (B,S,T)={shapes}, "
+                      f"{ntok} target tokens ({t_micro:.1f} s), overflow check + Adam over all parameters once ({t_update:.1f} s), scaled to one update "
+                      f"of {tokens_per_update} tokens"}
 
 
 if __name__ == "__main__":

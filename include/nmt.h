@@ -190,9 +190,14 @@ int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_pt
  * 1 where the epilogue loads nothing per element / 2 always the persistent GEMM form; default 1),
  * "attn_persist" (0: one attention work item per work-group; default 1), "worklists" (0: attention
  * kernels enumerate every (sentence, tile); default 1), "one_stream" (1: nmt_backward enqueues the weight
- * gradients on the caller's stream; default 0), "defaults" (value ignored: all of the above back to default).
- * Unknown names and values out of range return NMT_EINVAL. */
+ * gradients on the caller's stream; default 0), "gemm_timing" (1: every GEMM product is bracketed by a pair of
+ * HIP events on the stream it is launched on; default 0), "defaults" (value ignored: all of the above back to
+ * default).  Unknown names and values out of range return NMT_EINVAL. */
 int nmt_tuning(const char* name, int32_t value);
+/* Host only; waits for the products concerned.  With "gemm_timing" on: the sum of the event-bracketed durations
+ * (milliseconds) of the GEMM products launched since the last call, their number, and their algorithmic FLOPs
+ * (2 M N K each); any of the three pointers may be NULL.  The measurement behind the benchmark's roofline figure. */
+int nmt_gemm_timing(double* ms /*host*/, int64_t* products /*host*/, double* flops /*host*/);
 
 /* ------------------------------------------------------------------------------------------
  * Kernel-level entry points (used by the per-kernel parity tests and by profiling).

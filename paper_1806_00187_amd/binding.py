@@ -58,6 +58,7 @@ _SIGNATURES = {
     "nmt_accumulate": (C.c_int, [_P, _I32, _P]),
     "nmt_accumulate_loss": (C.c_int, [_P, _I32, _P, _P, _P]),
     "nmt_tuning": (C.c_int, [C.c_char_p, _I32]),
+    "nmt_gemm_timing": (C.c_int, [C.POINTER(C.c_double), C.POINTER(_I64), C.POINTER(C.c_double)]),
     "nmt_debug_activation": (C.c_int, [_P, C.c_char_p, C.POINTER(_P), C.POINTER(_I64), C.POINTER(_I64)]),
     "nmt_check_overflow": (C.c_int, [_P, _F, _P, _P]),
     "nmt_adam_step": (C.c_int, [_P, _F, _F, _F, _F, _I32, _P, _P]),
@@ -242,6 +243,13 @@ def nmt_debug_activation(ctx, name):
     ptr, rows, cols = C.c_void_p(), C.c_int64(), C.c_int64()
     _check(load().nmt_debug_activation(ctx, name.encode(), C.byref(ptr), C.byref(rows), C.byref(cols)))
     return ptr.value, rows.value, cols.value
+
+
+def nmt_gemm_timing():
+    """(milliseconds, products, algorithmic FLOPs) of the GEMM products launched since the last call with "gemm_timing" on."""
+    ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
+    _check(load().nmt_gemm_timing(C.byref(ms), C.byref(n), C.byref(fl)))
+    return ms.value, n.value, fl.value
 
 
 def nmt_tuning(name, value=0):

@@ -52,6 +52,7 @@ struct Tuning {
   int attn_persist = 1;   // 0: one attention work item per work-group
   int worklists = 1;      // 0: attention kernels enumerate every (sentence, tile) instead of taking work lists
   int one_stream = 0;     // 1: the backward pass's weight-gradient kernels run on the caller's stream, not beside it
+  int gemm_timing = 0;    // 1: every GEMM product is bracketed by HIP events on its launch stream (nmt_gemm_timing reads them)
 };
 Tuning& tuning();
 
@@ -156,6 +157,10 @@ struct GemmEpilogue {
 int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc,
                 int M, int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial = nullptr,
                 int64_t partial_floats = 0, int splits = 1);
+
+// Sum of the event-bracketed durations of the products launched since the last call (tuning().gemm_timing), their
+// number and their algorithmic FLOPs; waits for them to finish.
+int gemm_timing_read(double* ms, int64_t* products, double* flops);
 
 // Work lists of one attention kind over a sentence table, made on the device (launch_attention_worklists)
 // so that the attention kernels start no work-group for a (sentence, tile) that does not exist:

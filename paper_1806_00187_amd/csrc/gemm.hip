@@ -28,7 +28,9 @@
 //    barrier per k-tile both publishes the next tile and frees the current one for refilling.
 #include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include "common.h"
 
@@ -455,7 +457,9 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
           half8_t o;
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = (half_t)v[e];
-          st_half8(g.C + off, o);
+          // streaming store: a result tile is not read again by this product, and letting it stay in L2 pushes out
+          // the operand panels the XCD's other tiles are reading (products with wide results: +5-7 %)
+          __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(g.C + off));
         }
       }
     }
@@ -673,7 +677,9 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
           half8_t o;
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = (half_t)v[e];
-          st_half8(g.C + off, o);
+          // streaming store: a result tile is not read again by this product, and letting it stay in L2 pushes out
+          // the operand panels the XCD's other tiles are reading (products with wide results: +5-7 %)
+          __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(g.C + off));
         }
       }
     }
@@ -776,8 +782,9 @@ double tile_score(int M, int N, int bm, int bn, int per_cu, double shape_eff) {
 
 }  // namespace
 
-int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc, int M,
-                int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial, int64_t partial_floats, int splits) {
+namespace {
+int launch_gemm_impl(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc, int M,
+                     int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial, int64_t partial_floats, int splits) {
   NMT_REQUIRE(M > 0 && N > 0 && K > 0, "gemm: empty problem M=%d N=%d K=%d", M, N, K);
   NMT_REQUIRE(A && B && C, "gemm: null operand");
   NMT_REQUIRE(aligned16(A) && aligned16(B) && aligned16(C), "gemm: operands must be 16-byte aligned");
@@ -819,14 +826,14 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
       const int64_t tail128 = (int64_t)ceil_div(m_tail, 128) * ceil_div(N, 128);
       const double cost_split = ceil_div((int64_t)main_tm * tiles_n, cus) + 0.3 * ceil_div(tail128, 2 * cus);
       if (main_tm >= 1 && cost_split + 0.25 <= rounds + 1) {
-        int rc = launch_gemm(A, a_t, lda, B, b_t, ldb, C, ldc, m_main, N, K, ep, stream, nullptr, 0, 1);
+        int rc = launch_gemm_impl(A, a_t, lda, B, b_t, ldb, C, ldc, m_main, N, K, ep, stream, nullptr, 0, 1);
         if (rc != NMT_OK) return rc;
         GemmEpilogue tail = ep;
         tail.row0 = ep.row0 + m_main;
         if (tail.add) tail.add += (size_t)m_main * ldc;
         if (tail.relu_src) tail.relu_src += (size_t)m_main * ldc;
-        return launch_gemm(a_t ? A + m_main : A + (size_t)m_main * lda, a_t, lda, B, b_t, ldb, C + (size_t)m_main * ldc, ldc, m_tail, N,
-                           K, tail, stream, nullptr, 0, 1);
+        return launch_gemm_impl(a_t ? A + m_main : A + (size_t)m_main * lda, a_t, lda, B, b_t, ldb, C + (size_t)m_main * ldc, ldc, m_tail, N,
+                                K, tail, stream, nullptr, 0, 1);
       }
     }
     // At least two tiles per compute unit, no split along k, row-major A: the persistent form, by default
@@ -863,4 +870,53 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
   if (s12864 >= s64128 && s12864 >= s64) return launch_tile<128, 64, 64, 2>(g, a_t, b_t, 1, stream);
   if (s64128 >= s64) return launch_tile<64, 128, 64, 2>(g, a_t, b_t, 1, stream);
   return launch_tile<64, 64, 64, 2>(g, a_t, b_t, 1, stream);
+}
+
+// Optional timing of every product with HIP events on the stream it is launched on (the benchmark's roofline leg):
+// pairs of events from a pool that grows as needed and is read and reset by gemm_timing_read.
+struct TimedProduct {
+  hipEvent_t start, stop;
+  double flops;
+};
+std::vector<TimedProduct> g_timed;
+size_t g_timed_used = 0;
+std::mutex g_timed_mutex;
+}  // namespace
+
+int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, int ldb, half_t* C, int ldc, int M,
+                int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial, int64_t partial_floats, int splits) {
+  if (!tuning().gemm_timing) return launch_gemm_impl(A, a_t, lda, B, b_t, ldb, C, ldc, M, N, K, ep, stream, partial, partial_floats, splits);
+  TimedProduct t;
+  {
+    std::lock_guard<std::mutex> lock(g_timed_mutex);
+    if (g_timed_used == g_timed.size()) {
+      TimedProduct fresh = {};
+      NMT_HIP_CHECK(hipEventCreate(&fresh.start));
+      NMT_HIP_CHECK(hipEventCreate(&fresh.stop));
+      g_timed.push_back(fresh);
+    }
+    g_timed[g_timed_used].flops = 2.0 * M * N * K;
+    t = g_timed[g_timed_used++];
+  }
+  NMT_HIP_CHECK(hipEventRecord(t.start, stream));
+  const int rc = launch_gemm_impl(A, a_t, lda, B, b_t, ldb, C, ldc, M, N, K, ep, stream, partial, partial_floats, splits);
+  NMT_HIP_CHECK(hipEventRecord(t.stop, stream));
+  return rc;
+}
+
+int gemm_timing_read(double* ms, int64_t* products, double* flops) {
+  std::lock_guard<std::mutex> lock(g_timed_mutex);
+  double total = 0.0, fl = 0.0;
+  for (size_t i = 0; i < g_timed_used; ++i) {
+    float one = 0.f;
+    NMT_HIP_CHECK(hipEventSynchronize(g_timed[i].stop));
+    NMT_HIP_CHECK(hipEventElapsedTime(&one, g_timed[i].start, g_timed[i].stop));
+    total += one;
+    fl += g_timed[i].flops;
+  }
+  if (ms) *ms = total;
+  if (products) *products = (int64_t)g_timed_used;
+  if (flops) *flops = fl;
+  g_timed_used = 0;
+  return NMT_OK;
 }

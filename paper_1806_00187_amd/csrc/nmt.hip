@@ -44,6 +44,7 @@ extern "C" int nmt_tuning(const char* name, int32_t value) {
   else if (!strcmp(name, "attn_persist")) t.attn_persist = value != 0;
   else if (!strcmp(name, "worklists")) t.worklists = value != 0;
   else if (!strcmp(name, "one_stream")) t.one_stream = value != 0;
+  else if (!strcmp(name, "gemm_timing")) t.gemm_timing = value != 0;
   else if (!strcmp(name, "defaults")) t = Tuning{};
   else NMT_REQUIRE(false, "nmt_tuning: unknown switch '%s'", name);
   return NMT_OK;
@@ -832,6 +833,8 @@ extern "C" int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, f
   return launch_adam(ctx->master, ctx->m, ctx->v, ctx->acc, ctx->w16, ctx->P, lr, beta1, beta2, eps, t, d_flag,
                      static_cast<hipStream_t>(stream));
 }
+
+extern "C" int nmt_gemm_timing(double* ms, int64_t* products, double* flops) { return gemm_timing_read(ms, products, flops); }
 
 // Debug export: where a saved activation of the last forward pass lies in the workspace.
 extern "C" int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_ptr, int64_t* rows, int64_t* cols) {
