@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--group", type=int, default=16, help="sub-batches stacked into one forward/backward pass")
     ap.add_argument("--padded", action="store_true", help="keep the sub-batches' padding rows (default: sentences packed back to back)")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
+    ap.add_argument("--one-stream", action="store_true", help="profiling aid: weight-gradient kernels on the caller's stream, so that a kernel "
+                    "trace shows every kernel running alone")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives or sharding); use --gpus 1")
@@ -108,6 +110,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     A.load()
+    if args.one_stream:
+        A.nmt_tuning("one_stream", 1)
     model_name, k_micro, desc = WORKLOAD_DESC[args.workload]
     model = I.MODELS[model_name]
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
@@ -381,10 +385,10 @@ def gemm_leg(model, pass_rows, A, torch, log):
 
 def hbm_leg(sess, torch):
     """Achieved GB/s of the HBM-bound update kernels: algorithmic bytes per parameter
-    (accumulate 2+4+4, overflow check 4+4, Adam 16 read + 14 written) x P / duration."""
+    (accumulate 2+4+4, overflow check 4 read, Adam 16 read + 14 written) x P / duration."""
     P = sess.P
     out = {}
-    for name, fn, bpp in (("accumulate", lambda: sess.accumulate(False), 10), ("check_overflow", lambda: sess.check_overflow(1.0), 8),
+    for name, fn, bpp in (("accumulate", lambda: sess.accumulate(False), 10), ("check_overflow", lambda: sess.check_overflow(1.0), 4),
                           ("adam_step", None, 30)):
         if fn is None:
             sess.flag.zero_()

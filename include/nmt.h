@@ -155,14 +155,17 @@ int nmt_accumulate_loss(nmt_ctx* ctx, int32_t first, float* d_loss_total, int32_
  * sub-batch's gradient would.  nmt_accumulate divides it out again (exactly). */
 float nmt_grad_scale(const nmt_ctx* ctx);
 
-/* Conversion of the accumulated gradients to their original scale plus overflow detection in
- * one pass ("Half-Precision Training"): *d_flag = 1 iff any element of acc32 is inf or NaN,
- * else 0; acc32 is multiplied by inv_scale = 1 / (loss_scale * total n_tok) in place (its
- * content is meaningless when the flag is set). */
+/* Overflow detection on the accumulated gradients and their conversion to the original scale ("Half-Precision
+ * Training": after accumulation the fp16 gradients, by then fp32 sums, are brought back to the scale of the
+ * loss before the weights are updated).  *d_flag = 1 iff any element of acc32 is inf or NaN, else 0, in one
+ * read-only pass over acc32; inv_scale = 1 / (loss_scale * total n_tok) is remembered by the context and applied
+ * by nmt_adam_step to every element as it reads it (acc32 itself keeps the scaled sums: the unscaled gradient is
+ * never written out, which saves one 4-byte write and one 4-byte read per parameter). */
 int nmt_check_overflow(nmt_ctx* ctx, float inv_scale, int32_t* d_flag, void* stream);
 
 /* Adam ("Models and Hyperparameters": beta1 0.9, beta2 0.98, epsilon 1e-8) on the fp32 master weights
- * with gradient acc32 -- the optimizer runs in fp32 ("Half-Precision Training") -- then w16 =
+ * with gradient acc32 * inv_scale (the factor of the last nmt_check_overflow; 1 if none was made) -- the optimizer
+ * runs in fp32 ("Half-Precision Training") -- then w16 =
  * round-to-nearest-even of the new master weights.  t is the 1-based update count.  If *d_flag != 0 the
  * call changes nothing (the update is skipped on overflow). */
 int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, float eps, int32_t t,
@@ -307,8 +310,10 @@ int nmt_op_embed_bwd(const int32_t* d_ids_a, const void* d_dx_a, int32_t rows_a,
 /* Element-wise update kernels on n scalars (the bodies of nmt_accumulate, nmt_check_overflow
  * and nmt_adam_step). */
 int nmt_op_accumulate(const void* d_g16, float* d_acc32, int64_t n, int32_t first, void* stream);
+/* nmt_op_check_overflow is the single-pass form that also unscales in place: *d_flag as above and
+ * d_acc32 *= inv_scale.  nmt_op_adam updates with d_g32 * grad_scale. */
 int nmt_op_check_overflow(float* d_acc32, int64_t n, float inv_scale, int32_t* d_flag, void* stream);
-int nmt_op_adam(float* d_master32, float* d_m, float* d_v, const float* d_g32, void* d_w16, int64_t n,
+int nmt_op_adam(float* d_master32, float* d_m, float* d_v, const float* d_g32, float grad_scale, void* d_w16, int64_t n,
                 float lr, float beta1, float beta2, float eps, int32_t t, const int32_t* d_flag,
                 void* stream);
 

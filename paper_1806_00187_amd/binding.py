@@ -81,7 +81,7 @@ _SIGNATURES = {
     "nmt_op_embed_bwd": (C.c_int, [_P, _P, _I32, _DP, _P, _P, _I32, _DP, _P, _I32, _I32, _P, _P]),
     "nmt_op_accumulate": (C.c_int, [_P, _P, _I64, _I32, _P]),
     "nmt_op_check_overflow": (C.c_int, [_P, _I64, _F, _P, _P]),
-    "nmt_op_adam": (C.c_int, [_P, _P, _P, _P, _P, _I64, _F, _F, _F, _F, _I32, _P, _P]),
+    "nmt_op_adam": (C.c_int, [_P, _P, _P, _P, _F, _P, _I64, _F, _F, _F, _F, _I32, _P, _P]),
     "nmt_op_dropout_mask": (C.c_int, [_P, _I32, _I32, _DP, _P]),
 }
 
@@ -350,8 +350,9 @@ def nmt_op_check_overflow(acc32, n, inv_scale, flag, stream=None):
     _check(load().nmt_op_check_overflow(_p(acc32), n, inv_scale, _p(flag), _stream(stream)))
 
 
-def nmt_op_adam(master32, m, v, g32, w16, n, lr, beta1, beta2, eps, t, flag, stream=None):
-    _check(load().nmt_op_adam(_p(master32), _p(m), _p(v), _p(g32), _p(w16), n, lr, beta1, beta2, eps, t, _p(flag), _stream(stream)))
+def nmt_op_adam(master32, m, v, g32, w16, n, lr, beta1, beta2, eps, t, flag, grad_scale=1.0, stream=None):
+    _check(load().nmt_op_adam(_p(master32), _p(m), _p(v), _p(g32), grad_scale, _p(w16), n, lr, beta1, beta2, eps, t, _p(flag),
+                              _stream(stream)))
 
 
 def nmt_op_dropout_mask(keep, rows, n_cols, drop, stream=None):

@@ -807,11 +807,22 @@ int launch_gemm_impl(const half_t* A, bool a_t, int lda, const half_t* B, bool b
   if (splits == 0) {  // choose: a short, wide problem (a weight gradient over many positions) is cut along k
     splits = 1;
     if (partial && plain && t256 < full) {
-      int64_t want = (cus + t256 / 2) / t256;                   // one work-group per compute unit
+      int64_t want = (cus + t256 / 2) / t256;                   // large tiles: one work-group per compute unit
       want = want < K / 2048 ? want : K / 2048;                 // at least 2048 k per split
       want = want < partial_floats / plane ? want : partial_floats / plane;
       want = want < 64 ? want : 64;
-      if (want >= 2) splits = (int)want;
+      if (want >= 2) {
+        splits = (int)want;
+      } else {
+        // a contraction too short for that (the weight gradient of a single sub-batch): 128 x 128 tiles, two
+        // work-groups per compute unit, at least 512 k per split
+        const int64_t t128 = (int64_t)ceil_div(M, 128) * ceil_div(N, 128);
+        want = 2 * cus / t128;
+        want = want < K / 512 ? want : K / 512;
+        want = want < partial_floats / plane ? want : partial_floats / plane;
+        want = want < 64 ? want : 64;
+        if (want >= 2) splits = (int)want;
+      }
     }
   }
   NMT_REQUIRE(splits == 1 || plane * splits <= partial_floats, "gemm: partial-sum buffer of %lld floats too small for %d splits",

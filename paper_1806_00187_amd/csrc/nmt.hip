@@ -131,6 +131,7 @@ struct nmt_ctx {
   int Bt = 0, Ns = 0, Nt = 0, maxS = 0, maxT = 0, training = 0;  // sentences, source / target rows, longest sides
   float loss_scale = 1.f;
   float gscale = 1.f;  // power-of-two factor on everything the current pass writes to g16
+  float inv_scale = 1.f;  // what nmt_check_overflow was given: nmt_adam_step applies it to acc32 on the fly
   uint32_t step = 0;
   const int32_t *src = nullptr, *tgt_in = nullptr, *tgt_out = nullptr;
   const float* last_loss = nullptr;   // where the last forward call wrote its loss sum and token count
@@ -255,7 +256,7 @@ int64_t plan_workspace(const nmt_ctx* c, const GroupDims& gd, Plan& p) {
   p.cspart = take(colsum_scratch_floats((int)widest) * f4);
   p.embscratch = take(embed_bwd_scratch_ints((int)V, (int)(Ns + Nt), (int)d) * (int64_t)sizeof(int32_t));
   // fp32 partial sums of weight-gradient products cut along the (long) position axis
-  p.wgpart_floats = Nm >= 4096 ? kWgradPartialFloats : 0;
+  p.wgpart_floats = kWgradPartialFloats;
   p.wgpart = take(p.wgpart_floats * f4);
   p.total = cur;
   return cur;
@@ -824,14 +825,16 @@ extern "C" int nmt_accumulate_loss(nmt_ctx* ctx, int32_t first, float* d_loss_to
 }
 extern "C" int nmt_check_overflow(nmt_ctx* ctx, float inv_scale, int32_t* d_flag, void* stream) {
   NMT_REQUIRE(ctx && ctx->acc, "nmt_check_overflow: acc32 not bound");
-  return launch_check_overflow(ctx->acc, ctx->P, inv_scale, d_flag, static_cast<hipStream_t>(stream));
+  NMT_REQUIRE(isfinite(inv_scale) && inv_scale > 0.f, "nmt_check_overflow: inv_scale must be positive and finite");
+  ctx->inv_scale = inv_scale;
+  return launch_check_overflow(ctx->acc, ctx->P, inv_scale, d_flag, static_cast<hipStream_t>(stream), false);
 }
 extern "C" int nmt_adam_step(nmt_ctx* ctx, float lr, float beta1, float beta2, float eps, int32_t t, const int32_t* d_flag,
                              void* stream) {
   NMT_REQUIRE(ctx && ctx->acc && ctx->master && ctx->m && ctx->v && ctx->w16, "nmt_adam_step: optimizer buffers not bound");
   NMT_REQUIRE(d_flag, "nmt_adam_step: null flag");
   return launch_adam(ctx->master, ctx->m, ctx->v, ctx->acc, ctx->w16, ctx->P, lr, beta1, beta2, eps, t, d_flag,
-                     static_cast<hipStream_t>(stream));
+                     static_cast<hipStream_t>(stream), ctx->inv_scale);
 }
 
 extern "C" int nmt_gemm_timing(double* ms, int64_t* products, double* flops) { return gemm_timing_read(ms, products, flops); }
@@ -993,10 +996,10 @@ extern "C" int nmt_op_accumulate(const void* d_g16, float* d_acc32, int64_t n, i
 extern "C" int nmt_op_check_overflow(float* d_acc32, int64_t n, float inv_scale, int32_t* d_flag, void* stream) {
   return launch_check_overflow(d_acc32, n, inv_scale, d_flag, static_cast<hipStream_t>(stream));
 }
-extern "C" int nmt_op_adam(float* d_master32, float* d_m, float* d_v, const float* d_g32, void* d_w16, int64_t n, float lr,
-                           float beta1, float beta2, float eps, int32_t t, const int32_t* d_flag, void* stream) {
+extern "C" int nmt_op_adam(float* d_master32, float* d_m, float* d_v, const float* d_g32, float grad_scale, void* d_w16, int64_t n,
+                           float lr, float beta1, float beta2, float eps, int32_t t, const int32_t* d_flag, void* stream) {
   return launch_adam(d_master32, d_m, d_v, d_g32, static_cast<half_t*>(d_w16), n, lr, beta1, beta2, eps, t, d_flag,
-                     static_cast<hipStream_t>(stream));
+                     static_cast<hipStream_t>(stream), grad_scale);
 }
 extern "C" int nmt_op_dropout_mask(uint8_t* d_keep, int32_t rows, int32_t n_cols, const nmt_dropout* drop, void* stream) {
   NMT_TRY(check_drop(drop, "nmt_op_dropout_mask"));

@@ -70,8 +70,8 @@ __device__ __forceinline__ void load_presum(float (&y)[NCH][8], const half_t* __
     bits[i] = 0xFFu;
     if (c < chunks) {
       float s[8], r[8];
-      unpack8(ld_half8(sub + (size_t)row * d + c * 8), s);
-      unpack8(ld_half8(resid + (size_t)row * d + c * 8), r);
+      unpack8(ld_half8_nt(sub + (size_t)row * d + c * 8), s);
+      unpack8(ld_half8_nt(resid + (size_t)row * d + c * 8), r);
       if (drop.thr) bits[i] = drop_keep8(drop, (uint32_t)row, (uint32_t)c);
 #pragma unroll
       for (int e = 0; e < 8; ++e) y[i][e] = r[e] + (((bits[i] >> e) & 1u) ? s[e] * drop.scale : 0.f);
@@ -117,7 +117,7 @@ __global__ void __launch_bounds__(kThreads) res_ln_fwd_kernel(const half_t* __re
       unpack8(ld_half8(beta + c * 8), b);
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (y[i][e] - mean) * rstd * g[e] + b[e];
-      st_half8(out + (size_t)row * d + c * 8, pack8(o));
+      st_half8_nt(out + (size_t)row * d + c * 8, pack8(o));
     }
   }
   if (lane == 0) {
@@ -126,11 +126,13 @@ __global__ void __launch_bounds__(kThreads) res_ln_fwd_kernel(const half_t* __re
   }
 }
 
-// Backward.  Each wavefront walks groups of four rows (four rows in flight hide the load latency), keeps
-// per-lane column sums for dgamma, dbeta and the bias gradient in registers, and the block writes
-// one partial row per quantity (pitch NCH*512 floats, column-indexed).
-constexpr int kLnBwdMaxBlocks = 512;
-constexpr int kLnRows = 4;
+// Backward.  Each wavefront walks groups of kLnRows rows (their loads are all issued before anything is
+// computed), keeps per-lane column sums for dgamma, dbeta and the bias gradient in registers, and the block
+// writes one partial row per quantity (pitch NCH*512 floats, column-indexed).  The three inputs of a row stay in
+// registers as the fp16 values they were loaded as and are widened where they are used (twice: row statistics,
+// then the result), which keeps the kernel at four wavefronts per SIMD.
+constexpr int kLnBwdMaxBlocks = 1024;
+constexpr int kLnRows = 2;
 
 template <int NCH>
 __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __restrict__ dout, const half_t* __restrict__ sub,
@@ -141,36 +143,44 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
   extern __shared__ __align__(16) float red[];  // [3][NCH][64 lanes][8] = [3][NCH*512]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunks = d >> 3;
-  float sg[NCH][8], sb[NCH][8], sbias[NCH][8], gam[NCH][8];
+  float sg[NCH][8], sb[NCH][8], sbias[NCH][8];
+  half8_t gam[NCH];
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int c = lane + kWave * i;
-    if (c < chunks) unpack8(ld_half8(gamma + c * 8), gam[i]);
+    gam[i] = lane + kWave * i < chunks ? ld_half8(gamma + (lane + kWave * i) * 8) : zero_half8();
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      sg[i][e] = sb[i][e] = sbias[i][e] = 0.f;
-      if (c >= chunks) gam[i][e] = 0.f;
-    }
+    for (int e = 0; e < 8; ++e) sg[i][e] = sb[i][e] = sbias[i][e] = 0.f;
   }
   for (int row0 = (blockIdx.x * kWavesPerBlock + wave) * kLnRows; row0 < rows; row0 += gridDim.x * kWavesPerBlock * kLnRows) {
-    float y[kLnRows][NCH][8], go[kLnRows][NCH][8], mean[kLnRows], rstd[kLnRows], s1[kLnRows], s2[kLnRows];
+    half8_t hs[kLnRows][NCH], hr[kLnRows][NCH], hg[kLnRows][NCH];
     uint32_t bits[kLnRows][NCH];
+    float mean[kLnRows], rstd[kLnRows], s1[kLnRows], s2[kLnRows];
 #pragma unroll
     for (int u = 0; u < kLnRows; ++u) {
       const int row = min(row0 + u, rows - 1);  // a row past the end repeats the last one and is not written
-      load_presum<NCH>(y[u], sub, resid, row, d, lane, drop, bits[u]);
-      mean[u] = stats[2 * row];
-      rstd[u] = stats[2 * row + 1];
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        if (lane + kWave * i < chunks) {
-          unpack8(ld_half8(dout + (size_t)row * d + (lane + kWave * i) * 8), go[u][i]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) go[u][i][e] = 0.f;
-        }
+        const int c = lane + kWave * i;
+        const bool in = c < chunks;
+        hs[u][i] = in ? ld_half8_nt(sub + (size_t)row * d + c * 8) : zero_half8();
+        hr[u][i] = in ? ld_half8_nt(resid + (size_t)row * d + c * 8) : zero_half8();
+        hg[u][i] = in ? ld_half8_nt(dout + (size_t)row * d + c * 8) : zero_half8();
       }
+      mean[u] = stats[2 * row];
+      rstd[u] = stats[2 * row + 1];
     }
+#pragma unroll
+    for (int u = 0; u < kLnRows; ++u) {
+      const int row = min(row0 + u, rows - 1);
+#pragma unroll
+      for (int i = 0; i < NCH; ++i)
+        bits[u][i] = (drop.thr && lane + kWave * i < chunks) ? drop_keep8(drop, (uint32_t)row, (uint32_t)(lane + kWave * i)) : 0xFFu;
+    }
+    // normalised value of element e of chunk i of row u (the pre-normalisation sum is formed in fp32, as in the forward pass)
+    auto xhat = [&](int u, int i, int e) {
+      const float y = (float)hr[u][i][e] + (((bits[u][i] >> e) & 1u) ? (float)hs[u][i][e] * drop.scale : 0.f);
+      return (y - mean[u]) * rstd[u];
+    };
 #pragma unroll
     for (int u = 0; u < kLnRows; ++u) {
       const bool live = row0 + u < rows;
@@ -180,14 +190,13 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
         if (lane + kWave * i < chunks) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const float xh = (y[u][i][e] - mean[u]) * rstd[u];
-            y[u][i][e] = xh;  // keep the normalised value
-            const float g = go[u][i][e] * gam[i][e];
+            const float xh = xhat(u, i, e), go = (float)hg[u][i][e];
+            const float g = go * (float)gam[i][e];
             s1[u] += g;
             s2[u] += g * xh;
             if (live) {
-              sg[i][e] += go[u][i][e] * xh;
-              sb[i][e] += go[u][i][e];
+              sg[i][e] += go * xh;
+              sb[i][e] += go;
             }
           }
         }
@@ -201,6 +210,11 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
         s2[u] += __shfl_xor(s2[u], o, kWave);
       }
     }
+    // (the widened copies of the first pass are not kept: the inputs are widened again from their fp16 registers)
+#pragma unroll
+    for (int u = 0; u < kLnRows; ++u)
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) asm volatile("" : "+v"(hs[u][i]), "+v"(hr[u][i]), "+v"(hg[u][i]));
 #pragma unroll
     for (int u = 0; u < kLnRows; ++u) {
       const int row = row0 + u;
@@ -213,12 +227,12 @@ __global__ void __launch_bounds__(kThreads) res_ln_bwd_kernel(const half_t* __re
           float dy[8], dm[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            dy[e] = rstd[u] * (go[u][i][e] * gam[i][e] - m1 - y[u][i][e] * m2);
+            dy[e] = rstd[u] * ((float)hg[u][i][e] * (float)gam[i][e] - m1 - xhat(u, i, e) * m2);
             dm[e] = ((bits[u][i] >> e) & 1u) ? dy[e] * drop.scale : 0.f;
             sbias[i][e] += dm[e];
           }
-          st_half8(dy_out + (size_t)row * d + c * 8, pack8(dy));
-          if (dym_out) st_half8(dym_out + (size_t)row * d + c * 8, pack8(dm));
+          st_half8_nt(dy_out + (size_t)row * d + c * 8, pack8(dy));
+          if (dym_out) st_half8_nt(dym_out + (size_t)row * d + c * 8, pack8(dm));
         }
       }
     }
@@ -299,7 +313,7 @@ __global__ void __launch_bounds__(kThreads) colsum_kernel(const half_t* __restri
     for (; r + 3 * kWavesPerBlock < r1; r += 4 * kWavesPerBlock) {  // four independent loads in flight
       half8_t h[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) h[u] = ld_half8(src + (size_t)(r + u * kWavesPerBlock) * ld + col);
+      for (int u = 0; u < 4; ++u) h[u] = ld_half8_nt(src + (size_t)(r + u * kWavesPerBlock) * ld + col);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         float v[8];
@@ -769,8 +783,10 @@ int launch_residual_layernorm_bwd(const half_t* dout, const half_t* sub, const h
   NMT_REQUIRE(aligned16(dout) && aligned16(sub) && aligned16(resid) && aligned16(gamma) && aligned16(dy) && aligned16(dym),
               "layernorm_bwd: misaligned pointer");
   NMT_REQUIRE(!drop.thr || (drop.n_pos > 0 && dym), "layernorm_bwd: dropout needs the masked output and positions per sentence");
-  const int nblk = min(kLnBwdMaxBlocks, ceil_div(rows, kWavesPerBlock * kLnRows));
   const int nch = ln_nch(d);
+  // a grid that is resident at once (3 or 4 work-groups per compute unit fit, by registers): no second, partly filled round
+  const int resident = (nch >= 2 ? 3 : 4) * device_info().cus;
+  const int nblk = min(min(kLnBwdMaxBlocks, resident), ceil_div(rows, kWavesPerBlock * kLnRows));
   const dim3 grid(nblk), block(kThreads);
   const size_t smem = (size_t)3 * nch * 512 * sizeof(float);
   switch (nch) {

@@ -448,8 +448,15 @@ def test_adam_matches_oracle_and_skips_on_flag():
         assert rel_l2(host(m), omm["w"]) < 1e-6 and rel_l2(host(v), ov["w"]) < 1e-6
         assert (host(w16) == host(master).astype(np.float32).astype(np.float16).astype(np.float64)).all()
         assert rel_l2(host(w16), ref16) < 1e-3
+    # the gradient's scale factor is applied as it is read: g * 1024 with factor 1/1024 is the same update, bit for bit
+    g = rng.normal(size=n).astype(np.float32)
+    twin = [t_.clone() for t_ in (master, m, v, w16)]
+    A.nmt_op_adam(master, m, v, dev32(g), w16, n, 5e-4, 0.9, 0.98, 1e-8, 4, flag)
+    A.nmt_op_adam(twin[0], twin[1], twin[2], dev32(g * np.float32(1024)), twin[3], n, 5e-4, 0.9, 0.98, 1e-8, 4, flag, grad_scale=1.0 / 1024)
+    for a_, b_ in zip((master, m, v, w16), twin):
+        assert (host(a_) == host(b_)).all()
     snap = [host(t_) for t_ in (master, m, v, w16)]
     flag.fill_(1)
-    A.nmt_op_adam(master, m, v, dev32(rng.normal(size=n).astype(np.float32)), w16, n, 5e-4, 0.9, 0.98, 1e-8, 4, flag)
+    A.nmt_op_adam(master, m, v, dev32(rng.normal(size=n).astype(np.float32)), w16, n, 5e-4, 0.9, 0.98, 1e-8, 5, flag)
     for before, t_ in zip(snap, (master, m, v, w16)):
         assert (host(t_) == before).all()

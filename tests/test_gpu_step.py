@@ -158,10 +158,13 @@ def _step_parity(model_name, batches, weights, act_dropout=0.0, seed=0, loss_sca
     om = {k: np.zeros_like(v) for k, v in P16.items()}
     ov = {k: np.zeros_like(v) for k, v in P16.items()}
     O.adam_step(master, om, ov, g_ref, lr, 0.9, 0.98, 1e-8, t, flag_ref)
-    sess.check_overflow(1.0 / (loss_scale * ntok_gpu))
+    acc_before = sess.acc.clone()
+    inv_scale = 1.0 / (loss_scale * ntok_gpu)
+    sess.check_overflow(inv_scale)
     assert int(sess.flag.item()) == flag_ref == 0
+    assert torch.equal(sess.acc.view(torch.int32), acc_before.view(torch.int32))      # the check only reads; Adam applies the factor
     g_gpu = sess.named(sess.acc)
-    g_gpu = {k: v.astype(np.float64).reshape(P16[k].shape) for k, v in g_gpu.items()}
+    g_gpu = {k: (v * np.float32(inv_scale)).astype(np.float64).reshape(P16[k].shape) for k, v in g_gpu.items()}
     sess.adam_step(lr, t)
     check_master_weights(sess, master, f"{what}: master weights")
     # the Adam kernel alone: the oracle's Adam fed with the GPU's own fp32 gradient
