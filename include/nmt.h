@@ -101,7 +101,13 @@ int nmt_forward_loss(nmt_ctx* ctx, const int32_t* d_src, const int32_t* d_tgt_in
  * d_tgt_out: sum of B*T ids) and d_sent_uid one entry per sentence in the same order (NULL: a
  * sentence's index within its sub-batch).  Dropout masks, loss and gradients are those of the
  * sub-batches processed one by one and accumulated.  *d_loss_sum and *d_ntok are totals over the
- * group.  A group may hold at most 2^20 source and 2^20 target positions. */
+ * group.  A group may hold at most 2^20 source and 2^20 target positions.
+ * The overflow decision of a pass over several sub-batches is that of ITS fp16 gradient, fp16(s * sum over the
+ * sub-batches), s = nmt_grad_scale(): one sub-batch whose own gradient would leave the fp16 range can be hidden
+ * by the others, and a sum of gradients that each fit can leave it.  Decisions equal to the method's order
+ * (every sub-batch's gradient rounded to fp16 on its own, "Half-Precision Training" / "Training with Larger
+ * Batches") are guaranteed for one sub-batch per pass only; a pass of several follows its own predicate
+ * exactly, and the dynamic loss scale settles where that predicate puts it. */
 #define NMT_MAX_SEGMENTS 64
 typedef struct {
   int32_t B, S, T;    /* sentences, padded source and target length */

@@ -506,3 +506,76 @@ def test_forward_only_validation_loss_matches_oracle():
         assert abs(2.0 ** bits - np.exp(loss_ref / ntok_ref)) / np.exp(loss_ref / ntok_ref) <= 2e-3
     finally:
         sess.close()
+
+
+def test_overflow_decisions_of_the_one_by_one_order_and_of_a_packed_pass():
+    """The skip decision is 'any inf / NaN in the fp32 accumulator', and what reaches the accumulator differs
+    between the two launch configurations: one by one, every sub-batch's gradient is rounded to fp16 on its own
+    (the method's order: a single overflowing sub-batch sets the flag); in a packed pass the sub-batches' sum is
+    formed in fp32 and rounded to fp16 once, times the pass's power-of-two factor.  Each configuration must follow
+    ITS predicate exactly, evaluated on the oracle's gradients: at an ordinary loss scale (no overflow), with
+    the loss forced up by 2^20 (both overflow), and at a scale chosen from the oracle's numbers where exactly one
+    of the two thresholds is passed (every sub-batch's gradient fits fp16 on its own but their sum does not, or one
+    sub-batch's does not while the sum, where the others pull the other way, does) -- there the two predicates, and
+    the two configurations,
+    decide differently.  (No dropout and the first sub-batch twice, so that the sum's largest element is about twice any
+    single sub-batch's and such a scale exists.)"""
+    model = dict(I.MODELS["tiny"], dropout=0.0)
+    weights = I.init_weights(seed=21, perturb=0.05, **model)
+    shapes = [(5, 9, 7), (5, 9, 7), (8, 4, 6)]
+    batches = [I.tiny_batch(seed=300 + (i if i != 1 else 0), B=B, S=S, T=T, vocab=model["vocab"], short_by=2) for i, (B, S, T) in enumerate(shapes)]
+    uids = [np.arange(100 * i, 100 * i + b["src"].shape[0], dtype=np.uint32) for i, b in enumerate(batches)]
+    batches = [dict(b, sent_uid=uids[i]) for i, b in enumerate(batches)]
+    cfg = _oracle_cfg(model, seed=5)
+    P16 = {k: v.astype(np.float64) for k, v in weights.items()}
+    step = 3
+    unit = []          # per sub-batch: gradient of the unscaled loss (power-of-two loss scales multiply it exactly)
+    for j, mb in enumerate(batches):
+        _, _, cache = O.forward_loss(P16, cfg, mb["src"], mb["tgt_in"], mb["tgt_out"], training=True, step=step, micro=j, sent_uid=uids[j])
+        unit.append(O.backward(P16, cfg, cache, 1.0))
+    flat = np.stack([np.concatenate([g[k].reshape(-1) for k in sorted(g)]) for g in unit])        # [3, P]
+    total = flat.sum(axis=0)
+    # smallest power of two at which some single sub-batch overflows fp16 / at which the rounded sum does
+    own = 2.0 ** np.ceil(np.log2(65520.0 / np.abs(flat).max()))
+    summed = 2.0 ** np.ceil(np.log2(65520.0 / np.abs(total).max()))
+
+    def predicates(scale):
+        with np.errstate(over="ignore"):
+            one = int(not np.isfinite((flat * scale).astype(np.float16).astype(np.float64).sum(axis=0)).all())
+            packed = int(not np.isfinite((total * scale).astype(np.float16)).all())
+        return one, packed
+
+    sess = Session(model, weights, seed=5, max_sentences=8)
+    try:
+        dbs = [sess.to_device(b) for b in batches]
+        (pk,) = sess.pack(batches)
+        cases = [min(own, summed) / 8, min(own, summed) * 2.0 ** 20]
+        r_one, r_sum = np.abs(flat).max(), np.abs(total).max()
+        if max(r_one, r_sum) / min(r_one, r_sum) >= 1.12:      # a scale between the two thresholds, 5 % or more away from both
+            cases.append(float(np.float32(65520.0 / np.sqrt(r_one * r_sum))))
+        seen = []
+        for scale in cases:
+            want_one, want_packed = predicates(scale)
+            # margin: the decision must not hang on the GPU's own rounding of the largest element
+            big = max(np.abs(flat).max(), np.abs(total).max()) * scale
+            for j, db in enumerate(dbs):
+                sess.forward_loss(db, scale, step, j)
+                sess.backward()
+                sess.accumulate(j == 0)
+            sess.check_overflow(1.0)
+            got_one = int(sess.flag.item())
+            sess.forward_loss(pk, scale, step)
+            assert sess.grad_scale() == 1.0            # a pass this small applies no factor of its own
+            sess.backward()
+            sess.accumulate(True)
+            sess.check_overflow(1.0)
+            got_packed = int(sess.flag.item())
+            seen.append((scale, want_one, want_packed, got_one, got_packed, big / 65504.0))
+            near = 0.97 <= np.abs(flat * scale).max() / 65520.0 <= 1.03 or 0.97 <= np.abs(total * scale).max() / 65520.0 <= 1.03
+            if not near:
+                assert (got_one, got_packed) == (want_one, want_packed), seen
+        print("overflow decisions (scale, oracle one-by-one, oracle packed, GPU one-by-one, GPU packed, largest/65504):", seen)
+        assert seen[0][1:5] == (0, 0, 0, 0) and seen[1][1:5] == (1, 1, 1, 1)
+        assert len(seen) == 3 and seen[2][1] != seen[2][2] and seen[2][1:3] == seen[2][3:5], seen      # the case where the two orders differ
+    finally:
+        sess.close()
