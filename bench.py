@@ -204,6 +204,7 @@ def main():
                                             read_profile_traffic() if (args.workload == "big_accum" and packed and group == 16) else None)
         result["roofline"]["by_shape"] = gemm_leg(model, pass_rows, A, torch, log)
         result["hbm_kernels"] = hbm_leg(sess, torch)
+        result["fp32_comparison"] = fp32_leg(model, pass_rows, result["roofline"]["ms_per_update"], A, torch, log)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(model, weights, batches[:2], tokens_per_step, tr.scale, log)
     if result["roofline"] is None:      # --no-legs: only the end-to-end rate is known
@@ -227,23 +228,29 @@ def _timed(torch, fn, reps):
 
 def strict_leg(model, weights, batches, ntoks, shapes, steps, Session, Trainer, torch, log):
     """The same update in the method's literal order ("Training with Larger Batches"): the 16 padded sub-batches one by
-    one (forward + loss, backward, accumulate each; three in flight on separate streams, accumulation chained in
+    one (forward + loss, backward, accumulate each; four in flight on separate streams, accumulation chained in
     sub-batch order), then overflow check + Adam.  Timed over the same number of steps as the headline; the time
     of each of the five calls summed over one update comes from a serial (one sub-batch in flight) pass."""
-    sess = Session(model, weights, max_sentences=max(b["src"].shape[0] for b in batches), max_len=256, n_pipes=min(3, len(batches)))
+    import paper_1806_00187_amd as A
+    sess = Session(model, weights, max_sentences=max(b["src"].shape[0] for b in batches), max_len=256, n_pipes=min(4, len(batches)))
     dbs = [sess.to_device(b) for b in batches]
     for b in batches:
         sess.reserve(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1])
     tr = Trainer(sess, peak_lr=1e-3, warmup=4000, init_scale=128.0)
-    for _ in range(12):                                  # settle the loss scale
-        if not tr.step(dbs, n_tok=sum(ntoks))[2]:
-            break
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record(torch.cuda.current_stream())
-    flags = [tr.step(dbs, n_tok=sum(ntoks))[2] for _ in range(steps)]
-    e1.record(torch.cuda.current_stream())
-    torch.cuda.synchronize()
+    # four sub-batches in flight already fill the hardware queues: each one's weight gradients stay on its own stream
+    A.nmt_tuning("one_stream", 1)
+    try:
+        for _ in range(12):                                  # settle the loss scale
+            if not tr.step(dbs, n_tok=sum(ntoks))[2]:
+                break
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(torch.cuda.current_stream())
+        flags = [tr.step(dbs, n_tok=sum(ntoks))[2] for _ in range(steps)]
+        e1.record(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+    finally:
+        A.nmt_tuning("one_stream", 0)
     ms = e0.elapsed_time(e1) / steps
     sess.close()
     # per-call times of the 16-call path (serial, so that the events of one call do not cover another's kernels)
@@ -255,8 +262,8 @@ def strict_leg(model, weights, batches, ntoks, shapes, steps, Session, Trainer, 
     serial.close()
     flops = sum(model_flops(model, *s_) for s_ in shapes)
     tflops = flops / (ms * 1e-3) / 1e12
-    log(f"[bench] strict order (16 padded sub-batches one by one, 3 in flight): {ms:.2f} ms/update, {tflops:.1f} TFLOP/s, loss scale {tr.scale}")
-    return {"what": "16 x (forward+loss, backward, accumulate) over the padded sub-batches one by one (3 in flight), then overflow check + Adam",
+    log(f"[bench] strict order (16 padded sub-batches one by one, 4 in flight): {ms:.2f} ms/update, {tflops:.1f} TFLOP/s, loss scale {tr.scale}")
+    return {"what": "16 x (forward+loss, backward, accumulate) over the padded sub-batches one by one (4 in flight), then overflow check + Adam",
             "ms_per_step": ms, "value": sum(ntoks) / (ms * 1e-3), "unit": "tokens/s", "steps": steps, "loss_scale": tr.scale,
             "overflow_updates": int(sum(flags)), "achieved_tflops": tflops, "frac_of_fp16_peak": tflops / PEAK_FP16_TFLOPS,
             "phases_ms_per_update_serial": phases}
@@ -381,6 +388,42 @@ def gemm_leg(model, pass_rows, A, torch, log):
     return {"what": "each distinct shape timed alone on random operands", "achieved": achieved, "frac": achieved / PEAK_FP16_TFLOPS,
             "launches_per_update": n_launch, "avg_launch_us": tot_ms * 1e3 / n_launch, "ms_per_update": tot_ms,
             "by_kind_tflops": {k: v[0] / v[1] / 1e9 for k, v in per_kind.items()}, "worst_tflops": worst, "best_tflops": best}
+
+
+PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (published)
+
+
+def fp32_leg(model, pass_rows, fp16_gemm_ms, A, torch, log):
+    """What the paper measures first ("Half-Precision Training"; Table 1, "Our reimplementation" against "16-bit"): the
+    same work in fp32.  Every GEMM shape of the update through the benchmark-only fp32 product (fp32 matrix
+    instructions, fp32 operands and result), timed alone; set against the fp16 products of the timed step."""
+    agg = {}
+    for s_ in pass_rows:
+        for (M, N, K, a_t, b_t, count, _) in gemm_shapes(model, *s_):
+            agg[(M, N, K, a_t, b_t)] = agg.get((M, N, K, a_t, b_t), 0) + count
+    tot_ms = tot_fl = 0.0
+    for (M, N, K, a_t, b_t), count in agg.items():
+        ra, ca = (K, M) if a_t else (M, K)
+        rb, cb = (K, N) if b_t else (N, K)
+        ca4, cb4 = (ca + 3) // 4 * 4, (cb + 3) // 4 * 4
+        a = torch.randn(ra, ca4, device="cuda", dtype=torch.float32)
+        b = torch.randn(rb, cb4, device="cuda", dtype=torch.float32) * 0.03
+        # a weight gradient (small result, contraction over all positions) is cut along k as in the fp16 step
+        tiles = -(-M // 128) * -(-N // 128)
+        splits = max(1, min(64, 1024 // tiles, K // 512)) if (a_t and b_t) else 1
+        c = torch.empty(splits * M, N, device="cuda", dtype=torch.float32)
+        ms = _timed(torch, lambda: A.nmt_op_gemm_f32(a, a_t, ca4, b, b_t, cb4, c, N, M, N, K, splits), 2)
+        tot_ms += ms * count
+        tot_fl += 2.0 * M * N * K * count
+        del a, b, c
+    tflops = tot_fl / tot_ms / 1e9
+    log(f"[bench] fp32 comparison: the update's GEMMs in fp32 take {tot_ms:.1f} ms ({tflops:.1f} TFLOP/s) against {fp16_gemm_ms:.1f} ms in fp16: "
+        f"{tot_ms / fp16_gemm_ms:.1f}x")
+    return {"what": "every GEMM product of the update with fp32 operands on the fp32 matrix instructions (benchmark-only kernel), each shape timed alone",
+            "gemm_ms_per_update_fp32": tot_ms, "achieved": tflops, "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
+            "frac": tflops / PEAK_FP32_MATRIX_TFLOPS, "gemm_ms_per_update_fp16": fp16_gemm_ms,
+            "fp16_speedup_on_the_gemms": tot_ms / fp16_gemm_ms,
+            "paper": "2.9x shorter training with 16-bit at equal settings on 8 x V100 (Table 1, 'Our reimplementation' vs '16-bit')"}
 
 
 def hbm_leg(sess, torch):

@@ -245,6 +245,16 @@ int nmt_op_gemm_splitk(const void* d_A, int32_t a_t, int32_t lda, const void* d_
                        void* d_C, int32_t ldc, int32_t M, int32_t N, int32_t K, float* d_partial,
                        int64_t partial_floats, int32_t splits, void* stream);
 
+/* The same product with fp32 operands and an fp32 result, no epilogue: C[M,N] = sum_k A(m,k) B(n,k) on the fp32
+ * matrix instructions.  Benchmark only -- the training step never calls it: it times what the step's products cost
+ * without half precision ("Half-Precision Training" compares fp32 and fp16 training at equal settings; Table 1,
+ * rows "Our reimplementation" and "16-bit").  Operands 16-byte aligned, leading dimensions multiples of 4.
+ * splits (1..64) > 1 cuts the contraction into that many pieces (the form a weight gradient over many positions
+ * needs to fill the chip): piece z writes its partial product to rows [z*M, (z+1)*M) of d_C, which then holds
+ * splits * M rows; the caller sums them. */
+int nmt_op_gemm_f32(const float* d_A, int32_t a_t, int32_t lda, const float* d_B, int32_t b_t, int32_t ldb,
+                    float* d_C, int32_t ldc, int32_t M, int32_t N, int32_t K, int32_t splits, void* stream);
+
 /* Masked multi-head attention forward.  Q [B*Tq, *] with row stride ldq (head h at columns
  * h*dh..), K, V [B*Tk, *]; O [B*Tq, *]; d_lse fp32 = log-sum-exp of the scaled
  * scores, stored [H, B*Tq] (head-major).  Key j of sentence b is hidden iff d_key_ids[b*Tk + j] == pad_id, or causal != 0 and

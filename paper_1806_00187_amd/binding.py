@@ -65,6 +65,7 @@ _SIGNATURES = {
     "nmt_scaler_update": (C.c_int, [C.POINTER(C.c_float), C.POINTER(_I32), _I32, _I32]),
     "nmt_lr_schedule": (C.c_double, [_I64, C.c_double, _I64]),
     "nmt_op_gemm": (C.c_int, [_P, _I32, _I32, _P, _I32, _I32, _P, _I32, _I32, _I32, _I32, _P, _I32, _DP, _P, _P, _F, _P]),
+    "nmt_op_gemm_f32": (C.c_int, [_P, _I32, _I32, _P, _I32, _I32, _P, _I32, _I32, _I32, _I32, _I32, _P]),
     "nmt_op_gemm_splitk": (C.c_int, [_P, _I32, _I32, _P, _I32, _I32, _P, _I32, _I32, _I32, _I32, _P, _I64, _I32, _P]),
     "nmt_op_attention_fwd": (C.c_int, [_P, _I32, _P, _I32, _P, _I32, _P, _I32, _P, _P, _I32, _I32, _I32, _I32, _I32, _I32, _I32, _P]),
     "nmt_op_attention_bwd": (C.c_int, [_P, _I32, _P, _I32, _P, _I32, _P, _I32, _P, _I32, _P, _P, _I32, _P, _I32, _P, _I32, _P,
@@ -279,6 +280,10 @@ def nmt_op_gemm(A, a_t, lda, B, b_t, ldb, Cout, ldc, M, N, K, bias=None, relu=Fa
                 mask_scale=1.0, stream=None):
     _check(load().nmt_op_gemm(_p(A), int(a_t), lda, _p(B), int(b_t), ldb, _p(Cout), ldc, M, N, K, _p(bias), int(relu), _drop(drop),
                               _p(add), _p(relu_src), mask_scale, _stream(stream)))
+
+
+def nmt_op_gemm_f32(A, a_t, lda, B, b_t, ldb, Cout, ldc, M, N, K, splits=1, stream=None):
+    _check(load().nmt_op_gemm_f32(_p(A), int(a_t), lda, _p(B), int(b_t), ldb, _p(Cout), ldc, M, N, K, splits, _stream(stream)))
 
 
 def nmt_op_gemm_splitk(A, a_t, lda, B, b_t, ldb, Cout, ldc, M, N, K, partial, splits=0, stream=None):

@@ -164,6 +164,10 @@ int launch_gemm(const half_t* A, bool a_t, int lda, const half_t* B, bool b_t, i
                 int M, int N, int K, const GemmEpilogue& ep, hipStream_t stream, float* partial = nullptr,
                 int64_t partial_floats = 0, int splits = 1);
 
+// fp32 product on the matrix cores, for the benchmark's fp32 comparison leg (not used by the training step)
+int launch_gemm_f32(const float* A, bool a_t, int lda, const float* B, bool b_t, int ldb, float* C, int ldc, int M, int N, int K,
+                    int splits, hipStream_t stream);
+
 // Sum of the event-bracketed durations of the products launched since the last call (tuning().gemm_timing), their
 // number and their algorithmic FLOPs; waits for them to finish.
 int gemm_timing_read(double* ms, int64_t* products, double* flops);

@@ -903,6 +903,11 @@ extern "C" int nmt_op_gemm(const void* d_A, int32_t a_t, int32_t lda, const void
                      static_cast<half_t*>(d_C), ldc, M, N, K, ep, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int nmt_op_gemm_f32(const float* d_A, int32_t a_t, int32_t lda, const float* d_B, int32_t b_t, int32_t ldb, float* d_C,
+                               int32_t ldc, int32_t M, int32_t N, int32_t K, int32_t splits, void* stream) {
+  return launch_gemm_f32(d_A, a_t != 0, lda, d_B, b_t != 0, ldb, d_C, ldc, M, N, K, splits, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int nmt_op_gemm_splitk(const void* d_A, int32_t a_t, int32_t lda, const void* d_B, int32_t b_t, int32_t ldb, void* d_C,
                                   int32_t ldc, int32_t M, int32_t N, int32_t K, float* d_partial, int64_t partial_floats,
                                   int32_t splits, void* stream) {

@@ -56,6 +56,35 @@ def test_gemm_matches_oracle(M, N, K, mode):
     assert_close16(host(dC), Am @ Bm.T, f"gemm {mode} {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,N,K", [(128, 128, 16), (200, 136, 72), (37, 1000, 66), (515, 264, 203), (1031, 2052, 1024)])
+@pytest.mark.parametrize("mode", ["fwd", "dgrad", "wgrad"])
+def test_fp32_comparison_gemm_matches_oracle(M, N, K, mode):
+    """The benchmark-only fp32 product (fp32 matrix instructions) in the three operand layouts of a linear layer."""
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    a_t, b_t = {"fwd": (0, 0), "dgrad": (0, 1), "wgrad": (1, 1)}[mode]
+    r4 = lambda n: (n + 3) // 4 * 4
+    Am, Bm = rng.normal(size=(M, K)).astype(np.float32), (rng.normal(size=(N, K)) / math.sqrt(K)).astype(np.float32)
+    # leading dimensions are multiples of 4: pad the stored matrices' contiguous dimension
+    def stored(X, t):
+        Y = X.T if t else X
+        out = np.zeros((Y.shape[0], r4(Y.shape[1])), dtype=np.float32)
+        out[:, :Y.shape[1]] = Y
+        return dev32(out), out.shape[1]
+    dA, lda = stored(Am, a_t)
+    dB, ldb = stored(Bm, b_t)
+    ldc = r4(N)
+    dC = torch.full((M, ldc), float("nan"), dtype=torch.float32, device=DEV)
+    A.nmt_op_gemm_f32(dA, a_t, lda, dB, b_t, ldb, dC, ldc, M, N, K)
+    got, want = host(dC)[:, :N], Am.astype(np.float64) @ Bm.astype(np.float64).T
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (mode, M, N, K, np.abs(got - want).max())
+    if K >= 66:     # the contraction cut into three pieces: the partial products add up to the same
+        parts = torch.full((3 * M, ldc), float("nan"), dtype=torch.float32, device=DEV)
+        A.nmt_op_gemm_f32(dA, a_t, lda, dB, b_t, ldb, parts, ldc, M, N, K, splits=3)
+        got = host(parts).reshape(3, M, ldc)[:, :, :N].sum(axis=0)
+        assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (mode, "3 pieces")
+
+
 @pytest.mark.parametrize("M,N,K,splits", [(136, 264, 3003, 3), (256, 128, 8192, 0), (64, 64, 4500, 64), (1024, 512, 6000, 5),
                                             (2048, 2040, 1500, 3), (1024, 1024, 16384, 0)])  # the last two: large-tile kernel
 def test_gemm_split_along_k_matches_oracle(M, N, K, splits):
