@@ -477,9 +477,30 @@ __device__ __forceinline__ int clamp_id(int id, int vocab) { return id < 0 ? 0 :
 __device__ __forceinline__ int id_at(const int32_t* a, int na, const int32_t* b, int i, int vocab) {
   return clamp_id(i < na ? a[i] : b[i - na], vocab);
 }
-__global__ void __launch_bounds__(kThreads) emb_hist_kernel(const int32_t* a, int na, const int32_t* b, int nb, int vocab, int32_t* cnt) {
-  const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i < na + nb) atomicAdd(&cnt[id_at(a, na, b, i, vocab)], 1);
+// Histogram of the ids.  A frequent id (the end-of-sentence symbol, the most common word) would serialise one global
+// atomic per occurrence; each block therefore counts its contiguous share of the positions in LDS first, two 16-bit
+// counters per word (a block takes at most 65535 positions, so a counter cannot carry into its neighbour), and then
+// adds its non-zero counts to the global ones: one global atomic per (block, id that occurs in it).  Integer sums:
+// the result does not depend on the order.
+constexpr int kHistThreads = 1024;
+constexpr int kHistMaxPerBlock = 32768;
+__global__ void __launch_bounds__(kHistThreads) emb_hist_kernel(const int32_t* a, int na, const int32_t* b, int nb, int vocab, int per_block,
+                                                                int32_t* cnt) {
+  extern __shared__ uint32_t hist[];  // (vocab + 1) / 2 words
+  const int words = (vocab + 1) >> 1;
+  for (int w = threadIdx.x; w < words; w += kHistThreads) hist[w] = 0u;
+  __syncthreads();
+  const int n = na + nb, lo = min(n, (int)blockIdx.x * per_block), hi = min(n, lo + per_block);
+  for (int i = lo + (int)threadIdx.x; i < hi; i += kHistThreads) {
+    const int id = id_at(a, na, b, i, vocab);  // clamped to [0, vocab)
+    atomicAdd(&hist[id >> 1], 1u << (16 * (id & 1)));
+  }
+  __syncthreads();
+  for (int w = threadIdx.x; w < words; w += kHistThreads) {
+    const uint32_t v = hist[w];
+    if (v & 0xFFFFu) atomicAdd(&cnt[2 * w], (int32_t)(v & 0xFFFFu));
+    if ((v >> 16) && 2 * w + 1 < vocab) atomicAdd(&cnt[2 * w + 1], (int32_t)(v >> 16));
+  }
 }
 // exclusive scan of cnt[0..V) into start[0..V]; single block of 1024 threads
 // (start may be cnt itself)
@@ -922,8 +943,17 @@ int launch_embed_bwd(const int32_t* ids_a, const half_t* dx_a, int rows_a, const
   float* part = reinterpret_cast<float*>(scratch + e.part);
   hipLaunchKernelGGL(fill_int_kernel, dim3(ceil_div(vocab, kThreads)), dim3(kThreads), 0, stream, cnt, vocab, 0);
   NMT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(emb_hist_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, stream, ids_a, rows_a, ids_b, rows_b, vocab, cnt);
-  NMT_LAUNCH_CHECK();
+  {
+    // one block per compute unit, more if a block's share would exceed what its 16-bit counters hold
+    int blocks = device_info().cus;
+    if (ceil_div(n, blocks) > kHistMaxPerBlock) blocks = ceil_div(n, kHistMaxPerBlock);
+    const int per_block = ceil_div(n, blocks);
+    const size_t hist_bytes = (size_t)((vocab + 1) / 2) * sizeof(uint32_t);
+    if (hist_bytes > 64 * 1024)
+      NMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(emb_hist_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)hist_bytes));
+    hipLaunchKernelGGL(emb_hist_kernel, dim3(blocks), dim3(kHistThreads), hist_bytes, stream, ids_a, rows_a, ids_b, rows_b, vocab, per_block, cnt);
+    NMT_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, stream, cnt, start, vocab);
   NMT_LAUNCH_CHECK();
   // stable sort of the positions by id: low byte, then high byte
