@@ -199,7 +199,9 @@ int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_pt
  * 1 where the epilogue loads nothing per element / 2 always the persistent GEMM form; default 1),
  * "attn_persist" (0: one attention work item per work-group; default 1), "worklists" (0: attention
  * kernels enumerate every (sentence, tile); default 1), "one_stream" (1: nmt_backward enqueues the weight
- * gradients on the caller's stream; default 0), "gemm_timing" (1: every GEMM product is bracketed by a pair of
+ * gradients on the caller's stream; default 0), "gemm_share" (1..16, default 1: the number of products a
+ * caller keeps running side by side on streams of its own; large tiles are then chosen as if each product had
+ * that fraction of the compute units), "gemm_timing" (1: every GEMM product is bracketed by a pair of
  * HIP events on the stream it is launched on; default 0), "defaults" (value ignored: all of the above back to
  * default).  Unknown names and values out of range return NMT_EINVAL. */
 int nmt_tuning(const char* name, int32_t value);

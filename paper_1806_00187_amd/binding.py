@@ -253,8 +253,20 @@ def nmt_gemm_timing():
     return ms.value, n.value, fl.value
 
 
+_TUNING_SET = {}   # what this process has set through nmt_tuning (the library has no call that reads a switch back)
+
+
 def nmt_tuning(name, value=0):
     _check(load().nmt_tuning(name.encode(), int(value)))
+    if name == "defaults":
+        _TUNING_SET.clear()
+    else:
+        _TUNING_SET[name] = int(value)
+
+
+def tuning_value(name, default):
+    """The value last set for a launch-form switch through nmt_tuning, or `default` (the library's) if none was."""
+    return _TUNING_SET.get(name, default)
 
 
 def nmt_check_overflow(ctx, inv_scale, flag, stream=None):

@@ -21,6 +21,10 @@
 
 #include "common.h"
 
+#include <atomic>
+#include <mutex>
+#include <unordered_map>
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -589,8 +593,16 @@ constexpr size_t dkv_smem() { return (size_t)4 * (2 * 32 * (DH + 8) * sizeof(hal
 
 template <typename Kern>
 int allow_big_lds(Kern kern, size_t bytes) {
-  if (bytes > 64 * 1024)
-    NMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  if (bytes <= 64 * 1024) return NMT_OK;
+  // asked of the runtime once per kernel and size, not once per launch (callers may launch from several threads)
+  static std::mutex mu;
+  static std::unordered_map<const void*, size_t> allowed;
+  const void* key = reinterpret_cast<const void*>(kern);
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = allowed.find(key);
+  if (it != allowed.end() && it->second >= bytes) return NMT_OK;
+  NMT_HIP_CHECK(hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  allowed[key] = bytes;
   return NMT_OK;
 }
 
@@ -628,9 +640,12 @@ int fwd_launch(const AttnArgs& a0, hipStream_t stream) {
     a.vgx = (int)(qtile_bound(a.B, a.Nq, a.Tq) * ((a.H + 3) / 4));
     a.vgy = 1;
   }
-  static int resident = 0;  // (per head size: the function is a template)
-  if (!resident)
+  static std::atomic<int> resident_once{0};  // (per head size: the function is a template)
+  int resident = resident_once.load(std::memory_order_relaxed);
+  if (!resident) {
     if (int rc = resident_blocks(attn_fwd_kernel<DH>, kThreads, tile_smem<DH>(), &resident)) return rc;
+    resident_once.store(resident, std::memory_order_relaxed);
+  }
   const int64_t total = (int64_t)a.vgx * a.vgy;
   NMT_REQUIRE(total < (1ll << 31), "attention_fwd: too many work items");
   const int64_t grid = (total < resident || !tuning().attn_persist) ? total : resident;  // (not persistent: one work item per work-group)
@@ -648,9 +663,12 @@ int fused_launch(const AttnArgs& a, int n_k_rows, hipStream_t stream) {
   AttnArgs b = a;
   b.vgx = (int)(n * ((a.H + kWaves - 1) / kWaves));
   b.vgy = 1;
-  static int resident = 0;
-  if (NT <= 2 && !resident)
+  static std::atomic<int> resident_once{0};
+  int resident = resident_once.load(std::memory_order_relaxed);
+  if (NT <= 2 && !resident) {
     if (int rc = resident_blocks(attn_bwd_fused_kernel<DH, NT>, 64 * kWaves, smem, &resident)) return rc;
+    resident_once.store(resident, std::memory_order_relaxed);
+  }
   // (the instances for longer sentences, and everything with the persistent form switched off: one item per work-group)
   const int grid = (NT > 2 || b.vgx < resident || !tuning().attn_persist) ? b.vgx : resident;
   hipLaunchKernelGGL((attn_bwd_fused_kernel<DH, NT>), dim3((unsigned)grid), dim3(64 * kWaves), smem, stream, b);

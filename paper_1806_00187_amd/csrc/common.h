@@ -52,6 +52,8 @@ struct Tuning {
   int attn_persist = 1;   // 0: one attention work item per work-group
   int worklists = 1;      // 0: attention kernels enumerate every (sentence, tile) instead of taking work lists
   int one_stream = 0;     // 1: the backward pass's weight-gradient kernels run on the caller's stream, not beside it
+  int gemm_share = 1;     // products expected to run side by side (callers that keep several passes in flight): large tiles
+                          // are chosen as if each product had 1/gemm_share of the compute units
   int gemm_timing = 0;    // 1: every GEMM product is bracketed by HIP events on its launch stream (nmt_gemm_timing reads them)
 };
 Tuning& tuning();

@@ -749,7 +749,8 @@ int launch_tile(const GemmArgs& a, bool a_t, bool b_t, int splits, hipStream_t s
   g.group_m = tuning().gemm_group;
   g.xcds = device_info().xcds;
   if (splits > 1) {
-    g.k_chunk = (int)round_up(ceil_div(g.K, splits), BK);
+    static_assert(64 % BK == 0, "the k range of a split is a multiple of 64 whatever the tile, so that the tile shape changes no bit");
+    g.k_chunk = (int)round_up(ceil_div(g.K, splits), 64);
     splits = ceil_div(g.K, g.k_chunk);  // no empty split
   }
   if (splits <= 1) {
@@ -827,7 +828,9 @@ int launch_gemm_impl(const half_t* A, bool a_t, int lda, const half_t* B, bool b
   }
   NMT_REQUIRE(splits == 1 || plane * splits <= partial_floats, "gemm: partial-sum buffer of %lld floats too small for %d splits",
               (long long)partial_floats, splits);
-  if (t256 * splits >= full) {
+  // (a caller that keeps several passes in flight says so: each product then counts on its share of the chip)
+  const int64_t full_shared = full / tuning().gemm_share > 1 ? full / tuning().gemm_share : 1;
+  if (t256 * splits >= full_shared) {
     // A last, partly filled round of 256 x 256 tiles leaves compute units idle for a whole tile's
     // time.  If that round is small, the rows it would cover are given to a second launch with small
     // tiles (two work-groups per compute unit), which costs about a third of a round.

@@ -44,6 +44,7 @@ extern "C" int nmt_tuning(const char* name, int32_t value) {
   else if (!strcmp(name, "attn_persist")) t.attn_persist = value != 0;
   else if (!strcmp(name, "worklists")) t.worklists = value != 0;
   else if (!strcmp(name, "one_stream")) t.one_stream = value != 0;
+  else if (!strcmp(name, "gemm_share")) { NMT_REQUIRE(value >= 1 && value <= 16, "nmt_tuning: gemm_share must be in [1, 16]"); t.gemm_share = value; }
   else if (!strcmp(name, "gemm_timing")) t.gemm_timing = value != 0;
   else if (!strcmp(name, "defaults")) t = Tuning{};
   else NMT_REQUIRE(false, "nmt_tuning: unknown switch '%s'", name);
@@ -341,6 +342,8 @@ extern "C" void nmt_destroy(nmt_ctx* ctx) {
   if (ctx->side) {
     (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamDestroy(ctx->side);
+  }
+  if (ctx->ev_fork) {
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
     (void)hipEventDestroy(ctx->ev_done[0]);
@@ -645,19 +648,23 @@ extern "C" int nmt_backward(nmt_ctx* ctx, void* stream) {
     return NMT_ESTATE;
   }
   c->have_fwd = false;
-  if (!c->side) {
-    NMT_HIP_CHECK(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  const bool two_streams = !tuning().one_stream;
+  if (!c->ev_fork) {
     NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
     NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
     NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_done[0], hipEventDisableTiming));
     NMT_HIP_CHECK(hipEventCreateWithFlags(&c->ev_done[1], hipEventDisableTiming));
   }
+  // (the second stream comes into being when it is first needed: a stream that exists takes a place on one of the
+  //  process's few hardware queues even if nothing is ever enqueued on it)
+  if (two_streams && !c->side) NMT_HIP_CHECK(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
   const nmt_config& k = c->cfg;
   const int Bt = c->Bt, Ns = c->Ns, Nt = c->Nt, maxS = c->maxS, maxT = c->maxT;
   const int d = k.d_model, F = k.d_ff, V = k.vocab, H = k.n_heads, dh = d / H;
   const Plan& p = c->plan;
-  hipStream_t st = static_cast<hipStream_t>(stream), sd = c->side;
-  if (tuning().one_stream) sd = st;  // profiling aid: no overlap, so per-kernel times are those of kernels running alone
+  // one stream: for callers that keep several passes in flight on streams of their own, and for profiling (no overlap,
+  // so per-kernel times are those of kernels running alone)
+  hipStream_t st = static_cast<hipStream_t>(stream), sd = two_streams ? c->side : st;
   const Run r{c, st};   // input-gradient chain
   const Run w{c, sd};   // weight gradients
   const bool dropping = c->training && k.dropout > 0.f;

@@ -383,7 +383,7 @@ __global__ void __launch_bounds__(kThreads) softmax_xent_kernel(half_t* __restri
   for (int i = 0; i < NCH; ++i) {
     const int c = threadIdx.x + kThreads * i;
     if (c < chunks) {
-      reg[i] = ld_half8(z + c * 8);
+      reg[i] = ld_half8_nt(z + c * 8);
       const Pairs h = __builtin_bit_cast(Pairs, reg[i]);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -425,7 +425,7 @@ __global__ void __launch_bounds__(kThreads) softmax_xent_kernel(half_t* __restri
       half8_t o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (half_t)g[e];
-      st_half8(z + c * 8, o);
+      st_half8_nt(z + c * 8, o);
     }
   }
 }

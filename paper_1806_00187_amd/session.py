@@ -16,7 +16,10 @@ class Session:
     weights and optimizer buffers, own fp16 gradient buffer and workspace) and its own HIP stream, so
     the forward pass of one sub-batch overlaps the backward pass of the previous one.  Accumulation
     into the shared fp32 buffer is chained with events in sub-batch order, which keeps the sum
-    deterministic."""
+    deterministic.  How well the pipes overlap depends on how the runtime spreads the process's streams over its few
+    hardware queues, which a caller does not control: the same sixteen-sub-batch update of the big model measured
+    107 ms with four pipes in a process that had no other stream of its own, and 134-137 ms when a stream created
+    earlier (another session's second stream; it need not carry any work) was still alive."""
 
     def __init__(self, model, weights, max_sentences=1024, max_len=256, act_dropout=0.0, label_smoothing=0.1, ln_eps=1e-5,
                  seed=0, pad_id=1, device="cuda:0", optimizer=True, n_pipes=1):
@@ -136,24 +139,29 @@ class Session:
                         "max_tgt": int(tab[:, 1].max()), "src": dev(src), "tgt_in": dev(tin), "tgt_out": dev(tout)})
         return out
 
+    def _reserve_for(self, dbatch):
+        """Workspace (of every pipe) large enough for this sub-batch, group or packed pass; nothing happens if it already is."""
+        if "packed" in dbatch:
+            self._reserve_bytes(nmt.nmt_workspace_bytes_packed(self.ctx, dbatch["packed"].shape[0], dbatch["n_src"], dbatch["n_tgt"]))
+        elif "segs" in dbatch:
+            self.reserve(dbatch["segs"])
+        else:
+            self.reserve(dbatch["src"].shape[0], dbatch["src"].shape[1], dbatch["tgt_in"].shape[1])
+
     # ---- the five calls ----
     def forward_loss(self, dbatch, loss_scale, step, micro=0, training=True, pipe=0):
         """dbatch: one device sub-batch (2-D id tensors), a group made by Session.group or a packed pass made by Session.pack
         (for the last two `micro` is unused)."""
+        self._reserve_for(dbatch)
         if "packed" in dbatch:
-            need = nmt.nmt_workspace_bytes_packed(self.ctx, dbatch["packed"].shape[0], dbatch["n_src"], dbatch["n_tgt"])
-            self._reserve_bytes(need)
             nmt.nmt_forward_loss_packed(self.ctxs[pipe], dbatch["packed"], dbatch["n_src"], dbatch["n_tgt"], dbatch["max_src"],
                                         dbatch["max_tgt"], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step,
                                         self.loss_sums[pipe], self.ntoks[pipe], training=training)
             return
         if "segs" in dbatch:
-            self.reserve(dbatch["segs"])
             nmt.nmt_forward_loss_group(self.ctxs[pipe], dbatch["segs"], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale,
                                        step, self.loss_sums[pipe], self.ntoks[pipe], sent_uid=dbatch.get("sent_uid"), training=training)
             return
-        B, S = dbatch["src"].shape
-        self.reserve(B, S, dbatch["tgt_in"].shape[1])
         nmt.nmt_forward_loss(self.ctxs[pipe], dbatch["src"], dbatch["tgt_in"], dbatch["tgt_out"], loss_scale, step, micro,
                              self.loss_sums[pipe], self.ntoks[pipe], sent_uid=dbatch.get("sent_uid"), training=training)
 
@@ -188,8 +196,28 @@ class Session:
                 self.accumulate(j == 0)
                 nmt.nmt_accumulate_loss(self.ctx, j == 0, self.loss_tot, self.ntok_tot)
         else:
-            start = torch.cuda.Event()
-            start.record(main)
+            self._update_pipes(dbatches, loss_scale, step, main)
+        if n_tok is None:
+            n_tok = int(self.ntok_tot.item())
+        self.check_overflow(1.0 / (loss_scale * max(n_tok, 1)))
+        self.adam_step(lr, t, betas, eps)
+        return float(self.loss_tot.item()), n_tok, int(self.flag.item())
+
+    def _update_pipes(self, dbatches, loss_scale, step, main):
+        """Sub-batch j goes through pipe j % n_pipes; accumulation is chained with events in sub-batch order.  One host
+        thread enqueues the sub-batches whole, one after the other: the pipes then run staggered (the forward pass of one
+        beside the backward pass of another), which measured a quarter faster than pipes that start together, whether
+        those are fed by a thread each or forward passes first."""
+        for db in dbatches:
+            self._reserve_for(db)
+        start = torch.cuda.Event()
+        start.record(main)
+        # The products of the pipes run side by side: each takes large tiles as if it had its share of the chip, and
+        # each pipe's weight gradients stay on its own stream (the pipes already fill the hardware queues).
+        before = {k: nmt.tuning_value(k, d) for k, d in (("gemm_share", 1), ("one_stream", 0))}
+        nmt.nmt_tuning("gemm_share", self.n_pipes)
+        nmt.nmt_tuning("one_stream", 1)
+        try:
             prev = None
             for j, db in enumerate(dbatches):
                 p = j % self.n_pipes
@@ -205,12 +233,38 @@ class Session:
                     nmt.nmt_accumulate_loss(self.ctxs[p], j == 0, self.loss_tot, self.ntok_tot)
                     prev = torch.cuda.Event()
                     prev.record(s)
-            main.wait_event(prev)
-        if n_tok is None:
-            n_tok = int(self.ntok_tot.item())
-        self.check_overflow(1.0 / (loss_scale * max(n_tok, 1)))
-        self.adam_step(lr, t, betas, eps)
-        return float(self.loss_tot.item()), n_tok, int(self.flag.item())
+        finally:
+            for k, v in before.items():
+                nmt.nmt_tuning(k, v)
+        main.wait_event(prev)
+
+    def choose_streams(self, dbatches, loss_scale=1.0, tries=6, log=None):
+        """Picks the pipes' streams by measurement.  How well the pipes overlap depends on which hardware queues the
+        runtime has put their streams on (see the class note), and nothing but a run tells: up to `tries` sets of
+        streams each carry the forward + backward + accumulate part of one update over `dbatches` twice (weights and
+        optimizer state are not touched; the gradient buffers and the accumulator are overwritten, as they are by
+        the next update anyway), and the set whose second run was fastest is kept.  Returns its time in ms."""
+        if self.n_pipes == 1:
+            return None
+        main = torch.cuda.current_stream(self.device)
+        best = None
+        for _ in range(tries):
+            cand = [torch.cuda.Stream(device=self.device) for _ in range(self.n_pipes)]
+            self.streams = cand
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for rep in range(2):
+                torch.cuda.synchronize(self.device)
+                t0.record(main)
+                self._update_pipes(dbatches, loss_scale, 0, main)
+                t1.record(main)
+                torch.cuda.synchronize(self.device)
+            ms = t0.elapsed_time(t1)
+            if log:
+                log(f"[session] stream set {[hex(s.cuda_stream) for s in cand]}: {ms:.1f} ms")
+            if best is None or ms < best[0]:
+                best = (ms, cand)
+        self.streams = best[1]
+        return best[0]
 
     # ---- views for tests ----
     def activation(self, name, pipe=0):

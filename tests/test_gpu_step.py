@@ -330,14 +330,19 @@ def test_call_order_and_workspace_errors():
 
 def test_sub_batches_in_flight_give_bit_identical_updates():
     """Two sub-batches in flight on separate streams (forward of one beside backward of the other)
-    accumulate in the same order as the serial schedule: every buffer ends up bit-identical."""
+    accumulate in the same order as the serial schedule: every buffer ends up bit-identical, also after
+    the session has tried out several sets of streams (trial passes touch neither weights nor optimizer state)."""
     model = I.MODELS["tiny"]
     weights = I.init_weights(seed=0, perturb=0.1, **model)
     batches = [I.tiny_batch(seed=1001 + i, B=8 - i, S=16 - i, T=12 + i) for i in range(5)]
     outs = []
-    for pipes in (1, 2, 3):
+    for pipes, choose in ((1, False), (2, False), (3, False), (3, True)):
         sess = Session(model, weights, max_sentences=8, n_pipes=pipes)
         dbs = [sess.to_device(b) for b in batches]
+        if choose:
+            before = [host(x).copy() for x in (sess.master, sess.w16, sess.m, sess.v)]
+            assert sess.choose_streams(dbs, loss_scale=64.0, tries=3) > 0
+            assert all((host(x) == b).all() for x, b in zip((sess.master, sess.w16, sess.m, sess.v), before))
         res = [sess.update(dbs, 64.0, 5e-4, t) for t in (1, 2)]
         outs.append((res, host(sess.acc).copy(), host(sess.master).copy(), host(sess.w16).copy(), host(sess.m).copy()))
         sess.close()
