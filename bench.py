@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--group", type=int, default=16, help="sub-batches stacked into one forward/backward pass")
     ap.add_argument("--padded", action="store_true", help="keep the sub-batches' padding rows (default: sentences packed back to back)")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
+    ap.add_argument("--leg", default="all", choices=["all", "strict"], help="strict: only the one-by-one order (16 x forward/backward/"
+                    "accumulate, four in flight), e.g. under a profiler; prints that leg's record")
     ap.add_argument("--one-stream", action="store_true", help="profiling aid: weight-gradient kernels on the caller's stream, so that a kernel "
                     "trace shows every kernel running alone")
     args = ap.parse_args()
@@ -122,6 +124,9 @@ def main():
     shapes = [(b["src"].shape[0], b["src"].shape[1], b["tgt_in"].shape[1]) for b in batches]
     ntoks = [int((b["tgt_out"] != I.PAD).sum()) for b in batches]
     log(f"[bench] inputs ready in {time.time() - t0:.1f}s; sub-batch shapes (B,S,T): {shapes}")
+    if args.leg == "strict":
+        print(json.dumps({"strict_order": strict_leg(model, weights, batches, ntoks, shapes, args.steps, Session, Trainer, torch, log)}))
+        return
     group = max(1, min(args.group, k_micro))
     n_pass = -(-k_micro // group)
     sess = Session(model, weights, max_sentences=max(s[0] for s in shapes), max_len=256, n_pipes=max(1, min(args.pipes, n_pass)))
