@@ -191,8 +191,9 @@ __device__ __forceinline__ void store_rows(half_t* tile, const floatx16 (&acc)[(
 // forward: the wavefront owns 32 queries
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__device__ __forceinline__ void attn_fwd_item(const AttnArgs& a, const Item& it, unsigned char* smem_raw) {
+__device__ __forceinline__ void attn_fwd_item(const AttnArgs& a, int bx, int by, unsigned char* smem_raw) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8;
+  const Item it = work_item<1>(a, bx, by);
   if (!it.live) return;
   const Sent se = it.se;
   const int q0 = it.tile * 32;
@@ -261,27 +262,13 @@ __device__ __forceinline__ void attn_fwd_item(const AttnArgs& a, const Item& it,
 }
 // Persistent: the launch fills the chip once and every work-group walks through the work items with the
 // grid's stride.  A wavefront that ended after each item would first wait for its stores to land; here the
-// next item's loads go out right behind them.  The list entry of the NEXT item is asked for before the current
-// item is worked on: an item otherwise starts with two dependent round trips to memory (its list entry, then the
-// rows the entry points to), and a wavefront's items are short.
+// next item's loads go out right behind them.
 template <int DH>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH <= 64 ? 3 : 1, DH <= 64 ? 3 : 1)))
 attn_fwd_kernel(const AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int total = a.vgx * a.vgy;
-  int v = blockIdx.x;
-  if (v >= total) return;
-  Item cur = work_item<1>(a, v % a.vgx, v / a.vgx);
-  for (;;) {
-    const int nv = v + (int)gridDim.x;
-    const bool more = nv < total;
-    Item nxt = cur;
-    if (more) nxt = work_item<1>(a, nv % a.vgx, nv / a.vgx);
-    attn_fwd_item<DH>(a, cur, smem_raw);
-    if (!more) break;
-    cur = nxt;
-    v = nv;
-  }
+  for (int v = blockIdx.x; v < total; v += gridDim.x) attn_fwd_item<DH>(a, v % a.vgx, v / a.vgx, smem_raw);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -458,8 +445,9 @@ constexpr int fused_wave_lds() {
   return (2 * NT + 1) * 32 * (DH + 8) * 2 + 32 * kDsPitch * 2 + 2 * 32 * NT * 4;  // Q and dO tiles, one K tile, dS, lse and D
 }
 template <int DH, int NT>
-__device__ __forceinline__ void attn_bwd_fused_item(const AttnArgs& a, const Item& it, unsigned char* smem_raw) {
+__device__ __forceinline__ void attn_bwd_fused_item(const AttnArgs& a, int bx, unsigned char* smem_raw) {
   constexpr int DHP = DH < 32 ? 32 : DH, KS = DH / 16, DT = DHP / 32, PR = DH + 8, TILE = 32 * PR;
+  const Item it = work_item<2>(a, bx, 0, NT - 1);
   if (!it.live) return;
   const Sent se = it.se;
   const int tmax = max(se.Tq, se.Tk);
@@ -589,24 +577,12 @@ template <int DH, int NT>
 __global__ void __launch_bounds__(kThreads) attn_bwd_fused_kernel(const AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   if constexpr (NT <= 2) {
-    int v = blockIdx.x;
-    if (v >= a.vgx) return;
-    Item cur = work_item<2>(a, v, 0, NT - 1);
-    for (;;) {
-      const int nv = v + (int)gridDim.x;
-      const bool more = nv < a.vgx;
-      // (asked for ahead of the current item, as in the forward kernel, where there are registers to hold it)
-      constexpr bool AHEAD = DH <= 64;
-      Item nxt = cur;
-      if (AHEAD && more) nxt = work_item<2>(a, nv, 0, NT - 1);
+    for (int v = blockIdx.x; v < a.vgx; v += gridDim.x) {
       wave_sync();  // the wavefront's LDS tiles are free again
-      attn_bwd_fused_item<DH, NT>(a, cur, smem_raw);
-      if (!more) break;
-      cur = AHEAD ? nxt : work_item<2>(a, nv, 0, NT - 1);
-      v = nv;
+      attn_bwd_fused_item<DH, NT>(a, v, smem_raw);
     }
   } else {
-    attn_bwd_fused_item<DH, NT>(a, work_item<2>(a, blockIdx.x, 0, NT - 1), smem_raw);
+    attn_bwd_fused_item<DH, NT>(a, blockIdx.x, smem_raw);
   }
 }
 
