@@ -488,6 +488,18 @@ __device__ __forceinline__ void stage_read32(uint32_t a0, uint32_t a1, floatx4& 
   asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)" : "=&v"(lo), "=&v"(hi) : "v"(a0), "v"(a1) : "memory");
 }
 
+// a whole slab's staged rows, eight 16-byte reads, returned once all have arrived: one instruction sequence, so
+// that nothing can touch the registers between the reads and the wait
+__device__ __forceinline__ void stage_read_slab(const uint32_t (&a)[8], floatx4 (&d)[8]) {
+  asm volatile(
+      "ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
+      "ds_read_b128 %4, %12\n\tds_read_b128 %5, %13\n\tds_read_b128 %6, %14\n\tds_read_b128 %7, %15\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(d[0]), "=&v"(d[1]), "=&v"(d[2]), "=&v"(d[3]), "=&v"(d[4]), "=&v"(d[5]), "=&v"(d[6]), "=&v"(d[7])
+      : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
+      : "memory");
+}
+
 template <bool AT, bool BT, int BK, int NS>
 __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) {
   constexpr int BM = 256, BN = 256, NW = 8;
@@ -643,18 +655,28 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
           stage_write16(stg + (row * SW + swz(row, chunk) * 4) * 4, v4);
         }
       wave_sync();
+      // all of the slab's staged rows are asked for at once and waited for once (one LDS round trip per 32 rows)
+      static_assert(CH / 2 == 4, "a slab is read with four pairs of 16-byte reads per lane");
+      uint32_t sa[8];
+      floatx4 sd[8];   // sd[2 it], sd[2 it + 1]: columns 0..3 and 4..7 of the lane's chunk in pass it
 #pragma unroll
       for (int it = 0; it < CH / 2; ++it) {
         const int q = it * 64 + lane;
         const int rl = q / CH, c8 = q % CH;
+        sa[2 * it] = stg + (rl * SW + swz(rl, 2 * c8) * 4) * 4;
+        sa[2 * it + 1] = stg + (rl * SW + swz(rl, 2 * c8 + 1) * 4) * 4;
+      }
+      stage_read_slab(sa, sd);
+#pragma unroll
+      for (int it = 0; it < CH / 2; ++it) {
+        const int q = it * 64 + lane;
+        const int rl = q / CH;
         const int gr = m0c + wm * WM + i * 32 + rl;
         if (gr < g.M && gc < g.N) {
-          floatx4 lo, hi;
-          stage_read32(stg + (rl * SW + swz(rl, 2 * c8) * 4) * 4, stg + (rl * SW + swz(rl, 2 * c8 + 1) * 4) * 4, lo, hi);
           float v[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            v[e] = (e < 4 ? lo[e] : hi[e - 4]) * ep.out_scale + (float)bias8[e];
+            v[e] = (e < 4 ? sd[2 * it][e] : sd[2 * it + 1][e - 4]) * ep.out_scale + (float)bias8[e];
             if (ep.relu) v[e] = fmaxf(v[e], 0.f);
           }
           // (loads from here on queue behind the early requests: they cost part of what those save)
