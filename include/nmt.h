@@ -201,7 +201,8 @@ int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_pt
  * kernels enumerate every (sentence, tile); default 1), "one_stream" (1: nmt_backward enqueues the weight
  * gradients on the caller's stream; default 0), "gemm_share" (1..16, default 1: the number of products a
  * caller keeps running side by side on streams of its own; large tiles are then chosen as if each product had
- * that fraction of the compute units), "gemm_timing" (1: every GEMM product is bracketed by a pair of
+ * that fraction of the compute units), "gemm_tile" (0: tile shape chosen per product, the default; 1..5: every
+ * product that is not cut along k takes 256x256 / 128x128 / 128x64 / 64x128 / 64x64 tiles), "gemm_timing" (1: every GEMM product is bracketed by a pair of
  * HIP events on the stream it is launched on; default 0), "defaults" (value ignored: all of the above back to
  * default).  Unknown names and values out of range return NMT_EINVAL. */
 int nmt_tuning(const char* name, int32_t value);

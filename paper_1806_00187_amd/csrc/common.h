@@ -54,6 +54,7 @@ struct Tuning {
   int one_stream = 0;     // 1: the backward pass's weight-gradient kernels run on the caller's stream, not beside it
   int gemm_share = 1;     // products expected to run side by side (callers that keep several passes in flight): large tiles
                           // are chosen as if each product had 1/gemm_share of the compute units
+  int gemm_tile = 0;      // experiments: 0 = chosen per product; 1..5 force 256x256, 128x128, 128x64, 64x128, 64x64 tiles (products not cut along k)
   int gemm_timing = 0;    // 1: every GEMM product is bracketed by HIP events on its launch stream (nmt_gemm_timing reads them)
 };
 Tuning& tuning();

@@ -850,6 +850,15 @@ int launch_gemm_impl(const half_t* A, bool a_t, int lda, const half_t* B, bool b
   }
   NMT_REQUIRE(splits == 1 || plane * splits <= partial_floats, "gemm: partial-sum buffer of %lld floats too small for %d splits",
               (long long)partial_floats, splits);
+  if (const int forced = tuning().gemm_tile; forced && splits <= 1) {
+    switch (forced) {
+      case 1: return (!a_t && !b_t) ? launch_tile<256, 256, 64, 2, 8>(g, a_t, b_t, 1, stream) : launch_tile<256, 256, 32, 4, 8>(g, a_t, b_t, 1, stream);
+      case 2: return launch_tile<128, 128, 64, 2>(g, a_t, b_t, 1, stream);
+      case 3: return launch_tile<128, 64, 64, 2>(g, a_t, b_t, 1, stream);
+      case 4: return launch_tile<64, 128, 64, 2>(g, a_t, b_t, 1, stream);
+      default: return launch_tile<64, 64, 64, 2>(g, a_t, b_t, 1, stream);
+    }
+  }
   // (a caller that keeps several passes in flight says so: each product then counts on its share of the chip)
   const int64_t full_shared = full / tuning().gemm_share > 1 ? full / tuning().gemm_share : 1;
   if (t256 * splits >= full_shared) {

@@ -45,6 +45,7 @@ extern "C" int nmt_tuning(const char* name, int32_t value) {
   else if (!strcmp(name, "worklists")) t.worklists = value != 0;
   else if (!strcmp(name, "one_stream")) t.one_stream = value != 0;
   else if (!strcmp(name, "gemm_share")) { NMT_REQUIRE(value >= 1 && value <= 16, "nmt_tuning: gemm_share must be in [1, 16]"); t.gemm_share = value; }
+  else if (!strcmp(name, "gemm_tile")) { NMT_REQUIRE(value >= 0 && value <= 5, "nmt_tuning: gemm_tile is 0..5"); t.gemm_tile = value; }
   else if (!strcmp(name, "gemm_timing")) t.gemm_timing = value != 0;
   else if (!strcmp(name, "defaults")) t = Tuning{};
   else NMT_REQUIRE(false, "nmt_tuning: unknown switch '%s'", name);

@@ -207,6 +207,32 @@ def test_gemm_tile_order_changes_no_bit():
             A.nmt_tuning("gemm_group", group)
             for a, b in zip(ref, run()):
                 assert torch.equal(a.view(torch.int16), b.view(torch.int16)), group
+        A.nmt_tuning("defaults")
+        # the tile shape does not change a bit either: every compiled shape forced in turn, in all three operand
+        # layouts the step uses, with an epilogue, and large tiles chosen for a share of the chip
+        Ms, Ns, Ks = 1000, 776, 264
+        xa, xat = dev16(f16(rng.normal(size=(Ms, Ks)))), dev16(f16(rng.normal(size=(Ks, Ms))))
+        wb, wbt = dev16(f16(rng.normal(size=(Ns, Ks)) / 8)), dev16(f16(rng.normal(size=(Ks, Ns)) / 8))
+        bias = dev16(f16(rng.normal(size=Ns)))
+
+        def shapes_run():
+            outs = []
+            for a, a_t, b, b_t in ((xa, 0, wb, 0), (xa, 0, wbt, 1), (xat, 1, wbt, 1)):
+                c = torch.full((Ms, Ns), float("nan"), dtype=torch.float16, device=DEV)
+                A.nmt_op_gemm(a, a_t, Ms if a_t else Ks, b, b_t, Ns if b_t else Ks, c, Ns, Ms, Ns, Ks, bias=None if a_t else bias, relu=not a_t)
+                outs.append(c)
+            return outs
+
+        ref2 = shapes_run()
+        assert all(torch.isfinite(c).all() for c in ref2)
+        for tile in (1, 2, 3, 4, 5):
+            A.nmt_tuning("gemm_tile", tile)
+            for a, b in zip(ref2, shapes_run()):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), ("tile", tile)
+        A.nmt_tuning("gemm_tile", 0)
+        A.nmt_tuning("gemm_share", 16)
+        for a, b in zip(ref2 + ref, shapes_run() + run()):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "share"
     finally:
         A.nmt_tuning("defaults")
 
