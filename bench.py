@@ -149,6 +149,8 @@ def main():
     if packed:
         pass_rows = [(g["n_src"], g["n_tgt"]) for g in dbatches]
     tr = Trainer(sess, peak_lr=1e-3, warmup=4000, init_scale=128.0)
+    if sess.n_pipes > 1:    # several passes in flight: the streams that overlap best, by measurement
+        sess.choose_streams(dbatches, loss_scale=16.0, tries=6, log=log)
 
     # warm-up: also lets the dynamic loss scale settle (an overflowing update is skipped and halves it)
     skipped = 0
