@@ -195,8 +195,8 @@ double nmt_lr_schedule(int64_t t, double peak, int64_t warmup);
 int nmt_debug_activation(const nmt_ctx* ctx, const char* name, const void** d_ptr, int64_t* rows, int64_t* cols);
 
 /* Host only.  Process-wide switches of launch forms, for tests and profiling; none of them changes a
- * result bit.  name: "gemm_group" (tile rows swept together, >= 1; default 4), "gemm_persist" (0 never /
- * 1 where the epilogue loads nothing per element / 2 always the persistent GEMM form; default 1),
+ * result bit.  name: "gemm_group" (tile rows swept together, >= 1; default 4), "gemm_persist" (0: never the
+ * persistent GEMM form / 1: for large products whose epilogue loads nothing per element; default 1),
  * "attn_persist" (0: one attention work item per work-group; default 1), "worklists" (0: attention
  * kernels enumerate every (sentence, tile); default 1), "one_stream" (1: nmt_backward enqueues the weight
  * gradients on the caller's stream; default 0), "gemm_share" (1..16, default 1: the number of products a

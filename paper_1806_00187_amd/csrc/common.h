@@ -48,7 +48,7 @@ const DeviceInfo& device_info();
 // Process-wide switches of launch forms (nmt_tuning): which work-group computes what, never what is computed.
 struct Tuning {
   int gemm_group = 4;     // tile rows swept column by column before the next rows
-  int gemm_persist = 1;   // 0: never the persistent GEMM form, 1: for epilogues that load nothing per element, 2: always
+  int gemm_persist = 1;   // 0: never the persistent GEMM form, 1: where it applies (large products whose epilogue loads nothing per element)
   int attn_persist = 1;   // 0: one attention work item per work-group
   int worklists = 1;      // 0: attention kernels enumerate every (sentence, tile) instead of taking work lists
   int one_stream = 0;     // 1: the backward pass's weight-gradient kernels run on the caller's stream, not beside it

@@ -469,34 +469,40 @@ __global__ void __launch_bounds__(64 * NW) gemm_kernel(const GemmArgs g) {
 // ------------------------------------------------------------------------------------------------
 // Persistent form of the 256 x 256, 8-wave kernel for products whose epilogue loads nothing per
 // element (bias, ReLU and the output scale only): one work-group per compute unit walks its tiles
-// (the same tile -> XCD assignment as above) and asks for the first k-tiles of its next tile BEFORE
-// it stores the current one, so that their latency passes behind the epilogue instead of in front of
-// the next main loop.  Vector-memory operations retire in issue order on one counter: the wait for
-// those early k-tiles is "at most as many operations outstanding as were issued after them" (the
-// epilogue's stores and the remaining requests), which does not wait for the stores.  LDS: the stages
-// not being prefetched into serve as the epilogue's staging area.
+// (the same tile -> XCD assignment as above) and asks for the first k-tiles of its next tile -- the
+// whole stage ring -- BEFORE it stores the current one, so that their latency passes behind the
+// epilogue and the next main loop starts with its ring full.  Vector-memory operations retire in
+// issue order on one counter: the wait for the first of those k-tiles is "at most as many operations
+// outstanding as were issued after it" (the other requests and the epilogue's stores), which does not
+// wait for the stores.  The epilogue leaves the stages alone: bias, ReLU and scale are applied to the
+// accumulators where they are (MFMA layout), the fp16 results pass through the 32 KB of LDS the stage
+// ring leaves free (32 rows x 64 columns per wave, wave-private, so no work-group barrier) and leave
+// as whole 128-byte rows.
 // ------------------------------------------------------------------------------------------------
-// LDS accesses of the persistent kernel's staging rows, written as instructions: while requests into
-// other stages are in flight the compiler would otherwise put a wait for ALL of them in front of any
-// LDS access it cannot tell apart from their targets.
+// LDS accesses of the staging rows, written as instructions: while requests into the stages are in
+// flight the compiler would otherwise put a wait for ALL of them in front of any LDS access it
+// cannot tell apart from their targets.
 __device__ __forceinline__ uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
-__device__ __forceinline__ void stage_write16(uint32_t addr, floatx4 v) {
-  asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
-// two 16-byte reads, returned once both have arrived (and every earlier LDS operation of the wave)
-__device__ __forceinline__ void stage_read32(uint32_t a0, uint32_t a1, floatx4& lo, floatx4& hi) {
-  asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)" : "=&v"(lo), "=&v"(hi) : "v"(a0), "v"(a1) : "memory");
-}
-
-// a whole slab's staged rows, eight 16-byte reads, returned once all have arrived: one instruction sequence, so
-// that nothing can touch the registers between the reads and the wait
-__device__ __forceinline__ void stage_read_slab(const uint32_t (&a)[8], floatx4 (&d)[8]) {
+typedef _Float16 half4v_t __attribute__((ext_vector_type(4)));
+// eight 8-byte writes: one 32 x 64 slab of results (the lane's four consecutive columns of each of its eight column groups)
+__device__ __forceinline__ void out_write_slab(const uint32_t (&a)[8], const half4v_t (&v)[8]) {
   asm volatile(
-      "ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
-      "ds_read_b128 %4, %12\n\tds_read_b128 %5, %13\n\tds_read_b128 %6, %14\n\tds_read_b128 %7, %15\n\t"
+      "ds_write_b64 %0, %8\n\tds_write_b64 %1, %9\n\tds_write_b64 %2, %10\n\tds_write_b64 %3, %11\n\t"
+      "ds_write_b64 %4, %12\n\tds_write_b64 %5, %13\n\tds_write_b64 %6, %14\n\tds_write_b64 %7, %15"
+      :
+      : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]),
+        "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7])
+      : "memory");
+}
+// the slab back as rows: four 16-byte reads, returned once all have arrived (LDS operations of a wave complete in
+// order, so the writes above are done too); one instruction sequence, so that nothing touches the registers between
+// the reads and the wait
+__device__ __forceinline__ void out_read_slab(const uint32_t (&a)[4], half8_t (&d)[4]) {
+  asm volatile(
+      "ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
       "s_waitcnt lgkmcnt(0)"
-      : "=&v"(d[0]), "=&v"(d[1]), "=&v"(d[2]), "=&v"(d[3]), "=&v"(d[4]), "=&v"(d[5]), "=&v"(d[6]), "=&v"(d[7])
-      : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
+      : "=&v"(d[0]), "=&v"(d[1]), "=&v"(d[2]), "=&v"(d[3])
+      : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3])
       : "memory");
 }
 
@@ -507,12 +513,20 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
   using OpA = typename T::OpA;
   using OpB = typename T::OpB;
   static_assert(NS == 2 || NS == 4, "two or four stages");
+  static_assert(NS * T::STAGE == 128 * 1024, "the ring takes 128 KB; the staging rows take the 32 KB that are left");
+  // separate arrays (see gemm_kernel); the third and fourth exist only in the four-stage form
   __shared__ __align__(1024) unsigned char stage0[T::STAGE];
   __shared__ __align__(1024) unsigned char stage1[T::STAGE];
-  __shared__ __align__(1024) unsigned char stage2[NS > 2 ? T::STAGE : 16];
-  __shared__ __align__(1024) unsigned char stage3[NS > 3 ? T::STAGE : 16];
+  unsigned char *stage2 = nullptr, *stage3 = nullptr;
+  if constexpr (NS == 4) {
+    __shared__ __align__(1024) unsigned char stage2_[T::STAGE];
+    __shared__ __align__(1024) unsigned char stage3_[T::STAGE];
+    stage2 = stage2_;
+    stage3 = stage3_;
+  }
   constexpr int WGN = 4, WM = 128, WN = 64, TM = 4, TN = 2, KS = BK / 16;
-  static_assert((NS == 2 ? 1 : 2) * T::STAGE >= NW * 32 * WN * 4, "the spare stages must hold the staging area");
+  constexpr int kOutPitch = WN * 2;                       // bytes per staged row: 64 fp16
+  __shared__ __align__(16) unsigned char out_rows[NW * 32 * kOutPitch];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int nt = g.tiles_m * g.tiles_n;
@@ -585,11 +599,10 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
   };
   const int nk = (g.K + BK - 1) / BK;
   const GemmEpilogue& ep = g.ep;
-  // staging: 32 rows x 64 floats per wave, in the stages the early requests do not touch
-  constexpr int SW = 64, CH = SW / 8;
-  const uint32_t stg = NS == 2 ? lds_addr(stage1) + wave * (32 * SW * 4) : lds_addr(wave < 4 ? stage2 : stage3) + (wave & 3) * (32 * SW * 4);
-  auto swz = [](int row, int chunk) { return chunk ^ (row & 15); };
-  constexpr int kStores = TM * (CH / 2);  // global stores of one wave's epilogue on a tile that lies wholly inside C
+  // staged rows of this wave: row r, 16-byte chunk c (eight columns) at r * pitch + (c ^ (r & 7)) * 16, so that the
+  // eight lanes that read a row back cover its 128 bytes and sixteen lanes cover every bank once
+  const uint32_t out = lds_addr(out_rows) + wave * (32 * kOutPitch);
+  constexpr int kStores = TM * 4;  // global stores of one wave's epilogue on a tile that lies wholly inside C
 
   int lin = blockIdx.x;
   decode(lin, m0, n0);
@@ -624,13 +637,20 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
         k_tile(stage3, stage0, (kt + 7) * BK);
       }
     }
-    // what the epilogue needs of the current tile; its bias is fetched here, ahead of the requests
-    // below, and waited for together with the last refills (zeros past k), so that no wait of the
-    // epilogue has to pass those requests
+    // What the epilogue needs of the current tile.  The bias of the lane's columns in the MFMA layout (column group
+    // cg = 4 jj + q holds columns 32 jj + 8 q + 4 (lane / 32) .. + 3 of the wave's 64) is fetched here, ahead of the
+    // requests below, and waited for together with the last refills (zeros past k), so that no wait of the epilogue
+    // has to pass those requests.
     const int m0c = m0, n0c = n0;
-    const int gc = n0c + wn * WN + (lane & (CH - 1)) * 8;
-    half8_t bias8 = zero_half8();
-    if (ep.bias && gc < g.N) bias8 = ld_half8(ep.bias + gc);
+    const int g32 = lane >> 5, row = lane & 31;
+    const int col0 = n0c + wn * WN + 4 * g32;
+    half4v_t bias4[8];
+#pragma unroll
+    for (int cg = 0; cg < 8; ++cg) {
+      const int col = col0 + 8 * cg;   // (N is a multiple of 8 and col of 4: the four columns are inside C or all outside)
+      bias4[cg] = half4v_t{0, 0, 0, 0};
+      if (ep.bias && col < g.N) bias4[cg] = *reinterpret_cast<const half4v_t*>(ep.bias + col);
+    }
     __builtin_amdgcn_s_waitcnt(wait_vm_lds(0));
     __syncthreads();
     const int next = lin + (int)gridDim.x;
@@ -639,88 +659,54 @@ __global__ void __launch_bounds__(512) gemm_persistent_kernel(const GemmArgs g) 
       decode(next, m0, n0);
       setup();
       request(stage0, 0);
-      if constexpr (NS == 4) request(stage1, BK);
+      request(stage1, BK);
+      if constexpr (NS == 4) {
+        request(stage2, 2 * BK);
+        request(stage3, 3 * BK);
+      }
     }
-    // ---- epilogue of (m0c, n0c): accumulators -> the wave's staging rows -> 16-byte row stores ----
+    // ---- epilogue of (m0c, n0c): accumulators -> fp16 -> the wave's staging rows -> 16-byte pieces of whole rows ----
+    const int c8 = lane & 7;
+    const int gc = n0c + wn * WN + c8 * 8;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      if (i) wave_sync();
+      uint32_t wa[8];
+      half4v_t wv[8];
 #pragma unroll
-      for (int jj = 0; jj < SW / 32; ++jj)
+      for (int cg = 0; cg < 8; ++cg) {
+        const floatx16& a = acc[i][cg >> 2];
+        const int q = cg & 3;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const floatx16& a = acc[i][jj];
-          const floatx4 v4 = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
-          const int row = lane & 31, chunk = jj * 8 + 2 * q + (lane >> 5);
-          stage_write16(stg + (row * SW + swz(row, chunk) * 4) * 4, v4);
+        for (int e = 0; e < 4; ++e) {
+          float v = a[4 * q + e] * ep.out_scale + (float)bias4[cg][e];
+          if (ep.relu) v = fmaxf(v, 0.f);
+          wv[cg][e] = (_Float16)v;
         }
-      wave_sync();
-      // all of the slab's staged rows are asked for at once and waited for once (one LDS round trip per 32 rows)
-      static_assert(CH / 2 == 4, "a slab is read with four pairs of 16-byte reads per lane");
-      uint32_t sa[8];
-      floatx4 sd[8];   // sd[2 it], sd[2 it + 1]: columns 0..3 and 4..7 of the lane's chunk in pass it
-#pragma unroll
-      for (int it = 0; it < CH / 2; ++it) {
-        const int q = it * 64 + lane;
-        const int rl = q / CH, c8 = q % CH;
-        sa[2 * it] = stg + (rl * SW + swz(rl, 2 * c8) * 4) * 4;
-        sa[2 * it + 1] = stg + (rl * SW + swz(rl, 2 * c8 + 1) * 4) * 4;
+        wa[cg] = out + row * kOutPitch + ((cg ^ (row & 7)) << 4) + (g32 << 3);
       }
-      stage_read_slab(sa, sd);
+      out_write_slab(wa, wv);   // (the reads of the previous slab have returned: out_read_slab waits for them)
+      uint32_t ra[4];
+      half8_t rv[4];
 #pragma unroll
-      for (int it = 0; it < CH / 2; ++it) {
-        const int q = it * 64 + lane;
-        const int rl = q / CH;
-        const int gr = m0c + wm * WM + i * 32 + rl;
-        if (gr < g.M && gc < g.N) {
-          float v[8];
+      for (int it = 0; it < 4; ++it) {
+        const int rl = it * 8 + (lane >> 3);
+        ra[it] = out + rl * kOutPitch + ((c8 ^ (rl & 7)) << 4);
+      }
+      out_read_slab(ra, rv);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            v[e] = (e < 4 ? sd[2 * it][e] : sd[2 * it + 1][e - 4]) * ep.out_scale + (float)bias8[e];
-            if (ep.relu) v[e] = fmaxf(v[e], 0.f);
-          }
-          // (loads from here on queue behind the early requests: they cost part of what those save)
-          if (ep.drop.thr) {
-            const uint32_t bits = drop_keep8(ep.drop, (uint32_t)(gr + ep.row0), (uint32_t)gc >> 3);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = ((bits >> e) & 1u) ? v[e] * ep.drop.scale : 0.f;
-          }
-          const size_t off = (size_t)gr * g.ldc + gc;
-          if (ep.add) {
-            const half8_t ad = ld_half8(ep.add + off);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] += (float)ad[e];
-          }
-          if (ep.relu_src) {
-            const half8_t h = ld_half8(ep.relu_src + off);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = ((float)h[e] > 0.f) ? v[e] * ep.mask_scale : 0.f;
-          }
-          half8_t o;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] = (half_t)v[e];
-          // streaming store: a result tile is not read again by this product, and letting it stay in L2 pushes out
-          // the operand panels the XCD's other tiles are reading (products with wide results: +5-7 %)
-          __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(g.C + off));
-        }
+      for (int it = 0; it < 4; ++it) {
+        const int gr = m0c + wm * WM + i * 32 + it * 8 + (lane >> 3);
+        // streaming store: a result tile is not read again by this product, and letting it stay in L2 pushes out
+        // the operand panels the XCD's other tiles are reading (products with wide results: +5-7 %)
+        if (gr < g.M && gc < g.N) __builtin_nontemporal_store(rv[it], reinterpret_cast<half8_t*>(g.C + (size_t)gr * g.ldc + gc));
       }
     }
     if (!more) break;
-    // every wave is done with the staging rows (its reads have returned: stage_read32 waits for them).  A bare
-    // barrier: __syncthreads() carries a fence, which would wait for the stores and the early requests.
-    __builtin_amdgcn_s_barrier();
-    setup();
-    if constexpr (NS == 2) {
-      request(stage1, BK);
-    } else {
-      request(stage2, 2 * BK);
-      request(stage3, 3 * BK);
-    }
-    // wait for the first k-tile of the new tile: everything issued after it may stay outstanding (the
-    // second early request, the stores of a full tile, the requests just made); a tile at the edge of C
-    // stores fewer rows or columns, so there the wait is for everything
+    // wait for the first k-tile of the new tile: everything issued after it may stay outstanding (the other early
+    // requests and the stores of a full tile); a tile at the edge of C stores fewer rows or columns, so there the
+    // wait is for everything
     const bool whole = m0c + BM <= g.M && n0c + BN <= g.N;
-    constexpr int kLater = (NS == 4 ? 3 : 1) * kPerTile + kStores;
+    constexpr int kLater = (NS - 1) * kPerTile + kStores;
     static_assert(kLater < 64, "s_waitcnt vmcnt holds six bits");
     if (whole) __builtin_amdgcn_s_waitcnt(wait_vm(kLater));
     else __builtin_amdgcn_s_waitcnt(wait_vm(0));
@@ -881,16 +867,15 @@ int launch_gemm_impl(const half_t* A, bool a_t, int lda, const half_t* B, bool b
                                 K, tail, stream, nullptr, 0, 1);
       }
     }
-    // At least two tiles per compute unit, no split along k, row-major A: the persistent form, by default
-    // for epilogues that load nothing per element.  With such loads it still wins 1-11 % on a product
-    // running alone, but in the backward pass, where the weight-gradient kernels of the second stream
-    // share the chip, work-groups that never leave their compute unit cost more than they gain
-    // (measured on the whole update).  Tuning aid: NMT_GEMM_PERSIST=0 never, =2 for every epilogue.
-    // (Not for a k-major A: the one such product without a split, the vocabulary weight gradient, has so
-    //  long a contraction that the tile change hardly counts, and measured 6 % slower in this form.)
-    const int pmode = tuning().gemm_persist;
+    // At least two tiles per compute unit, no split along k, row-major A, an epilogue that loads nothing per
+    // element (bias, ReLU, scale): the persistent form.  (With an addend or a mask to load it gained 1-11 % on a
+    // product running alone but nothing on the update, where the weight-gradient kernels of the second stream
+    // share the chip and work-groups that never leave their compute unit cost more than they gain; the form no
+    // longer has those epilogues.  Not for a k-major A either: the one such product without a split, the
+    // vocabulary weight gradient, has so long a contraction that the tile change hardly counts, and measured
+    // 6 % slower in this form.)
     const bool loads_in_epilogue = ep.add || ep.relu_src || ep.drop.thr;
-    if (splits == 1 && t256 >= 2 * cus && !a_t && pmode != 0 && (pmode == 2 || !loads_in_epilogue)) {
+    if (splits == 1 && t256 >= 2 * cus && !a_t && tuning().gemm_persist && !loads_in_epilogue) {
       GemmArgs pg = g;
       pg.tiles_m = ceil_div(M, 256);
       pg.tiles_n = ceil_div(N, 256);

@@ -40,7 +40,7 @@ extern "C" int nmt_tuning(const char* name, int32_t value) {
   NMT_REQUIRE(name, "nmt_tuning: null name");
   Tuning& t = tuning();
   if (!strcmp(name, "gemm_group")) { NMT_REQUIRE(value >= 1, "nmt_tuning: gemm_group must be >= 1"); t.gemm_group = value; }
-  else if (!strcmp(name, "gemm_persist")) { NMT_REQUIRE(value >= 0 && value <= 2, "nmt_tuning: gemm_persist is 0, 1 or 2"); t.gemm_persist = value; }
+  else if (!strcmp(name, "gemm_persist")) { NMT_REQUIRE(value == 0 || value == 1, "nmt_tuning: gemm_persist is 0 or 1"); t.gemm_persist = value; }
   else if (!strcmp(name, "attn_persist")) t.attn_persist = value != 0;
   else if (!strcmp(name, "worklists")) t.worklists = value != 0;
   else if (!strcmp(name, "one_stream")) t.one_stream = value != 0;

@@ -112,13 +112,13 @@ def test_lr_schedule_matches_the_oracle():
 
 
 def test_tuning_switches_accept_their_names_and_reject_others():
-    for name, value in (("gemm_group", 3), ("gemm_persist", 2), ("attn_persist", 0), ("worklists", 0), ("one_stream", 1), ("gemm_share", 4), ("gemm_tile", 3), ("defaults", 0)):
+    for name, value in (("gemm_group", 3), ("gemm_persist", 0), ("attn_persist", 0), ("worklists", 0), ("one_stream", 1), ("gemm_share", 4), ("gemm_tile", 3), ("defaults", 0)):
         A.nmt_tuning(name, value)
     assert A.binding.tuning_value("gemm_share", 1) == 1 and A.binding.tuning_value("one_stream", 0) == 0   # "defaults" forgets what was set
     A.nmt_tuning("gemm_share", 2)
     assert A.binding.tuning_value("gemm_share", 1) == 2
     A.nmt_tuning("defaults")
-    for name, value in (("gemm_group", 0), ("gemm_persist", 3), ("gemm_share", 0), ("gemm_share", 17), ("gemm_tile", 6), ("no_such_switch", 1)):
+    for name, value in (("gemm_group", 0), ("gemm_persist", 2), ("gemm_share", 0), ("gemm_share", 17), ("gemm_tile", 6), ("no_such_switch", 1)):
         with pytest.raises(A.NmtError) as e:
             A.nmt_tuning(name, value)
         assert e.value.code == A.binding.NMT_EINVAL
