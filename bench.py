@@ -369,6 +369,9 @@ def gemm_leg(model, pass_rows, A, torch, log):
     per_kind = {}
     cache = {}
     partial = torch.empty(16 << 20, dtype=torch.float32, device="cuda")   # the step's partial-sum scratch size
+    warm = torch.randn(8192, 8192, device="cuda", dtype=torch.float16)   # the first shape is not timed on a chip at rest
+    _timed(torch, lambda: A.nmt_op_gemm(warm, 0, 8192, warm, 0, 8192, warm.new_empty(8192, 8192), 8192, 8192, 8192, 8192), 20)
+    del warm
     for (M, N, K, a_t, b_t, epi), count in agg.items():
         rows_a, cols_a = (K, M) if a_t else (M, K)
         rows_b, cols_b = (K, N) if b_t else (N, K)
