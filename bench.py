@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--no-legs", action="store_true", help="skip the per-phase / per-kernel legs (timed region only)")
     ap.add_argument("--leg", default="all", choices=["all", "strict"], help="strict: only the one-by-one order (16 x forward/backward/"
                     "accumulate, four in flight), e.g. under a profiler; prints that leg's record")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE", help="profiling aid: a launch-form switch of nmt_tuning "
+                    "set for the whole run (e.g. gemm_persist=0); none changes a result bit")
     ap.add_argument("--one-stream", action="store_true", help="profiling aid: weight-gradient kernels on the caller's stream, so that a kernel "
                     "trace shows every kernel running alone")
     args = ap.parse_args()
@@ -114,6 +116,9 @@ def main():
     A.load()
     if args.one_stream:
         A.nmt_tuning("one_stream", 1)
+    for item in args.tune:
+        name, _, value = item.partition("=")
+        A.nmt_tuning(name, int(value))
     model_name, k_micro, desc = WORKLOAD_DESC[args.workload]
     model = I.MODELS[model_name]
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
