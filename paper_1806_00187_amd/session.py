@@ -19,10 +19,12 @@ class Session:
     deterministic.  How well the pipes overlap depends on how the runtime spreads the process's streams over its few
     hardware queues, which a caller does not control: the same sixteen-sub-batch update of the big model measured
     107 ms with four pipes in a process that had no other stream of its own, and 134-137 ms when a stream created
-    earlier (another session's second stream; it need not carry any work) was still alive."""
+    earlier (another session's second stream; it need not carry any work) was still alive.  So the first update of a
+    session with several pipes times a few sets of streams on its own sub-batches and keeps the fastest
+    (choose_streams; auto_streams=False keeps the streams as created)."""
 
     def __init__(self, model, weights, max_sentences=1024, max_len=256, act_dropout=0.0, label_smoothing=0.1, ln_eps=1e-5,
-                 seed=0, pad_id=1, device="cuda:0", optimizer=True, n_pipes=1):
+                 seed=0, pad_id=1, device="cuda:0", optimizer=True, n_pipes=1, auto_streams=True):
         """model: dict(enc_layers, dec_layers, d_model, n_heads, d_ff, vocab, dropout);
         weights: dict name -> float16 numpy array (initial fp16 weights = initial master values)."""
         self.device = torch.device(device)
@@ -62,6 +64,8 @@ class Session:
         self.loss_tot = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.ntok_tot = torch.zeros(1, dtype=torch.int32, device=self.device)
         self.streams = [torch.cuda.Stream(device=self.device) for _ in range(n_pipes)] if n_pipes > 1 else [None]
+        # with several pipes, the first update tries a few sets of streams and keeps the best (choose_streams)
+        self._streams_chosen = n_pipes == 1 or not auto_streams
         for p in range(n_pipes):
             self._bind(p)
 
@@ -196,6 +200,8 @@ class Session:
                 self.accumulate(j == 0)
                 nmt.nmt_accumulate_loss(self.ctx, j == 0, self.loss_tot, self.ntok_tot)
         else:
+            if not self._streams_chosen:
+                self.choose_streams(dbatches, loss_scale, tries=4)
             self._update_pipes(dbatches, loss_scale, step, main)
         if n_tok is None:
             n_tok = int(self.ntok_tot.item())
@@ -244,6 +250,7 @@ class Session:
         streams each carry the forward + backward + accumulate part of one update over `dbatches` twice (weights and
         optimizer state are not touched; the gradient buffers and the accumulator are overwritten, as they are by
         the next update anyway), and the set whose second run was fastest is kept.  Returns its time in ms."""
+        self._streams_chosen = True
         if self.n_pipes == 1:
             return None
         main = torch.cuda.current_stream(self.device)
