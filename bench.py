@@ -10,8 +10,9 @@ update are timed over the same number of steps and reported side by side:
   * `strict_order`: the method's literal loop, 16 x (forward + loss, backward, accumulate) over the
     padded sub-batches one by one, then overflow check + Adam.
 Inputs are synthetic (seeded length / token distributions standing in for the paper's WMT
-sub-batches) and resident in HBM before the timed region starts.  Prints ONE JSON line; see
-the design doc for the field definitions.
+sub-batches) and resident in HBM before the timed region starts.  Prints ONE JSON line: the
+headline fields, `roofline` (the GEMM products of the timed step, from HIP events around each),
+`whole_update`, `strict_order`, `phases_ms_per_update`, `hbm_kernels`, `fp32_comparison`, `cpu_baseline`.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big_accum|big|big40k|base]
 """

@@ -51,7 +51,7 @@ def pytest_terminal_summary(terminalreporter, exitstatus, config):
         tr.write_line(line)
     try:
         import json
-        out = os.path.join(ROOT, "gpurun_out")
+        out = os.environ.get("NMT_TEST_OUTPUT_DIR") or os.path.join(ROOT, "gpurun_out")
         os.makedirs(out, exist_ok=True)
         with open(os.path.join(out, "parity_summary.json"), "w") as f:
             json.dump(PARITY, f, indent=1)

@@ -5,7 +5,8 @@ import torch
 DEV = "cuda:0"
 
 # Every gradient / weight comparison against the oracle leaves its figures here; tests/conftest.py prints
-# them at the end of the run (also under -q) and writes them to gpurun_out/parity_summary.json.
+# them at the end of the run (also under -q) and writes them to parity_summary.json in the run's output folder
+# (NMT_TEST_OUTPUT_DIR, or the folder tests/conftest.py defaults to).
 PARITY = []
 
 
