@@ -42,16 +42,11 @@ __global__ void __launch_bounds__(kThreads) embed_fwd_kernel(const int32_t* __re
   const float pos = (float)drop_row_pos(drop, (uint32_t)row);
   const float sq = sqrtf((float)d);
   const float k = -logf(10000.f) / (float)d;
-  // The hardware sine and cosine take the angle in revolutions; forming it costs a relative 6e-8 of the angle, i.e.
-  // an absolute 1e-4 at 2048 radians, well under half an fp16 step of the sum.  Positions beyond that (no sentence
-  // of the workloads here comes near) take the library functions, whose argument reduction is exact but costs
-  // more than the memory traffic of the whole kernel.
-  const bool fast = pos <= 2048.f;
 #pragma unroll
   for (int e = 0; e < 8; e += 2) {
     const float ang = pos * expf(k * (float)(c * 8 + e));
-    v[e] = v[e] * sq + (fast ? __sinf(ang) : sinf(ang));
-    v[e + 1] = v[e + 1] * sq + (fast ? __cosf(ang) : cosf(ang));
+    v[e] = v[e] * sq + sinf(ang);
+    v[e + 1] = v[e + 1] * sq + cosf(ang);
   }
   if (drop.thr) {
     const uint32_t bits = drop_keep8(drop, (uint32_t)row, (uint32_t)c);
